@@ -1,0 +1,120 @@
+"""Pins for oracle/gemm.py: the definition C = A . (B (.) mask)."""
+import numpy as np
+import pytest
+
+from oracle import gemm as og
+from tests.helpers import random_tw_mask
+import workloads as wl
+
+
+def _rand16(rng, shape, scale=1.0):
+    return (rng.standard_normal(shape) * scale).astype(np.float16)
+
+
+@pytest.mark.parametrize("M,K,N,seed", [(5, 7, 6, 0), (3, 16, 9, 1), (8, 5, 4, 2)])
+def test_matches_bruteforce_random_mask(M, K, N, seed):
+    rng = np.random.default_rng(seed)
+    A, B = _rand16(rng, (M, K)), _rand16(rng, (K, N))
+    mask = (rng.random((K, N)) < 0.5).astype(np.uint8)
+    ref = og.gemm_bruteforce(A, B, mask)
+    got = og.gemm_oracle(A, B, mask)
+    # fsum is exactly rounded; a K-term fp64 dot product differs by a few ulp
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-13 * max(1.0, np.abs(ref).max()))
+
+
+def test_matches_bruteforce_on_config1_slice():
+    c = wl.make_case(1)
+    rows = np.arange(0, c.M, 37)
+    cols = np.arange(0, c.N, 29)
+    ref = og.gemm_bruteforce(c.A[rows], c.B[:, cols], c.mask[:, cols])
+    got = og.gemm_oracle(c.A, c.B, c.mask)[np.ix_(rows, cols)]
+    np.testing.assert_allclose(got, ref, rtol=0, atol=1e-11)
+
+
+def test_small_integers_are_exact():
+    rng = np.random.default_rng(3)
+    Ai = rng.integers(-8, 9, (11, 13))
+    Bi = rng.integers(-8, 9, (13, 10))
+    mask = (rng.random((13, 10)) < 0.6).astype(np.uint8)
+    want = Ai @ (Bi * mask)                        # int64, exact
+    got = og.gemm_oracle(Ai.astype(np.float16), Bi.astype(np.float16), mask)
+    assert np.array_equal(got, want.astype(np.float64))
+
+
+def test_zero_sparsity_is_dense():
+    rng = np.random.default_rng(4)
+    A, B = _rand16(rng, (9, 12)), _rand16(rng, (12, 7))
+    ones = np.ones((12, 7), np.uint8)
+    dense = og.gemm_bruteforce(A, B, ones)
+    np.testing.assert_allclose(og.gemm_oracle(A, B, ones), dense, rtol=0, atol=1e-13)
+
+
+def test_identity_A_returns_masked_B_exactly():
+    rng = np.random.default_rng(5)
+    K, N = 24, 20
+    B = _rand16(rng, (K, N))
+    mask = random_tw_mask(rng, K, N, 8)
+    C = og.gemm_oracle(np.eye(K, dtype=np.float16), B, mask)
+    assert np.array_equal(C, B.astype(np.float64) * mask)
+
+
+def test_all_ones_counts_kept_elements():
+    rng = np.random.default_rng(6)
+    K, N = 40, 33
+    mask = random_tw_mask(rng, K, N, 8)
+    C = og.gemm_oracle(np.ones((3, K), np.float16), np.ones((K, N), np.float16), mask)
+    assert np.array_equal(C, np.broadcast_to(mask.sum(axis=0).astype(np.float64), (3, N)))
+
+
+def test_pruned_columns_are_exactly_zero_and_pruned_rows_do_not_matter():
+    rng = np.random.default_rng(7)
+    M, K, N, G = 6, 32, 40, 8
+    A, B = _rand16(rng, (M, K)), _rand16(rng, (K, N))
+    mask = random_tw_mask(rng, K, N, G, col_keep=0.7, row_keep=0.4)
+    C = og.gemm_oracle(A, B, mask)
+    dead = ~mask.any(axis=0)
+    assert dead.any()
+    assert not C[:, dead].any()
+    assert not og.abs_bound(A, B, mask)[:, dead].any()
+    # rows pruned in the first tile: changing those A columns leaves that tile alone
+    cols = np.flatnonzero(mask.any(axis=0))[:G]
+    pruned_rows = np.flatnonzero(~mask[:, cols].any(axis=1))
+    assert pruned_rows.size
+    A2 = A.copy()
+    A2[:, pruned_rows] = _rand16(rng, (M, pruned_rows.size), 50.0)
+    C2 = og.gemm_oracle(A2, B, mask)
+    assert np.array_equal(C[:, cols], C2[:, cols])
+
+
+def test_linearity_over_disjoint_masks():
+    # Section III-A (TEW): A.(B1+B2) = A.B1 + A.B2
+    rng = np.random.default_rng(8)
+    A, B = _rand16(rng, (7, 15)), _rand16(rng, (15, 11))
+    m1 = (rng.random((15, 11)) < 0.4).astype(np.uint8)
+    m2 = ((rng.random((15, 11)) < 0.5) & (m1 == 0)).astype(np.uint8)
+    lhs = og.gemm_oracle(A, B, m1) + og.gemm_oracle(A, B, m2)
+    rhs = og.gemm_oracle(A, B, m1 | m2)
+    np.testing.assert_allclose(lhs, rhs, rtol=0, atol=1e-12)
+
+
+def test_abs_bound_dominates_and_matches_bruteforce():
+    rng = np.random.default_rng(9)
+    A, B = _rand16(rng, (4, 9)), _rand16(rng, (9, 5))
+    mask = (rng.random((9, 5)) < 0.5).astype(np.uint8)
+    S = og.abs_bound(A, B, mask)
+    Sb = og.gemm_bruteforce(np.abs(A), np.abs(B), mask)
+    np.testing.assert_allclose(S, Sb, rtol=0, atol=1e-13)
+    assert (np.abs(og.gemm_oracle(A, B, mask)) <= S + 1e-15).all()
+
+
+def test_planted_mistakes_are_caught():
+    """A transposed operand or a dropped mask must fail the brute-force pin."""
+    rng = np.random.default_rng(10)
+    A, B = _rand16(rng, (6, 6)), _rand16(rng, (6, 6))
+    mask = (rng.random((6, 6)) < 0.5).astype(np.uint8)
+    ref = og.gemm_bruteforce(A, B, mask)
+    wrong_T = A.astype(np.float64) @ (B.astype(np.float64) * mask).T
+    wrong_mask_T = A.astype(np.float64) @ (B.astype(np.float64) * mask.T)
+    wrong_nomask = A.astype(np.float64) @ B.astype(np.float64)
+    for w in (wrong_T, wrong_mask_T, wrong_nomask):
+        assert np.abs(w - ref).max() > 1e-3

@@ -1,0 +1,170 @@
+"""Pins for oracle/prune.py and cross-check of the shared input generator."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle import prune as op
+import workloads as wl
+
+
+def _w(seed, K, N):
+    return wl.rng_fp16(seed, (K, N), 1.0)
+
+
+def test_closed_forms():
+    # Algorithm 3: s = 1 - sqrt(1 - s_t);  TVW: s = 1 - 2 (1 - s_t)
+    assert op.tw_split_sparsity(0.75) == pytest.approx(0.5)
+    assert op.tw_split_sparsity(0.0) == 0.0
+    assert (1 - op.tw_split_sparsity(0.9)) ** 2 == pytest.approx(0.1)
+    assert op.tvw_tw_sparsity(0.875) == pytest.approx(0.75)
+    assert op.tvw_tw_sparsity(0.5) == 0.0          # TVW minimum: plain 2:4
+    assert op.n_tiles(768, 128) == 6 and op.n_tiles(692, 128) == 6 and op.n_tiles(129, 128) == 2
+
+
+def test_tw_paper_hits_target_within_one_unit():
+    K, N, G = 64, 96, 16
+    w = _w(1, K, N)
+    m = op.tw_paper(w, 0.75, G)
+    # 50% of columns, then 50% of (tile,row) units
+    assert m.any(axis=0).sum() == N // 2
+    assert m.sum() == (N // 2) * K // 2
+    assert 1 - m.mean() == pytest.approx(0.75)
+
+
+def test_g1_without_column_step_is_elementwise():
+    # Introduction: tile size one makes TW equivalent to EW
+    w = _w(2, 12, 10)
+    s = 0.6
+    m_tw = op.tw(w, 1, s_cols=0.0, s_rows=s)
+    m_ew = op.ew(w, s)
+    assert np.array_equal(m_tw, m_ew)
+    # and EW is "keep the largest magnitudes": a one-liner
+    thr = np.sort((w.astype(np.float64) ** 2).ravel())[int(math.floor(s * w.size))]
+    assert np.array_equal(m_ew, ((w.astype(np.float64) ** 2) >= thr).astype(np.uint8))
+
+
+def test_single_tile_is_global_row_and_column_pruning():
+    # Introduction: tile size = matrix size gives plain row/column pruning
+    K, N = 20, 16
+    w = _w(3, K, N)
+    m = op.tw(w, N, s_cols=0.25, s_rows=0.5)
+    sq = w.astype(np.float64) ** 2
+    cols = np.sort(np.argsort(sq.sum(0), kind="stable")[N // 4:])
+    rows = np.sort(np.argsort(sq[:, cols].sum(1), kind="stable")[K // 2:])
+    want = np.zeros((K, N), np.uint8)
+    want[np.ix_(rows, cols)] = 1
+    assert np.array_equal(m, want)
+
+
+def test_tiles_are_cut_on_kept_columns():
+    # Section III-A TW-C: after column pruning every tile is G wide again
+    K, N, G = 16, 40, 8
+    w = _w(4, K, N)
+    m = op.tw(w, G, n_cols_pruned=10, rows_kept_per_tile=5)
+    cols = np.flatnonzero(m.any(0))
+    assert cols.size == 30
+    for i in range(0, 30, G):
+        tc = cols[i:i + G]
+        sub = m[:, tc]
+        assert (sub.sum(0) == 5).all()
+        assert (sub == sub[:, :1]).all()           # same rows across the tile
+
+
+def test_plain_2_4_when_tw_part_is_zero():
+    # TVW at 50%: TW part 0, every aligned group of 4 along K keeps exactly 2
+    K, N = 32, 24
+    w = _w(5, K, N)
+    m, tm = op.tvw_paper(w, 0.5, 8)
+    assert tm.all()
+    assert (m.reshape(K // 4, 4, N).sum(1) == 2).all()
+    # and they are the two largest magnitudes of each group
+    mag = np.abs(w.astype(np.float64)).reshape(K // 4, 4, N)
+    kept_min = np.where(m.reshape(K // 4, 4, N) == 1, mag, np.inf).min(1)
+    dropped_max = np.where(m.reshape(K // 4, 4, N) == 0, mag, -np.inf).max(1)
+    assert (kept_min >= dropped_max).all()
+
+
+def test_2_4_tie_keeps_lower_position():
+    w = np.array([[1, 1, 1, 1]], np.float16).T.repeat(3, axis=1)    # 4 x 3, all equal
+    m = op.vw24_condensed(w, np.ones((4, 3), np.uint8), 8)
+    assert np.array_equal(m[:, 0], [1, 1, 0, 0])
+
+
+def test_tvw_groups_follow_condensed_rows():
+    K, N, G = 48, 32, 8
+    w = _w(6, K, N)
+    m, tm = op.tvw_paper(w, 0.875, G)
+    assert 1 - tm.mean() == pytest.approx(0.75, abs=0.02)
+    cols = np.flatnonzero(tm.any(0))
+    for i in range(0, cols.size, G):
+        tc = cols[i:i + G]
+        rows = np.flatnonzero(tm[:, tc].any(1))
+        for g in range(0, rows.size - rows.size % 4, 4):
+            assert (m[np.ix_(rows[g:g + 4], tc)].sum(0) == 2).all()
+    assert not (m & ~tm).any()
+
+
+def test_rows_per_tile_rule():
+    # BERT-base 768x768, 10% columns pruned, 75% total: rho = .25*768/692
+    assert op.rows_per_tile(768, 768, 692, 0.25) == 213
+    assert op.rows_per_tile(768, 768, 692, 0.25, 4) == 212
+    assert op.rows_per_tile(256, 256, 256, 0.5) == 128
+    assert op.rows_per_tile(100, 10, 10, 1.0, 4) == 100
+
+
+# ---- the shared generator (workloads) against the oracle's own construction ----
+@pytest.mark.parametrize("K,N,G,sp,cf", [(64, 80, 16, 0.75, 0.1), (40, 50, 8, 0.5, 0.0), (96, 70, 32, 0.9, 0.2)])
+def test_workloads_per_tile_equals_oracle(K, N, G, sp, cf):
+    w = _w(10 + K, K, N)
+    got = wl.tw_mask(w, G, density=1 - sp, col_frac=cf, recipe="per_tile")
+    ncp = int(math.floor(cf * N))
+    want = op.tw(w, G, n_cols_pruned=ncp,
+                 rows_kept_per_tile=op.rows_per_tile(K, N, N - ncp, 1 - sp))
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("K,N,G,sp", [(64, 80, 16, 0.75), (48, 64, 8, 0.5)])
+def test_workloads_paper_recipe_equals_oracle(K, N, G, sp):
+    w = _w(20 + K, K, N)
+    got = wl.tw_mask(w, G, density=1 - sp, col_frac=None, recipe="paper")
+    assert np.array_equal(got, op.tw_paper(w, sp, G))
+
+
+def test_workloads_tvw_equals_oracle():
+    K, N, G, sp, cf = 64, 80, 16, 0.875, 0.1
+    w = _w(30, K, N)
+    m, tm = wl.tvw_mask(w, G, sparsity=sp, col_frac=cf)
+    ncp = int(math.floor(cf * N))
+    tm_o = op.tw(w, G, n_cols_pruned=ncp,
+                 rows_kept_per_tile=op.rows_per_tile(K, N, N - ncp, 2 * (1 - sp), 4))
+    assert np.array_equal(tm, tm_o)
+    assert np.array_equal(m, op.vw24_condensed(w, tm_o, G))
+
+
+def test_config1_recipe():
+    c = wl.make_case(1)
+    assert (c.M, c.K, c.N, c.G) == (128, 256, 256, 64)
+    assert c.mask.any(0).all()                                # no column pruning
+    for t in range(4):
+        sub = c.mask[:, 64 * t:64 * t + 64]
+        assert (sub.sum(0) == 128).all() and (sub == sub[:, :1]).all()
+    want = op.tw(c.B, 64, n_cols_pruned=0, rows_kept_per_tile=128)
+    assert np.array_equal(c.mask, want)
+
+
+def test_config2_structure():
+    c = wl.make_case(2, 0, with_A=False)
+    cols = np.flatnonzero(c.mask.any(0))
+    assert cols.size == 768 - 76
+    assert 1 - c.mask.mean() == pytest.approx(0.75, abs=2e-3)
+    kt = [int(c.mask[:, cols[i:i + 128]].any(1).sum()) for i in range(0, cols.size, 128)]
+    assert kt == [213] * 6
+
+
+def test_global_recipe_gives_uneven_tiles():
+    c = wl.make_case(2, 0, recipe="global", with_A=False)
+    cols = np.flatnonzero(c.mask.any(0))
+    kt = [int(c.mask[:, cols[i:i + 128]].any(1).sum()) for i in range(0, cols.size, 128)]
+    assert len(set(kt)) > 1
+    assert 1 - c.mask.mean() == pytest.approx(0.75, abs=1e-2)
