@@ -1,0 +1,176 @@
+/*
+ * twgemm.h - C ABI of the tile-wise (TW) / tile-vector-wise (TVW) sparse GEMM
+ * library for AMD MI355X (gfx950).
+ *
+ * The operation (paper Section III-A): C = A x B with A (M x K) activations,
+ * B (K x N) a pruned weight and C (M x N).  B is pruned tile-wise: whole
+ * columns are dropped (TW-C), the kept columns are cut into tiles of G, and
+ * every tile drops its own set of K-rows (TW-R).  TVW additionally keeps only
+ * 2 of every 4 consecutive kept rows per column (Section III-A, "TVW";
+ * Algorithm 3).  The library keeps B condensed per tile together with the
+ * indices of the unpruned rows / columns (Section V, "Tile Fusion and
+ * Compressed Tile Offset"; Listing 1's CTO_k / CTO_n) and computes
+ *
+ *      C = A . (B (.) mask)          fp16 inputs, fp32 accumulation, one
+ *                                    round-to-nearest-even to fp16
+ *
+ * in one kernel launch: gather of the kept rows of A, dense (or 2:4 sparse)
+ * matrix-core contraction over the condensed K, scatter to the kept columns
+ * of C.  alpha = 1 and beta = 0 (Listing 1's alpha/beta are not exposed).
+ *
+ * Conventions
+ *  - "host" pointers are ordinary CPU memory, "dev" pointers are device
+ *    memory of the current HIP device.  fp16 values travel as uint16_t bit
+ *    patterns on the host side and as raw 2-byte elements on the device.
+ *  - The caller owns every buffer it passes; tw_pack* copy what they need.
+ *    The library owns everything behind a handle until tw_free.
+ *  - All functions return a tw_status; nothing throws across the boundary.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *    tw_gemm / tw_dense_gemm only enqueue work on it: they never synchronise
+ *    and never allocate.
+ *  - Inputs are assumed finite.
+ */
+#ifndef TWGEMM_H
+#define TWGEMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct tw_handle_s* tw_handle_t; /* opaque packed weight */
+
+typedef enum {
+  TW_OK = 0,
+  TW_ERR_ARG = 1,         /* null pointer, non-positive size, bad enum, misaligned buffer */
+  TW_ERR_MASK = 2,        /* mask does not have the TW / TVW structure                    */
+  TW_ERR_UNSUPPORTED = 3, /* valid request this build has no kernel for                   */
+  TW_ERR_ALLOC = 4,       /* host or device allocation failed                             */
+  TW_ERR_HIP = 5,         /* a HIP runtime call failed (no device, launch error)          */
+  TW_ERR_STATE = 6        /* handle has no device copy yet / already freed                */
+} tw_status;
+
+typedef enum { TW_PATTERN_TW = 0, TW_PATTERN_TVW = 1 } tw_pattern;
+
+/*
+ * Memory layout of A and C.  Section V ("Memory Accesses Coalesce") stores the
+ * tiles transposed so that skipping a K-column of A / an N-column of C becomes
+ * skipping a contiguous row; TW_LAYOUT_KM is that form and the fast path.
+ *   TW_LAYOUT_KM: A is stored K x M (element (i,k) at A[k*lda + i]),
+ *                 C is stored N x M (element (i,n) at C[n*ldc + i]).
+ *   TW_LAYOUT_MK: A is M x K row-major (A[i*lda + k]), C is M x N row-major.
+ */
+typedef enum { TW_LAYOUT_KM = 0, TW_LAYOUT_MK = 1 } tw_layout;
+
+/*
+ * Logical (layout-independent) view of a packed weight; all pointers are host
+ * memory owned by the handle and valid until tw_free.
+ *
+ *   col_idx[n_kept]       ascending original indices of kept columns   (CTO_n as indices)
+ *   cto_n[n_kept]         col_idx[j] - j                                (offset form, Section V)
+ *   tile_k_off[n_tiles+1] prefix sums of K_t, the kept-row count of tile t
+ *   row_idx[sum K_t]      per tile, ascending original K indices        (CTO_k as indices)
+ *   cto_k[sum K_t]        row_idx[tile t][j] - j
+ *   Tile t covers condensed columns [t*G, min((t+1)*G, n_kept)), width W_t.
+ *   TW : values at val_off[t]: K_t x W_t row-major, V[j][w] = B[row_idx[t][j]][col_idx[t*G+w]]
+ *   TVW: groups of 4 consecutive entries of row_idx[t]; n_g = ceil(K_t/4).
+ *        values at val_off[t]: n_g x 2 x W_t; meta/valid at meta_off[t]: n_g x W_t bytes.
+ *        meta  = p0 | p1<<2 with p0 < p1 the two stored positions of the group,
+ *        valid = v0 | v1<<1, v_i = 1 if stored value i is a kept element of the
+ *        mask (else it is a +0 filler).
+ */
+typedef struct {
+  int32_t K, N, G, pattern;
+  int32_t n_kept, n_tiles;
+  const int32_t* col_idx;
+  const int32_t* cto_n;
+  const int32_t* tile_k_off;
+  const int32_t* row_idx;
+  const int32_t* cto_k;
+  const int64_t* val_off;   /* n_tiles+1, in fp16 elements */
+  const uint16_t* values;
+  const int64_t* meta_off;  /* n_tiles+1, in bytes; NULL for TW */
+  const uint8_t* meta;      /* NULL for TW */
+  const uint8_t* valid;     /* NULL for TW */
+} tw_packed_view;
+
+/*
+ * tw_pack_host - condense a pruned weight on the host (Section V: done
+ * "offline before the model inference starts"; Algorithm 3's Condense).
+ *   B_host     K x N row-major fp16 bit patterns (ldb = N)
+ *   mask_host  K x N bytes, non-zero = kept
+ *   tile_mask_host  TVW only, may be NULL: the TW-level mask the 2:4 step was
+ *              applied to.  When NULL the kept rows/columns are the ones with
+ *              any mask bit.  Ignored for TW.
+ *   G          tile width along N: 32, 64 or 128
+ * Errors: TW_ERR_ARG (null / K,N < 1 / bad G or pattern), TW_ERR_MASK (a kept
+ * row of a tile has a hole, the element mask leaves the tile mask, or a 2:4
+ * group keeps more than two), TW_ERR_ALLOC.  Touches no GPU.
+ */
+tw_status tw_pack_host(const uint16_t* B_host, const uint8_t* mask_host,
+                       const uint8_t* tile_mask_host, int K, int N, int G,
+                       int pattern, tw_handle_t* out);
+
+/* tw_upload - copy the device image of a packed weight to the current HIP
+ * device (synchronous).  Idempotent.  Errors: TW_ERR_ARG, TW_ERR_ALLOC, TW_ERR_HIP. */
+tw_status tw_upload(tw_handle_t h);
+
+/* tw_pack - tw_pack_host followed by tw_upload ("tw_pack(B, mask, G, pattern) -> handle"). */
+tw_status tw_pack(const uint16_t* B_host, const uint8_t* mask_host,
+                  const uint8_t* tile_mask_host, int K, int N, int G,
+                  int pattern, tw_handle_t* out);
+
+/*
+ * tw_gemm - C = A . (B (.) mask) for a packed weight (Listing 1 as one grouped
+ * launch; every element of C is written, pruned columns as +0).
+ *   A_dev, C_dev  device fp16; 16-byte aligned; lda, ldc in elements,
+ *                 multiples of 8.  KM: lda >= M, ldc >= M.  MK: lda >= K, ldc >= N.
+ *   M             >= 1
+ * Asynchronous on `stream`; allocates nothing; concurrent calls must use
+ * distinct C.  Errors: TW_ERR_ARG, TW_ERR_STATE (not uploaded),
+ * TW_ERR_UNSUPPORTED (layout without a kernel), TW_ERR_HIP (launch failed).
+ */
+tw_status tw_gemm(const void* A_dev, int M, int lda, int layout, tw_handle_t h,
+                  void* C_dev, int ldc, void* stream);
+
+/*
+ * tw_dense_gemm - the dense baseline C = A . B on the same matrix cores, same
+ * layouts and precision (Section V: the dense tiled GEMM the method starts from).
+ *   B_dev  device fp16, K x N row-major, ldb >= N, multiple of 8, 16-byte aligned.
+ */
+tw_status tw_dense_gemm(const void* A_dev, const void* B_dev, void* C_dev,
+                        int M, int K, int N, int lda, int ldb, int ldc,
+                        int layout, void* stream);
+
+/* tw_export - fill *out with the logical view (host pointers owned by h). */
+tw_status tw_export(tw_handle_t h, tw_packed_view* out);
+
+/* tw_unpack - inverse of packing: writes B (.) mask (fp16 bits, pruned = +0)
+ * and the mask (0/1), both K x N row-major host buffers; either may be NULL. */
+tw_status tw_unpack(tw_handle_t h, uint16_t* B_masked_host, uint8_t* mask_host);
+
+/* tw_free - release host and device memory of a handle (NULL is a no-op). */
+tw_status tw_free(tw_handle_t h);
+
+/* tw_status_str - static string for a status code. */
+const char* tw_status_str(int status);
+
+/*
+ * Tuning / introspection (not needed for correct use).
+ * tw_set_option: process-wide integer knobs read at the next tw_gemm /
+ * tw_dense_gemm call.  Unknown names give TW_ERR_ARG.
+ *   "tile_m"   0 = heuristic, else force the M-tile (64, 128 or 256)
+ *   "xcd_map"  1 (default) = remap workgroup ids so that one XCD walks all
+ *              N-tiles of an M-band; 0 = plain order
+ * tw_flop_counts: condensed multiply-add work of a handle:
+ *   *sum_kw = sum over tiles of K_t * W_t (kept-row x width products).
+ */
+tw_status tw_set_option(const char* name, int value);
+tw_status tw_flop_counts(tw_handle_t h, int64_t* sum_kw, int64_t* sum_k);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TWGEMM_H */

@@ -1,0 +1,195 @@
+"""ctypes binding with the same names as the C ABI.  Argument marshalling only:
+every step of the path runs inside libtwgemm.so.  The library is loaded from
+the package directory and is never built here; a missing library is an error
+(there is no fallback path)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+PATTERN_TW, PATTERN_TVW = 0, 1
+LAYOUT_KM, LAYOUT_MK = 0, 1
+
+EXPORTED_SYMBOLS = [
+    "tw_pack_host", "tw_upload", "tw_pack", "tw_gemm", "tw_dense_gemm", "tw_export",
+    "tw_unpack", "tw_free", "tw_status_str", "tw_set_option", "tw_flop_counts",
+]
+
+_lib = None
+
+
+class TwError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: {lib().tw_status_str(status).decode()} (status {status})")
+
+
+class _View(C.Structure):
+    _fields_ = [("K", C.c_int32), ("N", C.c_int32), ("G", C.c_int32), ("pattern", C.c_int32),
+                ("n_kept", C.c_int32), ("n_tiles", C.c_int32),
+                ("col_idx", C.POINTER(C.c_int32)), ("cto_n", C.POINTER(C.c_int32)),
+                ("tile_k_off", C.POINTER(C.c_int32)), ("row_idx", C.POINTER(C.c_int32)),
+                ("cto_k", C.POINTER(C.c_int32)), ("val_off", C.POINTER(C.c_int64)),
+                ("values", C.POINTER(C.c_uint16)), ("meta_off", C.POINTER(C.c_int64)),
+                ("meta", C.POINTER(C.c_uint8)), ("valid", C.POINTER(C.c_uint8))]
+
+
+def lib_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtwgemm.so")
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        p = lib_path()
+        if not os.path.exists(p):
+            raise ImportError(f"{p} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+        L = C.CDLL(p)
+        vp, i = C.c_void_p, C.c_int
+        L.tw_status_str.restype = C.c_char_p
+        L.tw_status_str.argtypes = [i]
+        L.tw_pack_host.argtypes = [vp, vp, vp, i, i, i, i, C.POINTER(vp)]
+        L.tw_pack.argtypes = L.tw_pack_host.argtypes
+        L.tw_upload.argtypes = [vp]
+        L.tw_gemm.argtypes = [vp, i, i, i, vp, vp, i, vp]
+        L.tw_dense_gemm.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, vp]
+        L.tw_export.argtypes = [vp, C.POINTER(_View)]
+        L.tw_unpack.argtypes = [vp, vp, vp]
+        L.tw_free.argtypes = [vp]
+        L.tw_set_option.argtypes = [C.c_char_p, i]
+        L.tw_flop_counts.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+        for name in EXPORTED_SYMBOLS:
+            if name != "tw_status_str":
+                getattr(L, name).restype = i
+        _lib = L
+    return _lib
+
+
+def _check(st: int, what: str):
+    if st != 0:
+        raise TwError(st, what)
+
+
+def _host_ptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+class PackedWeight:
+    """Owner of a tw_handle_t."""
+
+    def __init__(self, handle: C.c_void_p):
+        self._h = handle
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("handle already freed")
+        return self._h
+
+    def upload(self):
+        _check(lib().tw_upload(self.handle), "tw_upload")
+        return self
+
+    def export(self) -> dict:
+        """tw_export as numpy copies, in the layout of the logical packed form."""
+        v = _View()
+        _check(lib().tw_export(self.handle, C.byref(v)), "tw_export")
+        nt, nk = v.n_tiles, v.n_kept
+
+        def arr(ptr, n, dt):
+            if n == 0 or not ptr:
+                return np.zeros(0, dt)
+            return np.ctypeslib.as_array(ptr, shape=(n,)).astype(dt, copy=True)
+
+        tko = arr(v.tile_k_off, nt + 1, np.int32) if nt >= 0 else np.zeros(1, np.int32)
+        sk = int(tko[-1]) if tko.size else 0
+        rows = arr(v.row_idx, sk, np.int32)
+        ctok = arr(v.cto_k, sk, np.int32)
+        voff = arr(v.val_off, nt + 1, np.int64)
+        vals = arr(v.values, int(voff[-1]) if voff.size else 0, np.uint16)
+        out = dict(K=v.K, N=v.N, G=v.G, pattern=v.pattern, n_kept=nk, n_tiles=nt,
+                   col_idx=arr(v.col_idx, nk, np.int32), cto_n=arr(v.cto_n, nk, np.int32),
+                   row_idx=[rows[tko[t]:tko[t + 1]] for t in range(nt)],
+                   cto_k=[ctok[tko[t]:tko[t + 1]] for t in range(nt)])
+        widths = [min(v.G, nk - t * v.G) for t in range(nt)]
+        if v.pattern == PATTERN_TW:
+            out["values"] = [vals[voff[t]:voff[t + 1]].reshape(int(tko[t + 1] - tko[t]), widths[t])
+                             for t in range(nt)]
+        else:
+            moff = arr(v.meta_off, nt + 1, np.int64)
+            meta = arr(v.meta, int(moff[-1]) if moff.size else 0, np.uint8)
+            valid = arr(v.valid, int(moff[-1]) if moff.size else 0, np.uint8)
+            ng = [(int(tko[t + 1] - tko[t]) + 3) // 4 for t in range(nt)]
+            out["values"] = [vals[voff[t]:voff[t + 1]].reshape(ng[t], 2, widths[t]) for t in range(nt)]
+            out["meta"] = [meta[moff[t]:moff[t + 1]].reshape(ng[t], widths[t]) for t in range(nt)]
+            out["valid"] = [valid[moff[t]:moff[t + 1]].reshape(ng[t], widths[t]) for t in range(nt)]
+        return out
+
+    def unpack(self):
+        v = _View()
+        _check(lib().tw_export(self.handle, C.byref(v)), "tw_export")
+        Bm = np.empty((v.K, v.N), np.uint16)
+        mask = np.empty((v.K, v.N), np.uint8)
+        _check(lib().tw_unpack(self.handle, _host_ptr(Bm), _host_ptr(mask)), "tw_unpack")
+        return Bm, mask
+
+    def flop_counts(self):
+        a, b = C.c_int64(), C.c_int64()
+        _check(lib().tw_flop_counts(self.handle, C.byref(a), C.byref(b)), "tw_flop_counts")
+        return a.value, b.value
+
+    def free(self):
+        if self._h is not None:
+            h, self._h = self._h, None
+            _check(lib().tw_free(h), "tw_free")
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def _pack(fn_name, B16, mask, G, pattern, tile_mask):
+    B16 = np.ascontiguousarray(B16)
+    if B16.dtype != np.float16 and B16.dtype != np.uint16:
+        raise TypeError("B must be fp16 (or its uint16 bit patterns)")
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    if mask.shape != B16.shape or B16.ndim != 2:
+        raise ValueError("B and mask must be K x N")
+    if tile_mask is not None:
+        tile_mask = np.ascontiguousarray(tile_mask, dtype=np.uint8)
+        if tile_mask.shape != B16.shape:
+            raise ValueError("tile_mask must be K x N")
+    K, N = B16.shape
+    h = C.c_void_p()
+    st = getattr(lib(), fn_name)(_host_ptr(B16), _host_ptr(mask), _host_ptr(tile_mask),
+                                 K, N, int(G), int(pattern), C.byref(h))
+    _check(st, fn_name)
+    return PackedWeight(h)
+
+
+def tw_pack_host(B16, mask, G, pattern, tile_mask=None) -> PackedWeight:
+    return _pack("tw_pack_host", B16, mask, G, pattern, tile_mask)
+
+
+def tw_pack(B16, mask, G, pattern, tile_mask=None) -> PackedWeight:
+    return _pack("tw_pack", B16, mask, G, pattern, tile_mask)
+
+
+def tw_gemm(A_ptr: int, M: int, lda: int, layout: int, packed: PackedWeight, C_ptr: int,
+            ldc: int, stream: int = 0):
+    """A_ptr / C_ptr: device addresses (e.g. torch.Tensor.data_ptr()), stream: hipStream_t."""
+    _check(lib().tw_gemm(A_ptr, M, lda, layout, packed.handle, C_ptr, ldc, stream), "tw_gemm")
+
+
+def tw_dense_gemm(A_ptr: int, B_ptr: int, C_ptr: int, M: int, K: int, N: int, lda: int,
+                  ldb: int, ldc: int, layout: int, stream: int = 0):
+    _check(lib().tw_dense_gemm(A_ptr, B_ptr, C_ptr, M, K, N, lda, ldb, ldc, layout, stream),
+           "tw_dense_gemm")
+
+
+def tw_set_option(name: str, value: int):
+    _check(lib().tw_set_option(name.encode(), int(value)), "tw_set_option")

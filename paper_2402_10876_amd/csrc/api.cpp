@@ -1,0 +1,205 @@
+// C ABI of the library (see include/twgemm.h): argument checks, upload of the
+// packed image, kernel selection.  No torch types, no exceptions across.
+#include <hip/hip_runtime_api.h>
+
+#include <atomic>
+#include <cstring>
+#include <new>
+
+#include "kernels.h"
+#include "packed.h"
+
+namespace {
+
+std::atomic<int> opt_tile_m{0};
+std::atomic<int> opt_xcd_map{1};
+
+bool valid_G(int G) { return G == 32 || G == 64 || G == 128; }
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// M-tile heuristic: the largest tile that still gives every CU (256 of them)
+// about two workgroups; small problems fall back to smaller tiles.
+int pick_tile_m(int M, int n_tiles, int G) {
+  const int forced = opt_tile_m.load();
+  if (forced == 64 || forced == 128 || forced == 256) {
+    if (!(G == 32 && forced == 64)) return forced;
+  }
+  const int cand[3] = {256, 128, 64};
+  for (int tm : cand) {
+    if (G == 32 && tm == 64) break;
+    const long wgs = (long)((M + tm - 1) / tm) * n_tiles;
+    if (wgs >= 512) return tm;
+  }
+  return G == 32 ? 128 : 64;
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+extern "C" {
+
+const char* tw_status_str(int s) {
+  switch (s) {
+    case TW_OK: return "ok";
+    case TW_ERR_ARG: return "invalid argument";
+    case TW_ERR_MASK: return "mask is not TW/TVW conformant";
+    case TW_ERR_UNSUPPORTED: return "unsupported configuration";
+    case TW_ERR_ALLOC: return "allocation failed";
+    case TW_ERR_HIP: return "HIP runtime error";
+    case TW_ERR_STATE: return "handle not uploaded";
+    default: return "unknown status";
+  }
+}
+
+tw_status tw_pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_mask, int K,
+                       int N, int G, int pattern, tw_handle_t* out) {
+  if (!out) return TW_ERR_ARG;
+  *out = nullptr;
+  if (!B || !mask || K < 1 || N < 1 || !valid_G(G)) return TW_ERR_ARG;
+  if (pattern != TW_PATTERN_TW && pattern != TW_PATTERN_TVW) return TW_ERR_ARG;
+  tw_handle_s* h = new (std::nothrow) tw_handle_s();
+  if (!h) return TW_ERR_ALLOC;
+  tw_status st = twg::pack_host(B, mask, tile_mask, K, N, G, pattern, h);
+  if (st != TW_OK) { delete h; return st; }
+  *out = h;
+  return TW_OK;
+}
+
+tw_status tw_upload(tw_handle_t h) {
+  if (!h) return TW_ERR_ARG;
+  twg::DeviceImage& d = h->img;
+  if (d.blob) return TW_OK;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return TW_ERR_HIP;
+  // one allocation, 256-byte aligned parts
+  struct Part { const void* src; size_t bytes; size_t off; };
+  Part parts[7] = {
+      {d.col_idx.data(), d.col_idx.size() * 4, 0},   {d.tile_kp_off.data(), d.tile_kp_off.size() * 4, 0},
+      {d.row_idx.data(), d.row_idx.size() * 4, 0},   {d.zero_cols.data(), d.zero_cols.size() * 4, 0},
+      {d.tile_order.data(), d.tile_order.size() * 4, 0}, {d.vals.data(), d.vals.size() * 2, 0},
+      {d.meta.data(), d.meta.size() * 4, 0}};
+  size_t total = 0;
+  for (auto& p : parts) { p.off = total; total += align_up(p.bytes ? p.bytes : 1, 256); }
+  void* blob = nullptr;
+  if (hipMalloc(&blob, total) != hipSuccess) { (void)hipGetLastError(); return TW_ERR_ALLOC; }
+  for (auto& p : parts) {
+    if (!p.bytes) continue;
+    if (hipMemcpy((char*)blob + p.off, p.src, p.bytes, hipMemcpyHostToDevice) != hipSuccess) {
+      (void)hipFree(blob);
+      return TW_ERR_HIP;
+    }
+  }
+  char* b = (char*)blob;
+  d.d_col_idx = (const int32_t*)(b + parts[0].off);
+  d.d_tile_kp_off = (const int32_t*)(b + parts[1].off);
+  d.d_row_idx = (const int32_t*)(b + parts[2].off);
+  d.d_zero_cols = (const int32_t*)(b + parts[3].off);
+  d.d_tile_order = (const int32_t*)(b + parts[4].off);
+  d.d_vals = (const uint16_t*)(b + parts[5].off);
+  d.d_meta = (const uint32_t*)(b + parts[6].off);
+  d.blob = blob; d.blob_bytes = total; d.device = dev;
+  return TW_OK;
+}
+
+tw_status tw_pack(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_mask, int K, int N,
+                  int G, int pattern, tw_handle_t* out) {
+  tw_status st = tw_pack_host(B, mask, tile_mask, K, N, G, pattern, out);
+  if (st != TW_OK) return st;
+  st = tw_upload(*out);
+  if (st != TW_OK) { tw_free(*out); *out = nullptr; }
+  return st;
+}
+
+tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void* C, int ldc,
+                  void* stream) {
+  if (!A || !C || !h || M < 1) return TW_ERR_ARG;
+  if (layout != TW_LAYOUT_KM && layout != TW_LAYOUT_MK) return TW_ERR_ARG;
+  if (!aligned16(A) || !aligned16(C) || lda % 8 || ldc % 8) return TW_ERR_ARG;
+  if (!h->img.blob) return TW_ERR_STATE;
+  if (layout == TW_LAYOUT_MK) {
+    if (lda < h->K || ldc < h->N) return TW_ERR_ARG;
+    return TW_ERR_UNSUPPORTED;
+  }
+  if (lda < M || ldc < M) return TW_ERR_ARG;
+  if (h->pattern == TW_PATTERN_TVW) return TW_ERR_UNSUPPORTED;
+  twg::GemmArgs g{};
+  g.A = (const _Float16*)A; g.C = (_Float16*)C; g.M = M; g.lda = lda; g.ldc = ldc;
+  g.vals = (const _Float16*)h->img.d_vals;
+  g.row_idx = h->img.d_row_idx; g.tile_kp_off = h->img.d_tile_kp_off;
+  g.col_idx = h->img.d_col_idx; g.tile_order = h->img.d_tile_order;
+  g.zero_cols = h->img.d_zero_cols; g.n_zero = (int)h->img.zero_cols.size();
+  g.meta = h->img.d_meta;
+  g.n_tiles = h->n_tiles; g.K = h->K; g.N = h->N; g.xcd_map = opt_xcd_map.load();
+  const int tm = pick_tile_m(M, h->n_tiles > 0 ? h->n_tiles : 1, h->G);
+  hipError_t e = twg::launch_tw_km(h->G, tm, g, (hipStream_t)stream);
+  if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
+  return e == hipSuccess ? TW_OK : TW_ERR_HIP;
+}
+
+tw_status tw_dense_gemm(const void* A, const void* B, void* C, int M, int K, int N, int lda,
+                        int ldb, int ldc, int layout, void* stream) {
+  if (!A || !B || !C || M < 1 || K < 1 || N < 1) return TW_ERR_ARG;
+  if (layout != TW_LAYOUT_KM && layout != TW_LAYOUT_MK) return TW_ERR_ARG;
+  if (!aligned16(A) || !aligned16(B) || !aligned16(C) || lda % 8 || ldb % 8 || ldc % 8)
+    return TW_ERR_ARG;
+  if (ldb < N) return TW_ERR_ARG;
+  if (layout == TW_LAYOUT_MK) {
+    if (lda < K || ldc < N) return TW_ERR_ARG;
+    return TW_ERR_UNSUPPORTED;
+  }
+  if (lda < M || ldc < M) return TW_ERR_ARG;
+  twg::GemmArgs g{};
+  g.A = (const _Float16*)A; g.C = (_Float16*)C; g.M = M; g.lda = lda; g.ldc = ldc;
+  g.vals = (const _Float16*)B; g.ldb = ldb; g.K = K; g.N = N;
+  const int tn = 128;
+  g.n_tiles = (N + tn - 1) / tn;
+  g.xcd_map = opt_xcd_map.load();
+  const int tm = pick_tile_m(M, g.n_tiles, tn);
+  hipError_t e = twg::launch_dense_km(tn, tm, g, (hipStream_t)stream);
+  if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
+  return e == hipSuccess ? TW_OK : TW_ERR_HIP;
+}
+
+tw_status tw_export(tw_handle_t h, tw_packed_view* out) {
+  if (!h || !out) return TW_ERR_ARG;
+  std::memset(out, 0, sizeof(*out));
+  out->K = h->K; out->N = h->N; out->G = h->G; out->pattern = h->pattern;
+  out->n_kept = h->n_kept; out->n_tiles = h->n_tiles;
+  out->col_idx = h->col_idx.data(); out->cto_n = h->cto_n.data();
+  out->tile_k_off = h->tile_k_off.data(); out->row_idx = h->row_idx.data();
+  out->cto_k = h->cto_k.data(); out->val_off = h->val_off.data(); out->values = h->values.data();
+  if (h->pattern == TW_PATTERN_TVW) {
+    out->meta_off = h->meta_off.data(); out->meta = h->meta.data(); out->valid = h->valid.data();
+  }
+  return TW_OK;
+}
+
+tw_status tw_unpack(tw_handle_t h, uint16_t* Bm, uint8_t* mask) {
+  if (!h) return TW_ERR_ARG;
+  return twg::unpack_host(h, Bm, mask);
+}
+
+tw_status tw_free(tw_handle_t h) {
+  if (!h) return TW_OK;
+  tw_status st = TW_OK;
+  if (h->img.blob && hipFree(h->img.blob) != hipSuccess) st = TW_ERR_HIP;
+  delete h;
+  return st;
+}
+
+tw_status tw_set_option(const char* name, int value) {
+  if (!name) return TW_ERR_ARG;
+  if (!std::strcmp(name, "tile_m")) { opt_tile_m.store(value); return TW_OK; }
+  if (!std::strcmp(name, "xcd_map")) { opt_xcd_map.store(value != 0); return TW_OK; }
+  return TW_ERR_ARG;
+}
+
+tw_status tw_flop_counts(tw_handle_t h, int64_t* sum_kw, int64_t* sum_k) {
+  if (!h) return TW_ERR_ARG;
+  if (sum_kw) *sum_kw = h->sum_kw;
+  if (sum_k) *sum_k = h->sum_k;
+  return TW_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,32 @@
+// Internal: kernel argument block and launchers (host side sees only this).
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+
+namespace twg {
+
+struct GemmArgs {
+  const _Float16* A;   // K x M, element (i,k) at A[k*lda + i]
+  _Float16* C;         // N x M, element (i,n) at C[n*ldc + i]
+  int M, lda, ldc;
+  // TW: condensed weight image [sum Kp_t][G]; dense: B, K x N row-major
+  const _Float16* vals;
+  int ldb;                       // dense only
+  const int32_t* row_idx;        // TW: padded kept-row lists (CTO_k as indices)
+  const int32_t* tile_kp_off;    // TW: n_tiles+1 offsets into row_idx
+  const int32_t* col_idx;        // TW: n_tiles*G kept-column indices, -1 = none (CTO_n)
+  const int32_t* tile_order;     // TW: launch order of tiles (longest first) or null
+  const int32_t* zero_cols;      // pruned columns of C, written as +0
+  const uint32_t* meta;          // TVW: 2:4 position words
+  int n_zero;
+  int n_tiles, n_mtiles;
+  int K, N;                      // dense only
+  int xcd_map;
+};
+
+// G / tn: tile width (32, 64, 128); tm: M-tile (64, 128, 256).
+// hipErrorInvalidValue when no instance exists for (G, tm).
+hipError_t launch_tw_km(int G, int tm, GemmArgs g, hipStream_t stream);
+hipError_t launch_dense_km(int tn, int tm, GemmArgs g, hipStream_t stream);
+
+}  // namespace twg

@@ -1,0 +1,294 @@
+// Host packer: pruned weight + mask -> condensed per-tile blocks, kept-row and
+// kept-column index lists, compressed tile offsets and 2:4 positions.
+//
+// Paper: Section V removes the pruned rows and columns of every B tile offline
+// and replaces the tile masks by the indices of the unpruned rows / columns
+// ("Tile Fusion and Compressed Tile Offset"); Algorithm 3 condenses the kept
+// columns before cutting tiles of G.  Integer work only; results are unique
+// and compared bit for bit in the tests.
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "packed.h"
+
+namespace twg {
+
+namespace {
+
+// kept-column list and per-tile kept-row lists of a structure mask S (K x N).
+void structure_of(const uint8_t* S, int K, int N, int G, std::vector<int32_t>& cols,
+                  std::vector<int32_t>& tile_k_off, std::vector<int32_t>& rows) {
+  std::vector<uint8_t> col_any(N, 0);
+  for (int k = 0; k < K; ++k) {
+    const uint8_t* r = S + (size_t)k * N;
+    for (int n = 0; n < N; ++n) col_any[n] |= (r[n] != 0);
+  }
+  cols.clear();
+  for (int n = 0; n < N; ++n)
+    if (col_any[n]) cols.push_back(n);
+  const int n_kept = (int)cols.size();
+  const int n_tiles = (n_kept + G - 1) / G;
+  // tile id of every original column (-1 = pruned)
+  std::vector<int32_t> tile_of(N, -1);
+  for (int j = 0; j < n_kept; ++j) tile_of[cols[j]] = j / G;
+  // row_any[t][k]
+  std::vector<uint8_t> row_any((size_t)n_tiles * K, 0);
+  for (int k = 0; k < K; ++k) {
+    const uint8_t* r = S + (size_t)k * N;
+    for (int j = 0; j < n_kept; ++j)
+      if (r[cols[j]]) row_any[(size_t)(j / G) * K + k] = 1;
+  }
+  tile_k_off.assign(n_tiles + 1, 0);
+  rows.clear();
+  for (int t = 0; t < n_tiles; ++t) {
+    for (int k = 0; k < K; ++k)
+      if (row_any[(size_t)t * K + k]) rows.push_back(k);
+    tile_k_off[t + 1] = (int32_t)rows.size();
+  }
+}
+
+// true when S is exactly the union of (rows of tile t) x (columns of tile t)
+bool is_tile_wise(const uint8_t* S, int K, int N, int G, const std::vector<int32_t>& cols,
+                  const std::vector<int32_t>& tile_k_off) {
+  // S is contained in that union by construction, so equality <=> equal counts
+  int64_t nnz = 0;
+  for (size_t i = 0, e = (size_t)K * N; i < e; ++i) nnz += (S[i] != 0);
+  int64_t want = 0;
+  const int n_kept = (int)cols.size();
+  for (size_t t = 0; t + 1 < tile_k_off.size(); ++t) {
+    int w = std::min(G, n_kept - (int)t * G);
+    want += (int64_t)(tile_k_off[t + 1] - tile_k_off[t]) * w;
+  }
+  return nnz == want;
+}
+
+}  // namespace
+
+tw_status pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_mask, int K,
+                    int N, int G, int pattern, tw_handle_s* h) try {
+  h->K = K; h->N = N; h->G = G; h->pattern = pattern;
+  const bool tvw = pattern == TW_PATTERN_TVW;
+  const uint8_t* S = (tvw && tile_mask) ? tile_mask : mask;
+  structure_of(S, K, N, G, h->col_idx, h->tile_k_off, h->row_idx);
+  h->n_kept = (int32_t)h->col_idx.size();
+  h->n_tiles = (int32_t)h->tile_k_off.size() - 1;
+  if (!tvw || tile_mask) {
+    if (!is_tile_wise(S, K, N, G, h->col_idx, h->tile_k_off)) return TW_ERR_MASK;
+  }
+  if (tvw && tile_mask) {
+    for (size_t i = 0, e = (size_t)K * N; i < e; ++i)
+      if (mask[i] && !tile_mask[i]) return TW_ERR_MASK;
+  }
+  h->cto_n.resize(h->n_kept);
+  for (int j = 0; j < h->n_kept; ++j) h->cto_n[j] = h->col_idx[j] - j;
+  h->cto_k.resize(h->row_idx.size());
+  h->val_off.assign(h->n_tiles + 1, 0);
+  h->meta_off.assign(h->n_tiles + 1, 0);
+  h->sum_kw = 0; h->sum_k = 0;
+  for (int t = 0; t < h->n_tiles; ++t) {
+    const int k0 = h->tile_k_off[t], kt = h->tile_k_off[t + 1] - k0;
+    const int w = std::min(G, h->n_kept - t * G);
+    for (int j = 0; j < kt; ++j) h->cto_k[k0 + j] = h->row_idx[k0 + j] - j;
+    h->sum_kw += (int64_t)kt * w;
+    h->sum_k += kt;
+    if (!tvw) {
+      h->val_off[t + 1] = h->val_off[t] + (int64_t)kt * w;
+    } else {
+      const int ng = (kt + 3) / 4;
+      h->val_off[t + 1] = h->val_off[t] + (int64_t)ng * 2 * w;
+      h->meta_off[t + 1] = h->meta_off[t] + (int64_t)ng * w;
+    }
+  }
+  h->values.assign((size_t)h->val_off[h->n_tiles], 0);
+  if (!tvw) {
+    for (int t = 0; t < h->n_tiles; ++t) {
+      const int k0 = h->tile_k_off[t], kt = h->tile_k_off[t + 1] - k0;
+      const int w = std::min(G, h->n_kept - t * G);
+      uint16_t* v = h->values.data() + h->val_off[t];
+      const int32_t* cols = h->col_idx.data() + (size_t)t * G;
+      for (int j = 0; j < kt; ++j) {
+        const uint16_t* brow = B + (size_t)h->row_idx[k0 + j] * N;
+        for (int c = 0; c < w; ++c) v[(size_t)j * w + c] = brow[cols[c]];
+      }
+    }
+  } else {
+    h->meta.assign((size_t)h->meta_off[h->n_tiles], 0);
+    h->valid.assign((size_t)h->meta_off[h->n_tiles], 0);
+    for (int t = 0; t < h->n_tiles; ++t) {
+      const int k0 = h->tile_k_off[t], kt = h->tile_k_off[t + 1] - k0;
+      const int w = std::min(G, h->n_kept - t * G);
+      const int ng = (kt + 3) / 4;
+      uint16_t* v = h->values.data() + h->val_off[t];
+      uint8_t* me = h->meta.data() + h->meta_off[t];
+      uint8_t* va = h->valid.data() + h->meta_off[t];
+      const int32_t* cols = h->col_idx.data() + (size_t)t * G;
+      for (int g = 0; g < ng; ++g) {
+        const int glen = std::min(4, kt - 4 * g);
+        for (int c = 0; c < w; ++c) {
+          const int n = cols[c];
+          int setbits = 0, nset = 0;
+          for (int p = 0; p < glen; ++p)
+            if (mask[(size_t)h->row_idx[k0 + 4 * g + p] * N + n]) { setbits |= 1 << p; ++nset; }
+          if (nset > 2) return TW_ERR_MASK;
+          int chosen = setbits;  // top up with the lowest unset positions
+          for (int p = 0; p < 4 && nset < 2; ++p)
+            if (!(chosen >> p & 1)) { chosen |= 1 << p; ++nset; }
+          int pos[2], i = 0;
+          for (int p = 0; p < 4; ++p)
+            if (chosen >> p & 1) pos[i++] = p;
+          me[(size_t)g * w + c] = (uint8_t)(pos[0] | pos[1] << 2);
+          uint8_t vb = 0;
+          for (i = 0; i < 2; ++i) {
+            if (setbits >> pos[i] & 1) {
+              vb |= (uint8_t)(1 << i);
+              v[((size_t)g * 2 + i) * w + c] = B[(size_t)h->row_idx[k0 + 4 * g + pos[i]] * N + n];
+            }
+          }
+          va[(size_t)g * w + c] = vb;
+        }
+      }
+    }
+  }
+  build_device_image(h);
+  return TW_OK;
+} catch (const std::bad_alloc&) {
+  return TW_ERR_ALLOC;
+}
+
+tw_status unpack_host(const tw_handle_s* h, uint16_t* Bm, uint8_t* mask) {
+  const size_t total = (size_t)h->K * h->N;
+  if (Bm) std::memset(Bm, 0, total * sizeof(uint16_t));
+  if (mask) std::memset(mask, 0, total);
+  for (int t = 0; t < h->n_tiles; ++t) {
+    const int k0 = h->tile_k_off[t], kt = h->tile_k_off[t + 1] - k0;
+    const int w = std::min(h->G, h->n_kept - t * h->G);
+    const uint16_t* v = h->values.data() + h->val_off[t];
+    const int32_t* cols = h->col_idx.data() + (size_t)t * h->G;
+    if (h->pattern == TW_PATTERN_TW) {
+      for (int j = 0; j < kt; ++j) {
+        const size_t row = (size_t)h->row_idx[k0 + j] * h->N;
+        for (int c = 0; c < w; ++c) {
+          if (Bm) Bm[row + cols[c]] = v[(size_t)j * w + c];
+          if (mask) mask[row + cols[c]] = 1;
+        }
+      }
+    } else {
+      const uint8_t* me = h->meta.data() + h->meta_off[t];
+      const uint8_t* va = h->valid.data() + h->meta_off[t];
+      const int ng = (kt + 3) / 4;
+      for (int g = 0; g < ng; ++g)
+        for (int c = 0; c < w; ++c)
+          for (int i = 0; i < 2; ++i) {
+            if (!(va[(size_t)g * w + c] >> i & 1)) continue;
+            const int p = me[(size_t)g * w + c] >> (2 * i) & 3;
+            const size_t at = (size_t)h->row_idx[k0 + 4 * g + p] * h->N + cols[c];
+            if (Bm) Bm[at] = v[((size_t)g * 2 + i) * w + c];
+            if (mask) mask[at] = 1;
+          }
+    }
+  }
+  return TW_OK;
+}
+
+// ---------------------------------------------------------------------------
+// Device image.
+//
+// TW : per tile, Kp_t = K_t rounded up to KSTEP_TW rows of G halves, row-major,
+//      zero filled (rows past K_t and columns past W_t).
+// TVW: per tile, Kp_t = K_t rounded up to KSTEP_TVW.  The compressed tile is
+//      stored in the register order of v_smfmac_f32_32x32x32_f16's sparse
+//      operand: for K-stage s (64 rows), half u (32 rows), column block nb
+//      (32 columns) and lane l:  column w = 32 nb + l%32, the 16 condensed rows
+//      64 s + 32 u + 16 (l/32) .. +15, i.e. four groups of 4; element 2j+i is
+//      stored value i of the lane's group j.  A lane's 8 halves are contiguous
+//      (one 16-byte load), a wave's 64 lanes are contiguous (1 KiB).
+//      Position words: one u32 per (s, nb, lane); bits [16u+4j+3 : 16u+4j] =
+//      meta nibble of the lane's group j in half u (the instruction takes the
+//      16-bit half selected by its ABID field, 2 bits per stored element).
+// ---------------------------------------------------------------------------
+void build_device_image(tw_handle_s* h) {
+  DeviceImage& d = h->img;
+  const int G = h->G, nt = h->n_tiles;
+  const bool tvw = h->pattern == TW_PATTERN_TVW;
+  const int kstep = tvw ? KSTEP_TVW : KSTEP_TW;
+  d.col_idx.assign((size_t)nt * G, -1);
+  std::copy(h->col_idx.begin(), h->col_idx.end(), d.col_idx.begin());
+  d.tile_kp_off.assign(nt + 1, 0);
+  h->max_kp = 0;
+  for (int t = 0; t < nt; ++t) {
+    const int kt = h->tile_k_off[t + 1] - h->tile_k_off[t];
+    const int kp = (kt + kstep - 1) / kstep * kstep;
+    d.tile_kp_off[t + 1] = d.tile_kp_off[t] + kp;
+    h->max_kp = std::max(h->max_kp, kp);
+  }
+  d.row_idx.assign((size_t)d.tile_kp_off[nt], 0);
+  for (int t = 0; t < nt; ++t) {
+    const int k0 = h->tile_k_off[t], kt = h->tile_k_off[t + 1] - k0;
+    const int kp0 = d.tile_kp_off[t], kp = d.tile_kp_off[t + 1] - kp0;
+    for (int j = 0; j < kp; ++j)
+      d.row_idx[kp0 + j] = kt ? h->row_idx[k0 + std::min(j, kt - 1)] : 0;
+  }
+  d.zero_cols.clear();
+  {
+    size_t j = 0;
+    for (int n = 0; n < h->N; ++n) {
+      if (j < h->col_idx.size() && h->col_idx[j] == n) { ++j; continue; }
+      d.zero_cols.push_back(n);
+    }
+  }
+  d.tile_order.resize(nt);
+  for (int t = 0; t < nt; ++t) d.tile_order[t] = t;
+  std::stable_sort(d.tile_order.begin(), d.tile_order.end(), [&](int a, int b) {
+    return h->tile_k_off[a + 1] - h->tile_k_off[a] > h->tile_k_off[b + 1] - h->tile_k_off[b];
+  });
+  if (!tvw) {
+    d.vals.assign((size_t)d.tile_kp_off[nt] * G, 0);
+    for (int t = 0; t < nt; ++t) {
+      const int kt = h->tile_k_off[t + 1] - h->tile_k_off[t];
+      const int w = std::min(G, h->n_kept - t * G);
+      const uint16_t* v = h->values.data() + h->val_off[t];
+      uint16_t* o = d.vals.data() + (size_t)d.tile_kp_off[t] * G;
+      for (int j = 0; j < kt; ++j)
+        std::copy(v + (size_t)j * w, v + (size_t)(j + 1) * w, o + (size_t)j * G);
+    }
+    d.meta.clear();
+    return;
+  }
+  // TVW
+  const int nb_per_tile = G / 32;
+  d.vals.assign((size_t)d.tile_kp_off[nt] / 2 * G, 0);               // half the rows survive
+  d.meta.assign((size_t)d.tile_kp_off[nt] / KSTEP_TVW * nb_per_tile * 64, 0);
+  for (int t = 0; t < nt; ++t) {
+    const int kt = h->tile_k_off[t + 1] - h->tile_k_off[t];
+    const int ng = (kt + 3) / 4;
+    const int w = std::min(G, h->n_kept - t * G);
+    const int kp0 = d.tile_kp_off[t], kp = d.tile_kp_off[t + 1] - kp0;
+    const uint16_t* v = h->values.data() + h->val_off[t];
+    const uint8_t* me = h->meta.data() + h->meta_off[t];
+    uint16_t* ov = d.vals.data() + (size_t)kp0 / 2 * G;
+    uint32_t* om = d.meta.data() + (size_t)kp0 / KSTEP_TVW * nb_per_tile * 64;
+    for (int s = 0; s < kp / KSTEP_TVW; ++s)
+      for (int nb = 0; nb < nb_per_tile; ++nb)
+        for (int l = 0; l < 64; ++l) {
+          const int c = 32 * nb + l % 32;
+          uint32_t word = 0;
+          for (int u = 0; u < 2; ++u) {
+            uint16_t* dst = ov + ((((size_t)s * 2 + u) * nb_per_tile + nb) * 64 + l) * 8;
+            for (int j = 0; j < 4; ++j) {
+              const int g = 16 * s + 8 * u + 4 * (l / 32) + j;  // logical group of 4 rows
+              uint32_t nib = 0x4;                               // positions (0,1), zero values
+              if (g < ng && c < w) {
+                nib = me[(size_t)g * w + c];
+                dst[2 * j + 0] = v[((size_t)g * 2 + 0) * w + c];
+                dst[2 * j + 1] = v[((size_t)g * 2 + 1) * w + c];
+              }
+              word |= nib << (16 * u + 4 * j);
+            }
+          }
+          om[((size_t)s * nb_per_tile + nb) * 64 + l] = word;
+        }
+  }
+}
+
+}  // namespace twg

@@ -1,0 +1,61 @@
+// Internal: the object behind tw_handle_t.  Host-side logical form (what
+// tw_export shows), the host staging copy of the device image, and the device
+// pointers once uploaded.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+#include "twgemm.h"
+
+namespace twg {
+
+// K-step the device image is padded to.  One main-loop stage of the TW kernel
+// consumes KSTEP_TW condensed rows, one stage of the TVW kernel KSTEP_TVW
+// (two 2:4 sparse matrix-core instructions of 32 logical k each).
+constexpr int KSTEP_TW = 32;
+constexpr int KSTEP_TVW = 64;
+
+struct DeviceImage {
+  // host staging (filled by the packer)
+  std::vector<int32_t> col_idx;      // n_tiles*G, -1 = no column (narrow last tile)
+  std::vector<int32_t> tile_kp_off;  // n_tiles+1, prefix sums of padded K_t
+  std::vector<int32_t> row_idx;      // sum Kp_t; pads repeat the tile's last kept row (0 if none)
+  std::vector<int32_t> zero_cols;    // original indices of pruned columns
+  std::vector<int32_t> tile_order;   // tiles by descending K_t (longest first)
+  std::vector<uint16_t> vals;        // TW: [sum Kp_t][G]; TVW: swizzled compressed values
+  std::vector<uint32_t> meta;        // TVW: swizzled 2-bit position words
+  // device copies (one allocation, sub-pointers)
+  void* blob = nullptr;
+  size_t blob_bytes = 0;
+  int device = -1;
+  const int32_t* d_col_idx = nullptr;
+  const int32_t* d_tile_kp_off = nullptr;
+  const int32_t* d_row_idx = nullptr;
+  const int32_t* d_zero_cols = nullptr;
+  const int32_t* d_tile_order = nullptr;
+  const uint16_t* d_vals = nullptr;
+  const uint32_t* d_meta = nullptr;
+};
+
+}  // namespace twg
+
+struct tw_handle_s {
+  int32_t K = 0, N = 0, G = 0, pattern = 0;
+  int32_t n_kept = 0, n_tiles = 0;
+  std::vector<int32_t> col_idx, cto_n, tile_k_off, row_idx, cto_k;
+  std::vector<int64_t> val_off, meta_off;
+  std::vector<uint16_t> values;
+  std::vector<uint8_t> meta, valid;
+  int64_t sum_kw = 0, sum_k = 0;
+  int32_t max_kp = 0;  // largest padded K_t
+  twg::DeviceImage img;
+};
+
+namespace twg {
+// Fills *h from (B, mask[, tile_mask]).  Returns TW_OK / TW_ERR_MASK / TW_ERR_ALLOC.
+tw_status pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_mask,
+                    int K, int N, int G, int pattern, tw_handle_s* h);
+tw_status unpack_host(const tw_handle_s* h, uint16_t* Bm, uint8_t* mask);
+// Builds h->img host staging from the logical form.
+void build_device_image(tw_handle_s* h);
+}  // namespace twg

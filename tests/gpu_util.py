@@ -1,0 +1,54 @@
+"""GPU-side helpers for the parity tests: move a case to the device in the
+K x M / N x M layout, call the C ABI, bring C back as M x N."""
+import numpy as np
+
+
+def _torch():
+    import torch
+    return torch
+
+
+def to_dev_KM(A16, lda=None):
+    """A (M x K fp16) -> device tensor K x lda holding A^T; padding is NaN."""
+    torch = _torch()
+    M, K = A16.shape
+    lda = lda or (M + 7) // 8 * 8
+    At = np.full((K, lda), np.nan, np.float16)
+    At[:, :M] = A16.T
+    return torch.from_numpy(At).cuda(), lda
+
+
+def new_C(N, M, ldc=None, fill=float("nan")):
+    torch = _torch()
+    ldc = ldc or (M + 7) // 8 * 8
+    return torch.full((N, ldc), fill, dtype=torch.float16, device="cuda"), ldc
+
+
+def run_tw(tw, packed, A16, N, *, lda=None, ldc=None, fill=float("nan")):
+    """Returns (C as M x N float64, raw N x ldc fp16 array)."""
+    torch = _torch()
+    M = A16.shape[0]
+    At, lda = to_dev_KM(A16, lda)
+    Ct, ldc = new_C(N, M, ldc, fill)
+    tw.tw_gemm(At.data_ptr(), M, lda, tw.LAYOUT_KM, packed, Ct.data_ptr(), ldc,
+               torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    raw = Ct.cpu().numpy()
+    return raw[:, :M].T.astype(np.float64), raw
+
+
+def run_dense(tw, A16, B16, *, lda=None, ldb=None, ldc=None):
+    torch = _torch()
+    M, K = A16.shape
+    N = B16.shape[1]
+    At, lda = to_dev_KM(A16, lda)
+    ldb = ldb or (N + 7) // 8 * 8
+    Bp = np.full((K, ldb), np.nan, np.float16)
+    Bp[:, :N] = B16
+    Bd = torch.from_numpy(Bp).cuda()
+    Ct, ldc = new_C(N, M, ldc)
+    tw.tw_dense_gemm(At.data_ptr(), Bd.data_ptr(), Ct.data_ptr(), M, K, N, lda, ldb, ldc,
+                     tw.LAYOUT_KM, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    raw = Ct.cpu().numpy()
+    return raw[:, :M].T.astype(np.float64), raw
