@@ -46,6 +46,9 @@ def lib():
         p = lib_path()
         if not os.path.exists(p):
             raise ImportError(f"{p} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+        # PyTorch ships its own HIP/HSA runtime; it has to be the first one in the
+        # process, or torch later finds no GPU.  libtwgemm.so then binds to it.
+        import torch  # noqa: F401
         L = C.CDLL(p)
         vp, i = C.c_void_p, C.c_int
         L.tw_status_str.restype = C.c_char_p
