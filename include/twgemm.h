@@ -164,6 +164,9 @@ const char* tw_status_str(int status);
  *   "tile_m"   0 = heuristic, else force the M-tile (64, 128 or 256)
  *   "xcd_map"  1 (default) = remap workgroup ids so that one XCD walks all
  *              N-tiles of an M-band; 0 = plain order
+ *   "kernel"   0 = automatic, 1 = register-staged pipeline, 2 = asynchronous
+ *              global->LDS copy pipeline (TW_ERR_UNSUPPORTED where it has no instance)
+ *   "depth"    stages in flight of the asynchronous pipeline: 3 or 4 (default)
  * tw_flop_counts: condensed multiply-add work of a handle:
  *   *sum_kw = sum over tiles of K_t * W_t (kept-row x width products).
  */

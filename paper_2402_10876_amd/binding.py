@@ -37,7 +37,9 @@ class _View(C.Structure):
 
 
 def lib_path() -> str:
-    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libtwgemm.so")
+    """In-tree library; TWGEMM_LIB may point at another build of the same ABI."""
+    return os.environ.get("TWGEMM_LIB") or os.path.join(
+        os.path.dirname(os.path.abspath(__file__)), "libtwgemm.so")
 
 
 def lib():

@@ -13,6 +13,8 @@ namespace {
 
 std::atomic<int> opt_tile_m{0};
 std::atomic<int> opt_xcd_map{1};
+std::atomic<int> opt_kernel{0};   // 0 = automatic, 1 = register-staged, 2 = asynchronous copies
+std::atomic<int> opt_depth{4};
 
 bool valid_G(int G) { return G == 32 || G == 64 || G == 128; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -132,7 +134,11 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
   g.meta = h->img.d_meta;
   g.n_tiles = h->n_tiles; g.K = h->K; g.N = h->N; g.xcd_map = opt_xcd_map.load();
   const int tm = pick_tile_m(M, h->n_tiles > 0 ? h->n_tiles : 1, h->G);
-  hipError_t e = twg::launch_tw_km(h->G, tm, g, (hipStream_t)stream);
+  hipError_t e = hipErrorInvalidValue;
+  if (opt_kernel.load() != 1 && h->G != 32)
+    e = twg::launch_tw_km_dma(h->G, tm, opt_depth.load(), g, (hipStream_t)stream);
+  if (e == hipErrorInvalidValue && opt_kernel.load() != 2)
+    e = twg::launch_tw_km(h->G, tm, g, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
@@ -156,7 +162,11 @@ tw_status tw_dense_gemm(const void* A, const void* B, void* C, int M, int K, int
   g.n_tiles = (N + tn - 1) / tn;
   g.xcd_map = opt_xcd_map.load();
   const int tm = pick_tile_m(M, g.n_tiles, tn);
-  hipError_t e = twg::launch_dense_km(tn, tm, g, (hipStream_t)stream);
+  hipError_t e = hipErrorInvalidValue;
+  if (opt_kernel.load() != 1 && K % 32 == 0)
+    e = twg::launch_dense_km_dma(tn, tm, opt_depth.load(), g, (hipStream_t)stream);
+  if (e == hipErrorInvalidValue && opt_kernel.load() != 2)
+    e = twg::launch_dense_km(tn, tm, g, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
@@ -192,6 +202,8 @@ tw_status tw_set_option(const char* name, int value) {
   if (!name) return TW_ERR_ARG;
   if (!std::strcmp(name, "tile_m")) { opt_tile_m.store(value); return TW_OK; }
   if (!std::strcmp(name, "xcd_map")) { opt_xcd_map.store(value != 0); return TW_OK; }
+  if (!std::strcmp(name, "kernel")) { opt_kernel.store(value); return TW_OK; }
+  if (!std::strcmp(name, "depth")) { opt_depth.store(value == 3 ? 3 : 4); return TW_OK; }
   return TW_ERR_ARG;
 }
 

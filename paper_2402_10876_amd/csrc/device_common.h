@@ -1,0 +1,76 @@
+// Internal: device-side helpers shared by the kernels of this library.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "kernels.h"
+
+namespace twg {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef int int2v __attribute__((ext_vector_type(2)));
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+#define LDS_PTR(T, p) ((T __attribute__((address_space(3)))*)(p))
+#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
+
+constexpr int KS = 32;        // condensed rows per main-loop stage
+constexpr int NTHREADS = 256;
+
+// Developer build only (-DTWG_TRACE): wave 0 of the first workgroups records
+// shader-clock timestamps at the phase boundaries of the main loop.
+#ifdef TWG_TRACE
+constexpr int TRACE_WGS = 64, TRACE_SLOTS = 256;
+static __device__ unsigned long long twg_trace[TRACE_WGS * TRACE_SLOTS];  // one per source file
+#define TWG_TRACE_INIT()                                         \
+  const bool trace_on = threadIdx.x == 0 && blockIdx.x < TRACE_WGS; \
+  int trace_n = 0
+#define TWG_STAMP()                                                                   \
+  do {                                                                                \
+    if (trace_on && trace_n < TRACE_SLOTS)                                            \
+      twg_trace[blockIdx.x * TRACE_SLOTS + trace_n++] = __builtin_readcyclecounter(); \
+  } while (0)
+#else
+#define TWG_TRACE_INIT() do {} while (0)
+#define TWG_STAMP() do {} while (0)
+#endif
+
+// XOR mask applied to the byte offset inside a row of a k-major LDS tile with
+// RB bytes per row.  The LDS has 64 banks of 4 bytes; one half-wave of a
+// transposing read touches 4 consecutive rows x 64 bytes, and the mask sends
+// those four pieces to the four different quarters of the 256-byte bank period.
+template <int RB>
+__device__ __forceinline__ int swz_mask(int row) {
+  if constexpr (RB % 256 == 0) return (row & 3) << 6;
+  else if constexpr (RB == 128) return ((row >> 1) & 1) << 6;  // two rows per period
+  else return 0;                                                // RB == 64: four rows = one period
+}
+template <int RB>
+__device__ __forceinline__ int swz(int row, int xbytes) {
+  return row * RB + (xbytes ^ swz_mask<RB>(row));
+}
+
+// Workgroup id -> logical id.  Consecutive workgroup ids are dealt round-robin
+// to the 8 XCDs (each with its own L2); the remap hands every XCD a contiguous
+// range of logical ids.
+__device__ __forceinline__ int xcd_remap(int bid, int n) {
+  const int xcd = bid & 7, slot = bid >> 3;
+  const int per = n >> 3, rem = n & 7;
+  return (xcd < rem) ? xcd * (per + 1) + slot : rem * (per + 1) + (xcd - rem) * per + slot;
+}
+
+// Extra workgroups of a launch write +0 into one pruned column of C each.
+__device__ __forceinline__ void zero_fill_column(const GemmArgs& g, int which) {
+  const int col = g.zero_cols[which];
+  _Float16* row = g.C + (size_t)col * g.ldc;
+  const u32x4 z = {0u, 0u, 0u, 0u};
+  for (int m = threadIdx.x * 8; m < g.M; m += NTHREADS * 8) {
+    if (m + 8 <= g.M) *(u32x4*)(row + m) = z;
+    else for (int i = m; i < g.M; ++i) row[i] = (_Float16)0.f;
+  }
+}
+
+}  // namespace twg

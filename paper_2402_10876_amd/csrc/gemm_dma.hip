@@ -1,0 +1,346 @@
+// Grouped TW kernel / dense baseline, asynchronous-copy pipeline for gfx950.
+//
+// Same decomposition and layouts as the register-staged kernel (one workgroup
+// per (M-tile, N-tile) pair, Listing 1; A is K x M and C is N x M, Section V
+// "Memory Accesses Coalesce"), but the stage copies never pass through
+// registers: every wave issues global_load_lds_dwordx4, which moves 64 x 16
+// bytes from per-lane global addresses straight into 1 KiB of LDS.  D stages
+// of 32 condensed rows are in flight per workgroup; the only synchronisation
+// per stage is one vmcnt wait and one s_barrier.
+//
+//   gather  : lane l of a copy instruction fetches one 16-byte chunk of row
+//             row_idx[...] of A (Listing 1: CTO_k); the four (TM=128) rows an
+//             instruction covers come from one scalar load of the index list.
+//   LDS     : k-major tiles, 64-byte units XOR-swizzled (see swz_mask); the
+//             swizzle is applied on the global side, the LDS side of a copy
+//             instruction is always 1 KiB contiguous.
+//   MFMA    : operands come from ds_read_b64_tr_b16 issued from inline
+//             assembly.  The compiler orders every LDS read it knows about
+//             behind all earlier asynchronous copies (vmcnt(0)), which would
+//             serialise the pipeline; reads it cannot see are ordered by the
+//             explicit waits written here instead.
+//   overlap : the MFMAs of the second half of stage s are issued after the
+//             barrier and the operand reads of stage s+1, so LDS latency is
+//             hidden behind matrix-core work.
+#include <type_traits>
+
+#include "device_common.h"
+
+namespace twg {
+
+namespace {
+
+template <int OFF>
+__device__ __forceinline__ int2v tr_read(uint32_t addr) {
+  int2v v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+
+// One matrix-core operand (32 x-values x 16 k) = two transposed 64-bit reads.
+struct Frag { int2v lo, hi; };
+
+__device__ __forceinline__ half8 as_half8(const Frag& f) {
+  union { int2v s[2]; half8 h; } u;
+  u.s[0] = f.lo; u.s[1] = f.hi;
+  return u.h;
+}
+
+template <int N>
+__device__ __forceinline__ void wait_lds(Frag* f) {
+  // s_waitcnt tied to the fragments so that no use can be moved above it
+  if constexpr (N == 2)
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi));
+  else if constexpr (N == 3)
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi),
+                 "+v"(f[2].lo), "+v"(f[2].hi));
+  else if constexpr (N == 4)
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi),
+                 "+v"(f[2].lo), "+v"(f[2].hi), "+v"(f[3].lo), "+v"(f[3].hi));
+  else if constexpr (N == 6)
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi),
+                 "+v"(f[2].lo), "+v"(f[2].hi), "+v"(f[3].lo), "+v"(f[3].hi), "+v"(f[4].lo),
+                 "+v"(f[4].hi), "+v"(f[5].lo), "+v"(f[5].hi));
+  else static_assert(N == 2, "unsupported fragment count");
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+}  // namespace
+
+template <int TM, int TN, int WAVES_M, int D, bool DENSE>
+__global__ __launch_bounds__(NTHREADS) void tw_gemm_km_dma_kernel(GemmArgs g) {
+  constexpr int WAVES_N = 4 / WAVES_M;
+  constexpr int WM = TM / WAVES_M, WN = TN / WAVES_N;
+  constexpr int MB = WM / 32, NB = WN / 32;
+  static_assert(MB >= 1 && NB >= 1, "wave tile must hold a 32x32 block");
+  constexpr int RBA = TM * 2, RBB = TN * 2;            // LDS row bytes
+  constexpr int STAGE_A = KS * RBA, STAGE_B = KS * RBB, STAGE = STAGE_A + STAGE_B;
+  static_assert(STAGE_A % 4096 == 0 && STAGE_B % 4096 == 0, "a stage is a whole number of 1 KiB copies per wave");
+  constexpr int NIA = STAGE_A / 4096, NIB = STAGE_B / 4096;   // copy instructions per wave and stage
+  constexpr int RPIA = 1024 / RBA, RPIB = 1024 / RBB;         // tile rows per copy instruction
+  static_assert((RPIA == 2 || RPIA == 4 || RPIA == 8) && (NIA == 1 || NIA == 2 || NIA == 4), "");
+  static_assert(D == 3 || D == 4, "the stage wait below handles up to two newer stages");
+  constexpr int NPS = NIA + NIB;
+  constexpr int CA = TM / 8;
+  constexpr int CS = (TM + 4) * 2;                     // epilogue row bytes: 66 dwords mod 64 banks = 2
+  constexpr int PIPE_BYTES = D * STAGE, EPI_BYTES = TN * CS;
+  constexpr int LDS_BYTES = PIPE_BYTES > EPI_BYTES ? PIPE_BYTES : EPI_BYTES;
+  __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n_gemm = g.n_mtiles * g.n_tiles;
+  TWG_TRACE_INIT();
+  TWG_STAMP();
+  if ((int)blockIdx.x >= n_gemm) {
+    zero_fill_column(g, blockIdx.x - n_gemm);
+    return;
+  }
+  const int lid = g.xcd_map ? xcd_remap(blockIdx.x, n_gemm) : (int)blockIdx.x;
+  const int mt = lid / g.n_tiles;
+  int t = lid - mt * g.n_tiles;
+  if (!DENSE && g.tile_order) t = g.tile_order[t];
+  const int m0 = mt * TM;
+
+  int kp0, ns;
+  if constexpr (DENSE) { kp0 = 0; ns = g.K / KS; }     // host guarantees K % KS == 0
+  else { kp0 = g.tile_kp_off[t]; ns = (g.tile_kp_off[t + 1] - kp0) / KS; }
+  const _Float16* Bt = DENSE ? g.vals + (size_t)t * TN : g.vals + (size_t)kp0 * TN;
+  const int ldb = DENSE ? g.ldb : TN;
+
+  // kept-column indices of the rows of C^T this thread will store (CTO_n)
+  constexpr int ROWS_PER_PASS = NTHREADS / CA;
+  constexpr int NPASS = TN / ROWS_PER_PASS;
+  const int c = tid % CA, r0 = tid / CA;
+  int cols[NPASS];
+#pragma unroll
+  for (int i = 0; i < NPASS; ++i) {
+    const int n = r0 + i * ROWS_PER_PASS;
+    if constexpr (DENSE) { cols[i] = t * TN + n; if (cols[i] >= g.N) cols[i] = -1; }
+    else cols[i] = g.col_idx[t * TN + n];
+  }
+
+  // ---- geometry of the asynchronous copies --------------------------------
+  // Copy instruction j of this wave fills LDS bytes [(wave*NI + j) KiB, +1 KiB)
+  // of the stage; lane l owns the 16 bytes at l*16, i.e. tile row
+  // (wave*NI + j)*RPI + l*16/RB at physical byte (l*16) % RB, which holds the
+  // logical bytes physical ^ swz_mask(row).
+  const int lb = lane * 16;
+  const int a_rloc = lb / RBA, b_rloc = lb / RBB;
+  int a_el[NIA], b_el[NIB];
+#pragma unroll
+  for (int j = 0; j < NIA; ++j) {
+    const int row = (wave * NIA + j) * RPIA + a_rloc;
+    a_el[j] = ((lb % RBA) ^ swz_mask<RBA>(row)) / 2;
+    if (m0 + a_el[j] >= g.M) a_el[j] = 0;   // past M: re-read chunk 0 (those lanes are never stored)
+  }
+#pragma unroll
+  for (int j = 0; j < NIB; ++j) {
+    const int row = (wave * NIB + j) * RPIB + b_rloc;
+    b_el[j] = ((lb % RBB) ^ swz_mask<RBB>(row)) / 2;
+    if constexpr (DENSE) { if (t * TN + b_el[j] >= g.N) b_el[j] = 0; }
+  }
+  const _Float16* Abase = g.A + m0;
+
+  // Row indices of stage s for copy instruction j: RPIA consecutive entries of
+  // the kept-row list at a wave-uniform address.  They are fetched with scalar
+  // loads written in assembly: a vector load would share the in-order counter
+  // of the asynchronous copies, and waiting for it would drain the pipeline.
+  typedef int sidx_t __attribute__((ext_vector_type(RPIA)));
+  sidx_t rows_next[NIA];
+  auto fetch_rows = [&](int s) {
+    if constexpr (!DENSE) {
+#pragma unroll
+      for (int j = 0; j < NIA; ++j) {
+        const int* rp = g.row_idx + kp0 + s * KS + (wave * NIA + j) * RPIA;
+        if constexpr (RPIA == 2) asm volatile("s_load_dwordx2 %0, %1, 0x0" : "=s"(rows_next[j]) : "s"(rp));
+        else if constexpr (RPIA == 4) asm volatile("s_load_dwordx4 %0, %1, 0x0" : "=s"(rows_next[j]) : "s"(rp));
+        else asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(rows_next[j]) : "s"(rp));
+      }
+    }
+  };
+  auto issue = [&](int s) {        // uses rows_next (stage s), then prefetches stage s+1's
+    char* dstA = lds + (s % D) * STAGE;
+    char* dstB = dstA + STAGE_A;
+    if constexpr (!DENSE) {
+      // scalar loads return out of order: full wait, tied to the registers
+      if constexpr (NIA == 1) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(rows_next[0]));
+      else if constexpr (NIA == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(rows_next[0]), "+s"(rows_next[1]));
+      else asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(rows_next[0]), "+s"(rows_next[1]), "+s"(rows_next[2]), "+s"(rows_next[3]));
+    }
+#pragma unroll
+    for (int j = 0; j < NIA; ++j) {
+      int row;
+      if constexpr (DENSE) row = s * KS + (wave * NIA + j) * RPIA + a_rloc;
+      else {
+        row = rows_next[j][0];
+#pragma unroll
+        for (int q = 1; q < RPIA; ++q) row = (a_rloc == q) ? rows_next[j][q] : row;
+      }
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(Abase + (size_t)row * g.lda + a_el[j]),
+                                       LDS_PTR(void, dstA + (wave * NIA + j) * 1024), 16, 0, 0);
+    }
+#pragma unroll
+    for (int j = 0; j < NIB; ++j) {
+      const int row = s * KS + (wave * NIB + j) * RPIB + b_rloc;
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(Bt + (size_t)row * ldb + b_el[j]),
+                                       LDS_PTR(void, dstB + (wave * NIB + j) * 1024), 16, 0, 0);
+    }
+    fetch_rows(s + 1 < ns ? s + 1 : ns - 1);
+  };
+
+  floatx16 acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+  // per-lane LDS byte address of each operand block at stage buffer 0, k-step 0
+  const uint32_t lds0 = (uint32_t)(uintptr_t)LDS_PTR(char, lds);
+  const int p = lane & 15, q = lane >> 4;
+  const int frow = 8 * (q >> 1) + (p >> 2);
+  uint32_t fa[MB], fb[NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+    fa[i] = lds0 + swz<RBA>(frow, (wm * WM + i * 32 + 16 * (q & 1) + 4 * (p & 3)) * 2);
+#pragma unroll
+  for (int j = 0; j < NB; ++j)
+    fb[j] = lds0 + STAGE_A + swz<RBB>(frow, (wn * WN + j * 32 + 16 * (q & 1) + 4 * (p & 3)) * 2);
+
+  constexpr int NF = MB + NB;
+  Frag f0[NF], f1[NF];       // operands of k-steps 0 and 1 of a stage
+  auto read_step = [&](uint32_t boff, auto KK_, Frag* f) {
+    constexpr int KK = decltype(KK_)::value;
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+      f[i].lo = tr_read<KK * RBA>(fa[i] + boff);
+      f[i].hi = tr_read<(KK + 4) * RBA>(fa[i] + boff);
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      f[MB + j].lo = tr_read<KK * RBB>(fb[j] + boff);
+      f[MB + j].hi = tr_read<(KK + 4) * RBB>(fb[j] + boff);
+    }
+  };
+  auto mfma_step = [&](const Frag* f) {
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(as_half8(f[i]), as_half8(f[MB + j]),
+                                                           acc[i][j], 0, 0, 0);
+  };
+  using K0 = std::integral_constant<int, 0>;
+  using K16 = std::integral_constant<int, 16>;
+
+  if (ns > 0) {
+    fetch_rows(0);
+    for (int d = 0; d < D - 1; ++d)
+      if (d < ns) issue(d);
+  }
+  TWG_STAMP();
+  for (int s = 0; s < ns; ++s) {
+    // own copies of stage s have landed: at most the copies of the newer stages remain
+    int newer = ns - 1 - s;
+    if (newer > D - 2) newer = D - 2;
+    if (newer >= 2) wait_vm<2 * NPS>();
+    else if (newer == 1) wait_vm<NPS>();
+    else wait_vm<0>();
+    // everybody's copies of stage s have landed, everybody is done reading stage s-1
+    asm volatile("s_barrier" ::: "memory");
+    if (s + D - 1 < ns) issue(s + D - 1);
+    const uint32_t boff = (uint32_t)((s % D) * STAGE);
+    read_step(boff, K0{}, f0);
+    if (s > 0) mfma_step(f1);            // second k-step of the previous stage
+    wait_lds<NF>(f0);
+    read_step(boff, K16{}, f1);
+    mfma_step(f0);
+    wait_lds<NF>(f1);
+    TWG_STAMP();
+  }
+  if (ns > 0) mfma_step(f1);
+
+  // ---- epilogue: fp32 -> fp16 (RNE), stage as [n][m], store rows of C^T ----
+  const int m = m0 + c * 8;
+  long long dst_off[NPASS];
+#pragma unroll
+  for (int i = 0; i < NPASS; ++i)
+    dst_off[i] = (cols[i] < 0 || m >= g.M) ? -1 : (long long)cols[i] * g.ldc + m;
+  TWG_STAMP();
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const int n = wn * WN + j * 32 + (lane & 31);
+#pragma unroll
+      for (int rq = 0; rq < 4; ++rq) {
+        const int mm = wm * WM + i * 32 + 8 * rq + 4 * (lane >> 5);
+        half4 v;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) v[r] = (_Float16)acc[i][j][rq * 4 + r];
+        *(half4*)(lds + n * CS + mm * 2) = v;
+      }
+    }
+  __syncthreads();
+  TWG_STAMP();
+#pragma unroll
+  for (int i = 0; i < NPASS; ++i) {
+    const int n = r0 + i * ROWS_PER_PASS;
+    if (dst_off[i] < 0) continue;
+    union { uint2 h[2]; u32x4 v; } u;   // staging rows are 8-byte aligned only
+    u.h[0] = *(const uint2*)(lds + n * CS + c * 16);
+    u.h[1] = *(const uint2*)(lds + n * CS + c * 16 + 8);
+    _Float16* dst = g.C + dst_off[i];
+    if (m + 8 <= g.M) *(u32x4*)dst = u.v;
+    else {
+      const _Float16* e = (const _Float16*)(lds + n * CS + c * 16);
+      for (int qq = 0; m + qq < g.M; ++qq) dst[qq] = e[qq];
+    }
+  }
+  TWG_STAMP();
+}
+
+template <int TM, int TN, int WAVES_M, int D, bool DENSE>
+static hipError_t launch(const GemmArgs& g, hipStream_t stream) {
+  const int grid = g.n_mtiles * g.n_tiles + g.n_zero;
+  if (grid <= 0) return hipSuccess;
+  hipLaunchKernelGGL((tw_gemm_km_dma_kernel<TM, TN, WAVES_M, D, DENSE>), dim3(grid),
+                     dim3(NTHREADS), 0, stream, g);
+  return hipGetLastError();
+}
+
+template <bool DENSE>
+static hipError_t dispatch(int G, int tm, int depth, GemmArgs& g, hipStream_t stream) {
+  g.n_mtiles = (g.M + tm - 1) / tm;
+#define TWG_CASE(TM_, TN_, WM_, D_) \
+  if (G == TN_ && tm == TM_ && depth == D_) return launch<TM_, TN_, WM_, D_, DENSE>(g, stream);
+  TWG_CASE(64, 128, 1, 3) TWG_CASE(128, 128, 2, 3) TWG_CASE(256, 128, 2, 3)
+  TWG_CASE(64, 128, 1, 4) TWG_CASE(128, 128, 2, 4) TWG_CASE(256, 128, 2, 4)
+  TWG_CASE(128, 64, 2, 3) TWG_CASE(256, 64, 4, 3)
+  TWG_CASE(128, 64, 2, 4) TWG_CASE(256, 64, 4, 4)
+#undef TWG_CASE
+  return hipErrorInvalidValue;
+}
+
+#ifdef TWG_TRACE
+extern "C" int tw_debug_read_trace_dma(unsigned long long* out, int n) {
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(twg_trace), sizeof(unsigned long long) * n);
+}
+#endif
+
+hipError_t launch_tw_km_dma(int G, int tm, int depth, GemmArgs g, hipStream_t stream) {
+  return dispatch<false>(G, tm, depth, g, stream);
+}
+hipError_t launch_dense_km_dma(int tn, int tm, int depth, GemmArgs g, hipStream_t stream) {
+  return dispatch<true>(tn, tm, depth, g, stream);
+}
+
+}  // namespace twg

@@ -17,33 +17,11 @@
 // The epilogue rounds fp32 -> fp16 once, stages the tile in LDS and stores
 // whole rows of C^T at the kept-column indices (Listing 1: CTO_n).  Extra
 // workgroups of the same launch write +0 to the pruned columns of C.
-#include <hip/hip_runtime.h>
-#include <stdint.h>
+#include <type_traits>
 
-#include "kernels.h"
+#include "device_common.h"
 
 namespace twg {
-
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-typedef short short4v __attribute__((ext_vector_type(4)));
-typedef float floatx16 __attribute__((ext_vector_type(16)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-
-#define LDS_PTR(T, p) ((T __attribute__((address_space(3)))*)(p))
-
-constexpr int KS = 32;        // condensed rows per stage
-constexpr int NTHREADS = 256;
-
-// Byte offset of element (row, x) of a k-major LDS tile with RB bytes per row.
-// 32-byte segments are XOR-swizzled so that the four rows touched by one
-// 16-lane group of a transposing read fall into four different bank groups.
-template <int RB>
-__device__ __forceinline__ int swz(int row, int xbytes) {
-  int a = row * RB + xbytes;
-  if constexpr (RB % 128 == 0) return a ^ ((row & 3) << 5);
-  else return a ^ (((row >> 1) & 1) << 5);  // RB == 64: two rows per 128 B
-}
 
 // MFMA operand for 32 consecutive x (rows of D for srcA, columns for srcB) and
 // 16 consecutive k, from a k-major LDS tile.  Lane l gets x = x0 + l%32,
@@ -71,7 +49,7 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
   constexpr int NA = (KS * CA + NTHREADS - 1) / NTHREADS;  // chunks per thread and stage
   constexpr int NBK = (KS * CB + NTHREADS - 1) / NTHREADS;
   constexpr int STAGE_A = KS * RBA, STAGE_B = KS * RBB;
-  constexpr int CS = (TM + 8) * 2;                   // epilogue row bytes
+  constexpr int CS = (TM + 4) * 2;                   // epilogue row bytes: 66 dwords mod 64 banks = 2
   constexpr int PIPE_BYTES = 2 * (STAGE_A + STAGE_B);
   constexpr int EPI_BYTES = TN * CS;
   constexpr int LDS_BYTES = PIPE_BYTES > EPI_BYTES ? PIPE_BYTES : EPI_BYTES;
@@ -79,28 +57,18 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_gemm = g.n_mtiles * g.n_tiles;
+  TWG_TRACE_INIT();
+  TWG_STAMP();
 
   // ---- extra workgroups: +0 into the pruned columns of C -----------------
   if ((int)blockIdx.x >= n_gemm) {
-    const int col = g.zero_cols[blockIdx.x - n_gemm];
-    _Float16* row = g.C + (size_t)col * g.ldc;
-    const u32x4 z = {0u, 0u, 0u, 0u};
-    for (int m = tid * 8; m < g.M; m += NTHREADS * 8) {
-      if (m + 8 <= g.M) *(u32x4*)(row + m) = z;
-      else for (int i = m; i < g.M; ++i) row[i] = (_Float16)0.f;
-    }
+    zero_fill_column(g, blockIdx.x - n_gemm);
     return;
   }
 
-  // ---- workgroup -> (M-tile, N-tile).  Consecutive workgroup ids are dealt
-  // round-robin to the 8 XCDs; remap so that each XCD gets a contiguous range
-  // of logical ids, i.e. walks all N-tiles of an M-band out of its own L2.
-  int lid = blockIdx.x;
-  if (g.xcd_map) {
-    const int xcd = lid & 7, slot = lid >> 3;
-    const int per = n_gemm >> 3, rem = n_gemm & 7;
-    lid = (xcd < rem) ? xcd * (per + 1) + slot : rem * (per + 1) + (xcd - rem) * per + slot;
-  }
+  // ---- workgroup -> (M-tile, N-tile): one XCD walks all N-tiles of an M-band
+  // out of its own L2.
+  const int lid = g.xcd_map ? xcd_remap(blockIdx.x, n_gemm) : (int)blockIdx.x;
   const int mt = lid / g.n_tiles;
   int t = lid - mt * g.n_tiles;
   if (!DENSE && g.tile_order) t = g.tile_order[t];
@@ -111,29 +79,29 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
   else { kp0 = g.tile_kp_off[t]; ns = (g.tile_kp_off[t + 1] - kp0) / KS; }
   const _Float16* Bt = DENSE ? g.vals + (size_t)t * TN : g.vals + (size_t)kp0 * TN;
 
-  // per-thread chunk coordinates
-  int a_row[NA], a_c[NA], b_row[NBK], b_c[NBK];
-  bool a_on[NA], b_on[NBK];
+  // per-thread chunk coordinates.  Every thread moves NA chunks of A and NBK
+  // chunks of B per stage, without branches: a tile with fewer chunks than
+  // threads (TN = 32) is covered twice with identical data.
+  int a_row[NA], a_c[NA], a_slot[NA], b_row[NBK], b_c[NBK], b_slot[NBK];
+  bool b_live[NBK];
 #pragma unroll
   for (int i = 0; i < NA; ++i) {
-    int id = tid + i * NTHREADS;
-    a_on[i] = id < KS * CA; a_row[i] = (id / CA) % KS; a_c[i] = id % CA;
+    const int id = (tid + i * NTHREADS) % (KS * CA);
+    a_row[i] = id / CA; a_c[i] = id % CA;
+    a_slot[i] = swz<RBA>(a_row[i], a_c[i] * 16);
     // chunks starting past M re-read chunk 0 of the row (their lanes are never stored)
     if (m0 + a_c[i] * 8 >= g.M) a_c[i] = 0;
   }
 #pragma unroll
   for (int i = 0; i < NBK; ++i) {
-    int id = tid + i * NTHREADS;
-    b_on[i] = id < KS * CB; b_row[i] = (id / CB) % KS; b_c[i] = id % CB;
-    if constexpr (DENSE) { if (t * TN + b_c[i] * 8 >= g.N) b_on[i] = false; }
+    const int id = (tid + i * NTHREADS) % (KS * CB);
+    b_row[i] = id / CB; b_c[i] = id % CB;
+    b_slot[i] = swz<RBB>(b_row[i], b_c[i] * 16);
+    b_live[i] = true;
+    if constexpr (DENSE) {
+      if (t * TN + b_c[i] * 8 >= g.N) { b_live[i] = false; b_c[i] = 0; }  // past the last column
+    }
   }
-  // chunk slot in LDS keeps the logical position even when the source is clamped
-  int a_slot[NA];
-#pragma unroll
-  for (int i = 0; i < NA; ++i) a_slot[i] = swz<RBA>(a_row[i], (((tid + i * NTHREADS) % CA) * 16));
-  int b_slot[NBK];
-#pragma unroll
-  for (int i = 0; i < NBK; ++i) b_slot[i] = swz<RBB>(b_row[i], (((tid + i * NTHREADS) % CB) * 16));
 
   auto load_idx = [&](int s, int* out) {
 #pragma unroll
@@ -142,30 +110,33 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
       else out[i] = g.row_idx[kp0 + s * KS + a_row[i]];
     }
   };
-  u32x4 ra[NA], rb[NBK];
-  auto load_stage = [&](int s, const int* idx) {
+  // Two register sets: while stage s is consumed from LDS, the global loads of
+  // stages s+1 and s+2 are in flight.
+  u32x4 ra[2][NA], rb[2][NBK];
+  auto load_stage = [&](int s, const int* idx, u32x4* pa, u32x4* pb) {
 #pragma unroll
     for (int i = 0; i < NA; ++i)
-      ra[i] = *(const u32x4*)(g.A + (size_t)idx[i] * g.lda + m0 + a_c[i] * 8);
+      pa[i] = *(const u32x4*)(g.A + (size_t)idx[i] * g.lda + m0 + a_c[i] * 8);
 #pragma unroll
     for (int i = 0; i < NBK; ++i) {
-      u32x4 v = {0u, 0u, 0u, 0u};
       if constexpr (DENSE) {
-        int k = s * KS + b_row[i];
-        if (b_on[i] && k < g.K) v = *(const u32x4*)(Bt + (size_t)k * g.ldb + b_c[i] * 8);
+        const int k = s * KS + b_row[i];
+        const int kc = k < g.K ? k : g.K - 1;
+        u32x4 v = *(const u32x4*)(Bt + (size_t)kc * g.ldb + b_c[i] * 8);
+        const bool keep = b_live[i] && k < g.K;   // rows past K and columns past N count as zero
+        pb[i] = keep ? v : u32x4{0u, 0u, 0u, 0u};
       } else {
-        if (b_on[i]) v = *(const u32x4*)(Bt + (size_t)(s * KS + b_row[i]) * TN + b_c[i] * 8);
+        pb[i] = *(const u32x4*)(Bt + (size_t)(s * KS + b_row[i]) * TN + b_c[i] * 8);
       }
-      rb[i] = v;
     }
   };
-  auto store_stage = [&](int buf) {
+  auto store_stage = [&](int buf, const u32x4* pa, const u32x4* pb) {
     char* As = lds + buf * (STAGE_A + STAGE_B);
     char* Bs = As + STAGE_A;
 #pragma unroll
-    for (int i = 0; i < NA; ++i) if (a_on[i]) *(u32x4*)(As + a_slot[i]) = ra[i];
+    for (int i = 0; i < NA; ++i) *(u32x4*)(As + a_slot[i]) = pa[i];
 #pragma unroll
-    for (int i = 0; i < NBK; ++i) if ((tid + i * NTHREADS) < KS * CB) *(u32x4*)(Bs + b_slot[i]) = rb[i];
+    for (int i = 0; i < NBK; ++i) *(u32x4*)(Bs + b_slot[i]) = pb[i];
   };
 
   floatx16 acc[MB][NB];
@@ -176,20 +147,53 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
-  int idx[NA];
-  if (ns > 0) {
-    load_idx(0, idx);
-    load_stage(0, idx);
-    if (ns > 1) load_idx(1, idx);
+  // kept-column indices of the rows of C^T this thread will store (CTO_n)
+  constexpr int ROWS_PER_PASS = NTHREADS / CA;
+  constexpr int NPASS = TN / ROWS_PER_PASS;
+  const int c = tid % CA, r0 = tid / CA;
+  int cols[NPASS];
+#pragma unroll
+  for (int i = 0; i < NPASS; ++i) {
+    const int n = r0 + i * ROWS_PER_PASS;
+    if constexpr (DENSE) { cols[i] = t * TN + n; if (cols[i] >= g.N) cols[i] = -1; }
+    else cols[i] = g.col_idx[t * TN + n];
   }
-  for (int s = 0; s < ns; ++s) {
-    store_stage(s & 1);
-    __syncthreads();
-    if (s + 1 < ns) {
-      load_stage(s + 1, idx);
-      if (s + 2 < ns) load_idx(s + 2, idx);
+
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+  int idx[2][NA];
+  if (ns > 0) {
+    load_idx(0, idx[0]);
+    load_idx(ns > 1 ? 1 : 0, idx[1]);
+    load_stage(0, idx[0], ra[0], rb[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    // same issue order as the steady state (index list of stage s+2 before the
+    // data of stage s+1), so the loop's wait counts are exact from the start
+    load_idx(ns > 2 ? 2 : 0, idx[0]);
+    __builtin_amdgcn_sched_barrier(0);
+    load_stage(ns > 1 ? 1 : 0, idx[1], ra[1], rb[1]);
+    __builtin_amdgcn_sched_barrier(0);
+  }
+
+  // One main-loop iteration on register set P.  LOAD: also issue stage s+2.
+  auto body = [&](int s, auto P_, auto LOAD_) {
+    constexpr int P = decltype(P_)::value;
+    constexpr bool LOAD = decltype(LOAD_)::value;
+    TWG_STAMP();
+    store_stage(s & 1, ra[P], rb[P]);
+    TWG_STAMP();
+    if constexpr (LOAD) {
+      // issue order matters (loads retire in order): index list of stage s+3
+      // first, then the data of stage s+2, so that waiting for an index list
+      // never waits for data issued after it
+      __builtin_amdgcn_sched_barrier(0);
+      load_idx(s + 3 < ns ? s + 3 : ns - 1, idx[1 - P]);
+      __builtin_amdgcn_sched_barrier(0);
+      load_stage(s + 2, idx[P], ra[P], rb[P]);
+      __builtin_amdgcn_sched_barrier(0);
     }
+    // LDS writes done, then workgroup barrier; outstanding global loads stay in flight
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    TWG_STAMP();
     const char* As = lds + (s & 1) * (STAGE_A + STAGE_B);
     const char* Bs = As + STAGE_A;
 #pragma unroll
@@ -205,10 +209,40 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
         for (int j = 0; j < NB; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
+  };
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+  {
+    int s = 0;
+    for (; s + 3 < ns; s += 2) {          // both iterations prefetch (s+1+2 < ns)
+      body(s, I0{}, std::true_type{});
+      body(s + 1, I1{}, std::true_type{});
+    }
+    // here s is even and ns - s is 0, 1, 2 or 3
+    if (s + 2 < ns) {                      // three left: one more prefetching iteration
+      body(s, I0{}, std::true_type{});
+      body(s + 1, I1{}, std::false_type{});
+      body(s + 2, I0{}, std::false_type{});
+    } else if (s + 1 < ns) {
+      body(s, I0{}, std::false_type{});
+      body(s + 1, I1{}, std::false_type{});
+    } else if (s < ns) {
+      body(s, I0{}, std::false_type{});
+    }
   }
 
   // ---- epilogue: fp32 -> fp16 (RNE), stage as [n][m], store rows of C^T ----
+  // Destination offsets are formed here from the column indices loaded at kernel
+  // start: loads and stores share one in-order counter, so no load may still be
+  // pending once the stores begin, or every store would wait for its predecessor.
+  const int m = m0 + c * 8;
+  long long dst_off[NPASS];
+#pragma unroll
+  for (int i = 0; i < NPASS; ++i)
+    dst_off[i] = (cols[i] < 0 || m >= g.M) ? -1 : (long long)cols[i] * g.ldc + m;
+  TWG_STAMP();
   __syncthreads();
+  TWG_STAMP();
 #pragma unroll
   for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -224,23 +258,22 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
       }
     }
   __syncthreads();
-  constexpr int ROWS_PER_PASS = NTHREADS / CA;
-  const int c = tid % CA, r0 = tid / CA;
-  const int m = m0 + c * 8;
-#pragma unroll 4
-  for (int n = r0; n < TN; n += ROWS_PER_PASS) {
-    int col;
-    if constexpr (DENSE) { col = t * TN + n; if (col >= g.N) col = -1; }
-    else col = g.col_idx[t * TN + n];
-    if (col < 0 || m >= g.M) continue;
-    const u32x4 v = *(const u32x4*)(lds + n * CS + c * 16);
-    _Float16* dst = g.C + (size_t)col * g.ldc + m;
-    if (m + 8 <= g.M) *(u32x4*)dst = v;
+#pragma unroll
+  for (int i = 0; i < NPASS; ++i) {
+    const int n = r0 + i * ROWS_PER_PASS;
+    if (dst_off[i] < 0) continue;
+    // staging rows are 8-byte aligned only: two 8-byte reads per chunk
+    union { uint2 h[2]; u32x4 v; } u;
+    u.h[0] = *(const uint2*)(lds + n * CS + c * 16);
+    u.h[1] = *(const uint2*)(lds + n * CS + c * 16 + 8);
+    _Float16* dst = g.C + dst_off[i];
+    if (m + 8 <= g.M) *(u32x4*)dst = u.v;
     else {
-      const _Float16* hv = (const _Float16*)&v;
-      for (int i = 0; m + i < g.M; ++i) dst[i] = hv[i];
+      const _Float16* e = (const _Float16*)(lds + n * CS + c * 16);
+      for (int q = 0; m + q < g.M; ++q) dst[q] = e[q];
     }
   }
+  TWG_STAMP();
 }
 
 template <int TM, int TN, int WAVES_M, bool DENSE>
@@ -263,6 +296,12 @@ static hipError_t dispatch(int G, int tm, GemmArgs& g, hipStream_t stream) {
 #undef TWG_CASE
   return hipErrorInvalidValue;
 }
+
+#ifdef TWG_TRACE
+extern "C" int tw_debug_read_trace(unsigned long long* out, int n) {
+  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(twg_trace), sizeof(unsigned long long) * n);
+}
+#endif
 
 hipError_t launch_tw_km(int G, int tm, GemmArgs g, hipStream_t stream) {
   return dispatch<false>(G, tm, g, stream);

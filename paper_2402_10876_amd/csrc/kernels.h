@@ -28,5 +28,9 @@ struct GemmArgs {
 // hipErrorInvalidValue when no instance exists for (G, tm).
 hipError_t launch_tw_km(int G, int tm, GemmArgs g, hipStream_t stream);
 hipError_t launch_dense_km(int tn, int tm, GemmArgs g, hipStream_t stream);
+// Asynchronous-copy pipeline (gemm_dma.hip): G / tn in {64, 128}, depth = stages
+// in flight (3 or 4); the dense variant needs K % 32 == 0.
+hipError_t launch_tw_km_dma(int G, int tm, int depth, GemmArgs g, hipStream_t stream);
+hipError_t launch_dense_km_dma(int tn, int tm, int depth, GemmArgs g, hipStream_t stream);
 
 }  // namespace twg
