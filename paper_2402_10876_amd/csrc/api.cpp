@@ -14,7 +14,7 @@ namespace {
 std::atomic<int> opt_tile_m{0};
 std::atomic<int> opt_xcd_map{1};
 std::atomic<int> opt_kernel{0};   // 0 = automatic, 1 = register-staged, 2 = asynchronous copies
-std::atomic<int> opt_depth{4};
+std::atomic<int> opt_depth{3};
 
 bool valid_G(int G) { return G == 32 || G == 64 || G == 128; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -76,11 +76,11 @@ tw_status tw_upload(tw_handle_t h) {
   if (hipGetDevice(&dev) != hipSuccess) return TW_ERR_HIP;
   // one allocation, 256-byte aligned parts
   struct Part { const void* src; size_t bytes; size_t off; };
-  Part parts[7] = {
+  Part parts[8] = {
       {d.col_idx.data(), d.col_idx.size() * 4, 0},   {d.tile_kp_off.data(), d.tile_kp_off.size() * 4, 0},
       {d.row_idx.data(), d.row_idx.size() * 4, 0},   {d.zero_cols.data(), d.zero_cols.size() * 4, 0},
       {d.tile_order.data(), d.tile_order.size() * 4, 0}, {d.vals.data(), d.vals.size() * 2, 0},
-      {d.meta.data(), d.meta.size() * 4, 0}};
+      {d.meta.data(), d.meta.size() * 4, 0}, {d.tile_sched.data(), d.tile_sched.size() * 4, 0}};
   size_t total = 0;
   for (auto& p : parts) { p.off = total; total += align_up(p.bytes ? p.bytes : 1, 256); }
   void* blob = nullptr;
@@ -100,6 +100,7 @@ tw_status tw_upload(tw_handle_t h) {
   d.d_tile_order = (const int32_t*)(b + parts[4].off);
   d.d_vals = (const uint16_t*)(b + parts[5].off);
   d.d_meta = (const uint32_t*)(b + parts[6].off);
+  d.d_tile_sched = (const int32_t*)(b + parts[7].off);
   d.blob = blob; d.blob_bytes = total; d.device = dev;
   return TW_OK;
 }
@@ -130,6 +131,7 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
   g.vals = (const _Float16*)h->img.d_vals;
   g.row_idx = h->img.d_row_idx; g.tile_kp_off = h->img.d_tile_kp_off;
   g.col_idx = h->img.d_col_idx; g.tile_order = h->img.d_tile_order;
+  g.tile_sched = h->img.d_tile_sched;
   g.zero_cols = h->img.d_zero_cols; g.n_zero = (int)h->img.zero_cols.size();
   g.meta = h->img.d_meta;
   g.n_tiles = h->n_tiles; g.K = h->K; g.N = h->N; g.xcd_map = opt_xcd_map.load();
@@ -203,7 +205,7 @@ tw_status tw_set_option(const char* name, int value) {
   if (!std::strcmp(name, "tile_m")) { opt_tile_m.store(value); return TW_OK; }
   if (!std::strcmp(name, "xcd_map")) { opt_xcd_map.store(value != 0); return TW_OK; }
   if (!std::strcmp(name, "kernel")) { opt_kernel.store(value); return TW_OK; }
-  if (!std::strcmp(name, "depth")) { opt_depth.store(value == 3 ? 3 : 4); return TW_OK; }
+  if (!std::strcmp(name, "depth")) { opt_depth.store(value == 4 ? 4 : 3); return TW_OK; }
   return TW_ERR_ARG;
 }
 

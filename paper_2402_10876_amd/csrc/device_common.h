@@ -21,9 +21,9 @@ constexpr int KS = 32;        // condensed rows per main-loop stage
 constexpr int NTHREADS = 256;
 
 // Developer build only (-DTWG_TRACE): wave 0 of the first workgroups records
-// shader-clock timestamps at the phase boundaries of the main loop.
+// constant-rate (100 MHz) timestamps at the phase boundaries of the main loop.
 #ifdef TWG_TRACE
-constexpr int TRACE_WGS = 64, TRACE_SLOTS = 256;
+constexpr int TRACE_WGS = 2048, TRACE_SLOTS = 48;
 static __device__ unsigned long long twg_trace[TRACE_WGS * TRACE_SLOTS];  // one per source file
 #define TWG_TRACE_INIT()                                         \
   const bool trace_on = threadIdx.x == 0 && blockIdx.x < TRACE_WGS; \
@@ -31,7 +31,7 @@ static __device__ unsigned long long twg_trace[TRACE_WGS * TRACE_SLOTS];  // one
 #define TWG_STAMP()                                                                   \
   do {                                                                                \
     if (trace_on && trace_n < TRACE_SLOTS)                                            \
-      twg_trace[blockIdx.x * TRACE_SLOTS + trace_n++] = __builtin_readcyclecounter(); \
+      twg_trace[blockIdx.x * TRACE_SLOTS + trace_n++] = __builtin_amdgcn_s_memrealtime(); \
   } while (0)
 #else
 #define TWG_TRACE_INIT() do {} while (0)

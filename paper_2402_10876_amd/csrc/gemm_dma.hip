@@ -64,6 +64,14 @@ __device__ __forceinline__ void wait_lds(Frag* f) {
   else static_assert(N == 2, "unsupported fragment count");
 }
 
+// Wave-uniform 16-byte record through the scalar cache, complete on return.
+typedef int int4v __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ int4v scalar_load4(const void* p) {
+  int4v r;
+  asm volatile("s_load_dwordx4 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(r) : "s"(p));
+  return r;
+}
+
 template <int N>
 __device__ __forceinline__ void wait_vm() {
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
@@ -102,13 +110,15 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_dma_kernel(GemmArgs g) {
   }
   const int lid = g.xcd_map ? xcd_remap(blockIdx.x, n_gemm) : (int)blockIdx.x;
   const int mt = lid / g.n_tiles;
-  int t = lid - mt * g.n_tiles;
-  if (!DENSE && g.tile_order) t = g.tile_order[t];
+  int t = lid - mt * g.n_tiles;          // launch position of the tile, then the tile itself
   const int m0 = mt * TM;
 
   int kp0, ns;
   if constexpr (DENSE) { kp0 = 0; ns = g.K / KS; }     // host guarantees K % KS == 0
-  else { kp0 = g.tile_kp_off[t]; ns = (g.tile_kp_off[t + 1] - kp0) / KS; }
+  else {
+    const int4v rec = scalar_load4(g.tile_sched + 4 * t);
+    t = rec[0]; kp0 = rec[1]; ns = rec[2] / KS;
+  }
   const _Float16* Bt = DENSE ? g.vals + (size_t)t * TN : g.vals + (size_t)kp0 * TN;
   const int ldb = DENSE ? g.ldb : TN;
 
@@ -166,6 +176,12 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_dma_kernel(GemmArgs g) {
   auto issue = [&](int s) {        // uses rows_next (stage s), then prefetches stage s+1's
     char* dstA = lds + (s % D) * STAGE;
     char* dstB = dstA + STAGE_A;
+#pragma unroll
+    for (int j = 0; j < NIB; ++j) {       // the weight block needs no index list: first
+      const int row = s * KS + (wave * NIB + j) * RPIB + b_rloc;
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(Bt + (size_t)row * ldb + b_el[j]),
+                                       LDS_PTR(void, dstB + (wave * NIB + j) * 1024), 16, 0, 0);
+    }
     if constexpr (!DENSE) {
       // scalar loads return out of order: full wait, tied to the registers
       if constexpr (NIA == 1) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(rows_next[0]));
@@ -183,12 +199,6 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_dma_kernel(GemmArgs g) {
       }
       __builtin_amdgcn_global_load_lds(GLOBAL_PTR(Abase + (size_t)row * g.lda + a_el[j]),
                                        LDS_PTR(void, dstA + (wave * NIA + j) * 1024), 16, 0, 0);
-    }
-#pragma unroll
-    for (int j = 0; j < NIB; ++j) {
-      const int row = s * KS + (wave * NIB + j) * RPIB + b_rloc;
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(Bt + (size_t)row * ldb + b_el[j]),
-                                       LDS_PTR(void, dstB + (wave * NIB + j) * 1024), 16, 0, 0);
     }
     fetch_rows(s + 1 < ns ? s + 1 : ns - 1);
   };
@@ -255,10 +265,12 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_dma_kernel(GemmArgs g) {
     else wait_vm<0>();
     // everybody's copies of stage s have landed, everybody is done reading stage s-1
     asm volatile("s_barrier" ::: "memory");
-    if (s + D - 1 < ns) issue(s + D - 1);
     const uint32_t boff = (uint32_t)((s % D) * STAGE);
     read_step(boff, K0{}, f0);
     if (s > 0) mfma_step(f1);            // second k-step of the previous stage
+    // the copies of stage s+D-1 go into the buffer of stage s-1, which every wave
+    // has finished reading; their address arithmetic hides behind the LDS reads
+    if (s + D - 1 < ns) issue(s + D - 1);
     wait_lds<NF>(f0);
     read_step(boff, K16{}, f1);
     mfma_step(f0);
@@ -291,16 +303,22 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_dma_kernel(GemmArgs g) {
     }
   __syncthreads();
   TWG_STAMP();
+  // all staged chunks into registers first, then the stores back to back
+  union Chunk { uint2 h[2]; u32x4 v; };   // staging rows are 8-byte aligned only
+  Chunk ck[NPASS];
 #pragma unroll
   for (int i = 0; i < NPASS; ++i) {
     const int n = r0 + i * ROWS_PER_PASS;
+    ck[i].h[0] = *(const uint2*)(lds + n * CS + c * 16);
+    ck[i].h[1] = *(const uint2*)(lds + n * CS + c * 16 + 8);
+  }
+#pragma unroll
+  for (int i = 0; i < NPASS; ++i) {
     if (dst_off[i] < 0) continue;
-    union { uint2 h[2]; u32x4 v; } u;   // staging rows are 8-byte aligned only
-    u.h[0] = *(const uint2*)(lds + n * CS + c * 16);
-    u.h[1] = *(const uint2*)(lds + n * CS + c * 16 + 8);
     _Float16* dst = g.C + dst_off[i];
-    if (m + 8 <= g.M) *(u32x4*)dst = u.v;
+    if (m + 8 <= g.M) *(u32x4*)dst = ck[i].v;
     else {
+      const int n = r0 + i * ROWS_PER_PASS;
       const _Float16* e = (const _Float16*)(lds + n * CS + c * 16);
       for (int qq = 0; m + qq < g.M; ++qq) dst[qq] = e[qq];
     }

@@ -16,6 +16,7 @@ struct GemmArgs {
   const int32_t* tile_kp_off;    // TW: n_tiles+1 offsets into row_idx
   const int32_t* col_idx;        // TW: n_tiles*G kept-column indices, -1 = none (CTO_n)
   const int32_t* tile_order;     // TW: launch order of tiles (longest first) or null
+  const int32_t* tile_sched;     // TW: per launch position {tile, kp offset, Kp_t, width}, 16-byte records
   const int32_t* zero_cols;      // pruned columns of C, written as +0
   const uint32_t* meta;          // TVW: 2:4 position words
   int n_zero;

@@ -242,6 +242,14 @@ void build_device_image(tw_handle_s* h) {
   std::stable_sort(d.tile_order.begin(), d.tile_order.end(), [&](int a, int b) {
     return h->tile_k_off[a + 1] - h->tile_k_off[a] > h->tile_k_off[b + 1] - h->tile_k_off[b];
   });
+  d.tile_sched.resize((size_t)nt * 4);
+  for (int pos = 0; pos < nt; ++pos) {
+    const int t = d.tile_order[pos];
+    d.tile_sched[4 * pos + 0] = t;
+    d.tile_sched[4 * pos + 1] = d.tile_kp_off[t];
+    d.tile_sched[4 * pos + 2] = d.tile_kp_off[t + 1] - d.tile_kp_off[t];
+    d.tile_sched[4 * pos + 3] = std::min(G, h->n_kept - t * G);
+  }
   if (!tvw) {
     d.vals.assign((size_t)d.tile_kp_off[nt] * G, 0);
     for (int t = 0; t < nt; ++t) {

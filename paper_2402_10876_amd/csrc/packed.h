@@ -22,6 +22,7 @@ struct DeviceImage {
   std::vector<int32_t> row_idx;      // sum Kp_t; pads repeat the tile's last kept row (0 if none)
   std::vector<int32_t> zero_cols;    // original indices of pruned columns
   std::vector<int32_t> tile_order;   // tiles by descending K_t (longest first)
+  std::vector<int32_t> tile_sched;   // per launch position: {tile, kp offset, Kp_t, width}
   std::vector<uint16_t> vals;        // TW: [sum Kp_t][G]; TVW: swizzled compressed values
   std::vector<uint32_t> meta;        // TVW: swizzled 2-bit position words
   // device copies (one allocation, sub-pointers)
@@ -33,6 +34,7 @@ struct DeviceImage {
   const int32_t* d_row_idx = nullptr;
   const int32_t* d_zero_cols = nullptr;
   const int32_t* d_tile_order = nullptr;
+  const int32_t* d_tile_sched = nullptr;
   const uint16_t* d_vals = nullptr;
   const uint32_t* d_meta = nullptr;
 };
