@@ -125,7 +125,6 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
     return TW_ERR_UNSUPPORTED;
   }
   if (lda < M || ldc < M) return TW_ERR_ARG;
-  if (h->pattern == TW_PATTERN_TVW) return TW_ERR_UNSUPPORTED;
   twg::GemmArgs g{};
   g.A = (const _Float16*)A; g.C = (_Float16*)C; g.M = M; g.lda = lda; g.ldc = ldc;
   g.vals = (const _Float16*)h->img.d_vals;
@@ -135,6 +134,11 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
   g.zero_cols = h->img.d_zero_cols; g.n_zero = (int)h->img.zero_cols.size();
   g.meta = h->img.d_meta;
   g.n_tiles = h->n_tiles; g.K = h->K; g.N = h->N; g.xcd_map = opt_xcd_map.load();
+  if (h->pattern == TW_PATTERN_TVW) {
+    hipError_t e = twg::launch_tvw_km(h->G, 128, opt_depth.load(), g, (hipStream_t)stream);
+    if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
+    return e == hipSuccess ? TW_OK : TW_ERR_HIP;
+  }
   const int tm = pick_tile_m(M, h->n_tiles > 0 ? h->n_tiles : 1, h->G);
   hipError_t e = hipErrorInvalidValue;
   if (opt_kernel.load() != 1 && h->G != 32)

@@ -33,5 +33,7 @@ hipError_t launch_dense_km(int tn, int tm, GemmArgs g, hipStream_t stream);
 // in flight (3 or 4); the dense variant needs K % 32 == 0.
 hipError_t launch_tw_km_dma(int G, int tm, int depth, GemmArgs g, hipStream_t stream);
 hipError_t launch_dense_km_dma(int tn, int tm, int depth, GemmArgs g, hipStream_t stream);
+// TVW (2:4 inside the kept rows) on the sparse matrix instruction (gemm_tvw.hip).
+hipError_t launch_tvw_km(int G, int tm, int depth, GemmArgs g, hipStream_t stream);
 
 }  // namespace twg
