@@ -1,16 +1,18 @@
 #!/usr/bin/env python3
-"""Benchmark of the TW sparse GEMM hot path on one MI355X.
+"""Benchmark of the TW / TVW sparse GEMM hot path on one MI355X.
 
 A step = the six linear-layer GEMMs of one BERT-base encoder layer at batch 32 x
 sequence 128 (M = 4096): four 768x768 (Q, K, V, output), 768x3072 (FFN1) and
-3072x768 (FFN2), weights pruned tile-wise to 75 % (G = 128, 10 % of the columns
-plus magnitude-scored rows per tile), synthetic seeded data.  Each step works on
-its own set of activations, outputs and packed weights out of `--sets` rotating
-sets (12 = one per encoder layer, about 1.4 GB in total), so operands come from
-HBM rather than from the 256 MB last-level cache.
+3072x768 (FFN2), with synthetic seeded weights pruned tile-wise (G = 128):
+  --pattern tw  : 75 % sparsity, 10 % of the columns plus magnitude-scored rows
+                  per tile (the default, the configuration the metric is quoted on)
+  --pattern tvw : the same tile-wise part plus 2:4 along the kept rows, 87.5 %
+Each step works on its own set of activations, outputs and packed weights out of
+`--sets` rotating sets (12 = one per encoder layer, about 1.4 GB in total), so
+operands come from HBM rather than from the 256 MB last-level cache.
 
 Prints ONE JSON line: dense-equivalent TFLOP/s of the whole step, plus
-`roofline` (dominant kernel = the FFN1-shaped launch, HBM-bound) and
+`roofline` (the grouped GEMM kernel, HBM-bound at this sparsity) and
 `cpu_baseline` (the fp64 oracle timed on the host cores).
 """
 from __future__ import annotations
@@ -28,19 +30,15 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 FP16_PEAK_TFLOPS = 2500.0
+PLAN = [(0, 4), (1, 1), (2, 1)]          # (shape index in the config, copies per layer)
 
 
-def layer_shapes():
-    import workloads as wl
-    s = wl.SHAPES[2]
-    # (shape_index, copies per layer)
-    return [(0, 4), (1, 1), (2, 1)], s
-
-
-def algorithmic_bytes(M, K, N, sum_kw, sum_k):
-    """Bytes one TW launch must move: A once, all of C (pruned columns are
-    written as zeros), the condensed weight with its row index list."""
-    return 2 * M * K + 2 * M * N + 2 * sum_kw + 4 * sum_k
+def algorithmic_bytes(M, K, N, pattern, sum_kw, sum_k):
+    """Bytes one launch must move: A once, all of C (pruned columns are written
+    as zeros), the condensed weight (TVW: half the values plus 4 position bits
+    per group and column) and its kept-row list."""
+    w = 2 * sum_kw if pattern == "tw" else sum_kw + sum_kw // 8
+    return 2 * M * K + 2 * M * N + w + 4 * sum_k
 
 
 def main():
@@ -49,9 +47,11 @@ def main():
     ap.add_argument("--steps", type=int, default=240)
     ap.add_argument("--warmup", type=int, default=24)
     ap.add_argument("--sets", type=int, default=12)
-    ap.add_argument("--pattern", default="tw", choices=["tw"])
+    ap.add_argument("--pattern", default="tw", choices=["tw", "tvw"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run plain device copies of 256 MiB (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (--gpus must be 1)",
@@ -64,118 +64,136 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
-    plan, shapes = layer_shapes()
+    cfg = 2 if args.pattern == "tw" else 3
+    shapes = wl.SHAPES[cfg]
     M = shapes[0].M
     stream = torch.cuda.current_stream().cuda_stream
+    pat = tw.PATTERN_TW if args.pattern == "tw" else tw.PATTERN_TVW
 
-    # ---- build the rotating sets: packed weights, A^T, C^T ------------------
+    # ---- rotating sets: packed weights, A^T, C^T ----------------------------
     t_pack = 0.0
-    sets = []
-    meta = {}
+    sets, meta, case_cache = [], {}, {}
     gen = torch.Generator(device="cpu").manual_seed(1234)
-    case_cache = {}
     for s in range(args.sets):
         ops = []
-        for si, copies in plan:
+        for si, copies in PLAN:
             shp = shapes[si]
             for cidx in range(copies):
                 variant = (s * 4 + cidx) % 10
                 if (si, variant) not in case_cache:
-                    case_cache[(si, variant)] = wl.make_case(2, si, variant=variant, with_A=False)
+                    case_cache[(si, variant)] = wl.make_case(cfg, si, variant=variant, with_A=False)
                 c = case_cache[(si, variant)]
                 t0 = time.perf_counter()
-                packed = tw.tw_pack(c.B, c.mask, c.G, tw.PATTERN_TW)
+                packed = tw.tw_pack(c.B, c.mask, c.G, pat, tile_mask=c.tile_mask if args.pattern == "tvw" else None)
                 t_pack += time.perf_counter() - t0
                 skw, sk = packed.flop_counts()
-                meta[si] = dict(K=shp.K, N=shp.N, sum_kw=skw, sum_k=sk, name=shp.name)
-                At = (torch.randn((shp.K, M), generator=gen, dtype=torch.float32)).to(torch.float16).to(dev)
+                meta[si] = dict(K=shp.K, N=shp.N, sum_kw=skw, sum_k=sk, name=shp.name,
+                                alg=algorithmic_bytes(M, shp.K, shp.N, args.pattern, skw, sk))
+                At = torch.randn((shp.K, M), generator=gen, dtype=torch.float32).to(torch.float16).to(dev)
                 Ct = torch.empty((shp.N, M), dtype=torch.float16, device=dev)
                 ops.append((si, packed, At, Ct))
         sets.append(ops)
     torch.cuda.synchronize()
 
-    def step(i, ev=None):
-        for si, packed, At, Ct in sets[i % args.sets]:
-            if ev is not None and si == 1:
-                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                e0.record()
-                tw.tw_gemm(At.data_ptr(), M, M, tw.LAYOUT_KM, packed, Ct.data_ptr(), M, stream)
-                e1.record()
-                ev.append((e0, e1))
-            else:
-                tw.tw_gemm(At.data_ptr(), M, M, tw.LAYOUT_KM, packed, Ct.data_ptr(), M, stream)
+    def launch(o):
+        tw.tw_gemm(o[2].data_ptr(), M, M, tw.LAYOUT_KM, o[1], o[3].data_ptr(), M, stream)
 
+    def step(i):
+        for o in sets[i % args.sets]:
+            launch(o)
+
+    # ---- the timed region -------------------------------------------------------
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
-    ev = []
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(i, ev)
+        step(i)
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    sec_per_step = (t1 - t0) / args.steps
-    dom_ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    sec_per_step = (time.perf_counter() - t0) / args.steps
 
-    dense_flops_step = sum(2.0 * M * shapes[si].K * shapes[si].N * copies for si, copies in plan)
-    cond_flops_step = sum(2.0 * M * meta[si]["sum_kw"] * copies for si, copies in plan)
+    # ---- the same steps again, one pair of HIP events around the launches of each
+    # step, recorded on the stream the kernels run on: elapsed / launches is the
+    # average launch duration (back-to-back launches, so the gap between two
+    # kernels is part of it)
+    ev = []
+    for i in range(args.steps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); step(i); e1.record()
+        ev.append((e0, e1))
+    torch.cuda.synchronize()
+    launches = sum(c for _, c in PLAN)
+    avg_launch_ms = float(np.mean([a.elapsed_time(b) for a, b in ev])) / launches
+    alg_per_launch = sum(meta[si]["alg"] * c for si, c in PLAN) / launches
+
+    # ---- per shape: 24 back-to-back launches between two events, rotating sets ----
+    def time_shape(si, fn, reps=24, rounds=5):
+        best = []
+        for _ in range(rounds):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for r in range(reps):
+                fn([x for x in sets[r % args.sets] if x[0] == si][0])
+            e1.record()
+            torch.cuda.synchronize()
+            best.append(e0.elapsed_time(e1) / reps)
+        return float(np.median(best))
+    per_shape_ms = {si: time_shape(si, launch) for si, _ in PLAN}
+
+    dense_flops_step = sum(2.0 * M * shapes[si].K * shapes[si].N * c for si, c in PLAN)
+    cond_flops_step = sum(2.0 * M * meta[si]["sum_kw"] * c for si, c in PLAN)
     value = dense_flops_step / sec_per_step / 1e12
 
-    # ---- per-shape kernel times (events around back-to-back launches, rotating sets)
-    def time_shape(si, fn, reps=60):
-        evs = []
-        for r in range(reps + 10):
-            ops = [o for o in sets[r % args.sets] if o[0] == si]
-            o = ops[0]
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record(); fn(o); e1.record()
-            if r >= 10:
-                evs.append((e0, e1))
-        torch.cuda.synchronize()
-        return float(np.median([a.elapsed_time(b) for a, b in evs])) * 1e-3
-
+    # ---- our own dense MFMA GEMM at the same shapes (outside the timed region) -----
     detail = {}
-    dense_B = {}
-    for si, copies in plan:
+    for si, copies in PLAN:
         shp = shapes[si]
-        t_tw = time_shape(si, lambda o: tw.tw_gemm(o[2].data_ptr(), M, M, tw.LAYOUT_KM, o[1], o[3].data_ptr(), M, stream))
-        d = dict(tw_us=t_tw * 1e6, dense_eq_tflops=2.0 * M * shp.K * shp.N / t_tw / 1e12,
-                 condensed_mfma_util=2.0 * M * meta[si]["sum_kw"] / t_tw / 1e12 / FP16_PEAK_TFLOPS,
-                 alg_GBps=algorithmic_bytes(M, shp.K, shp.N, meta[si]["sum_kw"], meta[si]["sum_k"]) / t_tw / 1e9)
+        t_sp = per_shape_ms[si] * 1e-3
+        d = dict(sparse_us=t_sp * 1e6, dense_eq_tflops=2.0 * M * shp.K * shp.N / t_sp / 1e12,
+                 condensed_mfma_util=2.0 * M * meta[si]["sum_kw"] / t_sp / 1e12 / FP16_PEAK_TFLOPS,
+                 alg_GBps=meta[si]["alg"] / t_sp / 1e9, alg_bytes=meta[si]["alg"])
         if not args.no_dense:
-            Bd = wl.make_B(wl.seed_for(2, si), shp.K, shp.N, shp.sigma)
-            dense_B[si] = torch.from_numpy(Bd).to(dev)
-            t_d = time_shape(si, lambda o: tw.tw_dense_gemm(o[2].data_ptr(), dense_B[si].data_ptr(), o[3].data_ptr(),
-                                                            M, shp.K, shp.N, M, shp.N, M, tw.LAYOUT_KM, stream))
-            d.update(dense_us=t_d * 1e6, dense_tflops=2.0 * M * shp.K * shp.N / t_d / 1e12, speedup_vs_dense=t_d / t_tw)
+            Bd = torch.from_numpy(wl.make_B(wl.seed_for(cfg, si), shp.K, shp.N, shp.sigma)).to(dev)
+            t_d = time_shape(si, lambda o: tw.tw_dense_gemm(o[2].data_ptr(), Bd.data_ptr(), o[3].data_ptr(), M, shp.K,
+                                                            shp.N, M, shp.N, M, tw.LAYOUT_KM, stream)) * 1e-3
+            d.update(dense_us=t_d * 1e6, dense_tflops=2.0 * M * shp.K * shp.N / t_d / 1e12,
+                     speedup_vs_dense=t_d / t_sp)
         detail[shp.name] = d
     if not args.no_dense:
-        t_dense_step = sum(detail[shapes[si].name]["dense_us"] * copies for si, copies in plan)
-        t_tw_step = sum(detail[shapes[si].name]["tw_us"] * copies for si, copies in plan)
-        detail["step_speedup_vs_dense_kernel_sum"] = t_dense_step / t_tw_step
+        detail["step_speedup_vs_own_dense"] = (
+            sum(detail[shapes[si].name]["dense_us"] * c for si, c in PLAN) /
+            sum(detail[shapes[si].name]["sparse_us"] * c for si, c in PLAN))
 
-    m1 = meta[1]
-    alg = algorithmic_bytes(M, m1["K"], m1["N"], m1["sum_kw"], m1["sum_k"])
-    achieved = alg / (dom_ms * 1e-3) / 1e9
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+
+    achieved = alg_per_launch / (avg_launch_ms * 1e-3) / 1e9
+    kern = "tw_gemm_km_dma_kernel" if args.pattern == "tw" else "tvw_gemm_km_kernel"
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=achieved / HBM_PEAK_GBS, traffic=None,
-                    kernel="tw_gemm_km_kernel (bert_base_ffn1, TW 75 %)",
-                    avg_launch_us=dom_ms * 1e3, algorithmic_bytes=alg)
+                    kernel=f"{kern} (all {launches} launches of a step; the step runs nothing else)",
+                    avg_launch_us=avg_launch_ms * 1e3, algorithmic_bytes_per_launch=alg_per_launch)
 
-    out = dict(metric="TW sparse GEMM effective (dense-equivalent) TFLOP/s, BERT-base layer at 75 % sparsity",
+    out = dict(metric=f"{args.pattern.upper()} sparse GEMM effective (dense-equivalent) TFLOP/s, BERT-base layer",
                value=value, unit="TFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
                ms_per_step=sec_per_step * 1e3, higher_is_better=True, scaling="weak",
                vs_baseline=None, dtype="f16", data="synthetic",
-               config=dict(workload="BERT-base linear layers as TW GEMM (config 2): M=4096, 4x 768x768 + 768x3072 + 3072x768, "
-                                    "G=128, 75 % sparsity (10 % columns + per-tile rows), layout K x M / N x M",
-                           sets=args.sets, pattern="tw"),
+               config=dict(workload=f"BERT-base linear layers as {args.pattern.upper()} GEMM (config {cfg}): M=4096, "
+                                    "4x 768x768 + 768x3072 + 3072x768, G=128, "
+                                    + ("75 % sparsity (10 % columns + per-tile rows)" if args.pattern == "tw" else
+                                       "87.5 % sparsity (tile-wise 75 % + 2:4)") + ", layout K x M / N x M",
+                           sets=args.sets, pattern=args.pattern),
                condensed_flop_mfma_util=cond_flops_step / sec_per_step / 1e12 / FP16_PEAK_TFLOPS,
-               pack_seconds_per_weight=t_pack / (args.sets * 6),
+               pack_seconds_per_weight=t_pack / (args.sets * launches),
                roofline=roofline, detail=detail)
 
     if not args.no_cpu_baseline:
         from oracle import gemm as og
-        cases = [(wl.make_case(2, si), copies) for si, copies in plan]
+        cases = [(wl.make_case(cfg, si), copies) for si, copies in PLAN]
         reps = []
         for _ in range(3):
             t0 = time.perf_counter()

@@ -122,9 +122,10 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
   if (!h->img.blob) return TW_ERR_STATE;
   if (layout == TW_LAYOUT_MK) {
     if (lda < h->K || ldc < h->N) return TW_ERR_ARG;
-    return TW_ERR_UNSUPPORTED;
+    if (h->pattern == TW_PATTERN_TVW) return TW_ERR_UNSUPPORTED;   // TVW exists for K x M only
+  } else if (lda < M || ldc < M) {
+    return TW_ERR_ARG;
   }
-  if (lda < M || ldc < M) return TW_ERR_ARG;
   twg::GemmArgs g{};
   g.A = (const _Float16*)A; g.C = (_Float16*)C; g.M = M; g.lda = lda; g.ldc = ldc;
   g.vals = (const _Float16*)h->img.d_vals;
@@ -134,6 +135,11 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
   g.zero_cols = h->img.d_zero_cols; g.n_zero = (int)h->img.zero_cols.size();
   g.meta = h->img.d_meta;
   g.n_tiles = h->n_tiles; g.K = h->K; g.N = h->N; g.xcd_map = opt_xcd_map.load();
+  if (layout == TW_LAYOUT_MK) {
+    hipError_t e = twg::launch_tw_mk(h->G, g, (hipStream_t)stream);
+    if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
+    return e == hipSuccess ? TW_OK : TW_ERR_HIP;
+  }
   if (h->pattern == TW_PATTERN_TVW) {
     hipError_t e = twg::launch_tvw_km(h->G, 128, opt_depth.load(), g, (hipStream_t)stream);
     if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
@@ -158,15 +164,19 @@ tw_status tw_dense_gemm(const void* A, const void* B, void* C, int M, int K, int
   if (ldb < N) return TW_ERR_ARG;
   if (layout == TW_LAYOUT_MK) {
     if (lda < K || ldc < N) return TW_ERR_ARG;
-    return TW_ERR_UNSUPPORTED;
+  } else if (lda < M || ldc < M) {
+    return TW_ERR_ARG;
   }
-  if (lda < M || ldc < M) return TW_ERR_ARG;
   twg::GemmArgs g{};
   g.A = (const _Float16*)A; g.C = (_Float16*)C; g.M = M; g.lda = lda; g.ldc = ldc;
   g.vals = (const _Float16*)B; g.ldb = ldb; g.K = K; g.N = N;
   const int tn = 128;
   g.n_tiles = (N + tn - 1) / tn;
   g.xcd_map = opt_xcd_map.load();
+  if (layout == TW_LAYOUT_MK) {
+    hipError_t em = twg::launch_dense_mk(tn, g, (hipStream_t)stream);
+    return em == hipSuccess ? TW_OK : TW_ERR_HIP;
+  }
   const int tm = pick_tile_m(M, g.n_tiles, tn);
   hipError_t e = hipErrorInvalidValue;
   if (opt_kernel.load() != 1 && K % 32 == 0)

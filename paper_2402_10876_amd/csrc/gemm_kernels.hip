@@ -38,7 +38,12 @@ __device__ __forceinline__ half8 lds_operand(const char* tile, int x0, int k0, i
   return u.h;
 }
 
-template <int TM, int TN, int WAVES_M, bool DENSE>
+// MK = true: A is M x K and C is M x N, both row-major (the layout Section V
+// calls uncoalesced once rows are pruned).  Only the global accesses differ:
+// the gather reads single halves A[m][row_idx[k]] and the scatter writes single
+// halves C[m][col_idx[n]]; LDS tiles, MFMA feeding and staging are unchanged.
+// It is a compatibility path and is not tuned.
+template <int TM, int TN, int WAVES_M, bool DENSE, bool MK>
 __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
   constexpr int WAVES_N = 4 / WAVES_M;
   constexpr int WM = TM / WAVES_M, WN = TN / WAVES_N;
@@ -62,7 +67,12 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
 
   // ---- extra workgroups: +0 into the pruned columns of C -----------------
   if ((int)blockIdx.x >= n_gemm) {
-    zero_fill_column(g, blockIdx.x - n_gemm);
+    if constexpr (MK) {
+      const int col = g.zero_cols[blockIdx.x - n_gemm];
+      for (int i = tid; i < g.M; i += NTHREADS) g.C[(size_t)i * g.ldc + col] = (_Float16)0.f;
+    } else {
+      zero_fill_column(g, blockIdx.x - n_gemm);
+    }
     return;
   }
 
@@ -116,7 +126,18 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
   auto load_stage = [&](int s, const int* idx, u32x4* pa, u32x4* pb) {
 #pragma unroll
     for (int i = 0; i < NA; ++i)
-      pa[i] = *(const u32x4*)(g.A + (size_t)idx[i] * g.lda + m0 + a_c[i] * 8);
+      if constexpr (MK) {
+        union { _Float16 e[8]; u32x4 v; } u;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          int mm = m0 + a_c[i] * 8 + q;
+          if (mm >= g.M) mm = g.M - 1;
+          u.e[q] = g.A[(size_t)mm * g.lda + idx[i]];
+        }
+        pa[i] = u.v;
+      } else {
+        pa[i] = *(const u32x4*)(g.A + (size_t)idx[i] * g.lda + m0 + a_c[i] * 8);
+      }
 #pragma unroll
     for (int i = 0; i < NBK; ++i) {
       if constexpr (DENSE) {
@@ -266,22 +287,27 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
     union { uint2 h[2]; u32x4 v; } u;
     u.h[0] = *(const uint2*)(lds + n * CS + c * 16);
     u.h[1] = *(const uint2*)(lds + n * CS + c * 16 + 8);
-    _Float16* dst = g.C + dst_off[i];
-    if (m + 8 <= g.M) *(u32x4*)dst = u.v;
-    else {
-      const _Float16* e = (const _Float16*)(lds + n * CS + c * 16);
-      for (int q = 0; m + q < g.M; ++q) dst[q] = e[q];
+    if constexpr (MK) {
+      const _Float16* e = (const _Float16*)&u;
+      for (int q = 0; q < 8 && m + q < g.M; ++q) g.C[(size_t)(m + q) * g.ldc + cols[i]] = e[q];
+    } else {
+      _Float16* dst = g.C + dst_off[i];
+      if (m + 8 <= g.M) *(u32x4*)dst = u.v;
+      else {
+        const _Float16* e = (const _Float16*)(lds + n * CS + c * 16);
+        for (int q = 0; m + q < g.M; ++q) dst[q] = e[q];
+      }
     }
   }
   TWG_STAMP();
 }
 
-template <int TM, int TN, int WAVES_M, bool DENSE>
+template <int TM, int TN, int WAVES_M, bool DENSE, bool MK>
 static hipError_t launch(const GemmArgs& g, hipStream_t stream) {
   const int grid = g.n_mtiles * g.n_tiles + g.n_zero;
   if (grid <= 0) return hipSuccess;
-  hipLaunchKernelGGL((tw_gemm_km_kernel<TM, TN, WAVES_M, DENSE>), dim3(grid), dim3(NTHREADS), 0,
-                     stream, g);
+  hipLaunchKernelGGL((tw_gemm_km_kernel<TM, TN, WAVES_M, DENSE, MK>), dim3(grid), dim3(NTHREADS),
+                     0, stream, g);
   return hipGetLastError();
 }
 
@@ -289,11 +315,20 @@ template <bool DENSE>
 static hipError_t dispatch(int G, int tm, GemmArgs& g, hipStream_t stream) {
   g.n_mtiles = (g.M + tm - 1) / tm;
 #define TWG_CASE(TM_, TN_, WM_) \
-  if (G == TN_ && tm == TM_) return launch<TM_, TN_, WM_, DENSE>(g, stream);
+  if (G == TN_ && tm == TM_) return launch<TM_, TN_, WM_, DENSE, false>(g, stream);
   TWG_CASE(64, 128, 1) TWG_CASE(128, 128, 2) TWG_CASE(256, 128, 2)
   TWG_CASE(64, 64, 2) TWG_CASE(128, 64, 2) TWG_CASE(256, 64, 4)
   TWG_CASE(128, 32, 4) TWG_CASE(256, 32, 4)
 #undef TWG_CASE
+  return hipErrorInvalidValue;
+}
+
+template <bool DENSE>
+static hipError_t dispatch_mk(int G, GemmArgs& g, hipStream_t stream) {
+  g.n_mtiles = (g.M + 127) / 128;
+  if (G == 128) return launch<128, 128, 2, DENSE, true>(g, stream);
+  if (G == 64) return launch<128, 64, 2, DENSE, true>(g, stream);
+  if (G == 32) return launch<128, 32, 4, DENSE, true>(g, stream);
   return hipErrorInvalidValue;
 }
 
@@ -309,5 +344,7 @@ hipError_t launch_tw_km(int G, int tm, GemmArgs g, hipStream_t stream) {
 hipError_t launch_dense_km(int tn, int tm, GemmArgs g, hipStream_t stream) {
   return dispatch<true>(tn, tm, g, stream);
 }
+hipError_t launch_tw_mk(int G, GemmArgs g, hipStream_t stream) { return dispatch_mk<false>(G, g, stream); }
+hipError_t launch_dense_mk(int tn, GemmArgs g, hipStream_t stream) { return dispatch_mk<true>(tn, g, stream); }
 
 }  // namespace twg

@@ -78,7 +78,7 @@ __global__ __launch_bounds__(NTHREADS) void tvw_gemm_km_kernel(GemmArgs g) {
   constexpr int WAVES_M = 4 / WAVES_N;
   constexpr int WN = TN / WAVES_N, WM = TM / WAVES_M;
   constexpr int NB = WN / 32, MB = WM / 32;
-  static_assert(NB == 2 && MB == 2, "this instance list keeps 64 x 64 wave tiles");
+  static_assert(NB == 2 && (MB == 1 || MB == 2), "wave tiles are 64 columns by 32 or 64 rows of C^T");
   constexpr int NBT = TN / 32;                           // column blocks of the tile
   constexpr int RBA = TM * 2;
   constexpr int STAGE_A = KS2 * RBA;                     // gathered A rows
@@ -209,10 +209,15 @@ __global__ __launch_bounds__(NTHREADS) void tvw_gemm_km_kernel(GemmArgs g) {
     for (int i = 0; i < NB; ++i) f.v[i] = lds_read128<U * NBT * 1024>(fv[i] + boff);
   };
   auto wait_step = [&](Step& f) {
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(f.d[0].q[0]), "+v"(f.d[0].q[1]), "+v"(f.d[0].q[2]), "+v"(f.d[0].q[3]),
-                   "+v"(f.d[1].q[0]), "+v"(f.d[1].q[1]), "+v"(f.d[1].q[2]), "+v"(f.d[1].q[3]),
-                   "+v"(f.v[0]), "+v"(f.v[1]), "+v"(idx[0]), "+v"(idx[1]));
+    if constexpr (MB == 2)
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(f.d[0].q[0]), "+v"(f.d[0].q[1]), "+v"(f.d[0].q[2]), "+v"(f.d[0].q[3]),
+                     "+v"(f.d[1].q[0]), "+v"(f.d[1].q[1]), "+v"(f.d[1].q[2]), "+v"(f.d[1].q[3]),
+                     "+v"(f.v[0]), "+v"(f.v[1]), "+v"(idx[0]), "+v"(idx[1]));
+    else
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(f.d[0].q[0]), "+v"(f.d[0].q[1]), "+v"(f.d[0].q[2]), "+v"(f.d[0].q[3]),
+                     "+v"(f.v[0]), "+v"(f.v[1]), "+v"(idx[0]), "+v"(idx[1]));
   };
   auto smfmac_step = [&](auto U_, const Step& f, const int* ix) {
     constexpr int U = decltype(U_)::value;
@@ -308,6 +313,8 @@ hipError_t launch_tvw_km(int G, int tm, int depth, GemmArgs g, hipStream_t strea
   g.n_mtiles = (g.M + tm - 1) / tm;
   if (G == 128 && tm == 128 && depth == 3) return launch<128, 128, 2, 3>(g, stream);
   if (G == 128 && tm == 128 && depth == 4) return launch<128, 128, 2, 4>(g, stream);
+  if (G == 64 && tm == 128 && depth == 3) return launch<128, 64, 1, 3>(g, stream);
+  if (G == 64 && tm == 128 && depth == 4) return launch<128, 64, 1, 4>(g, stream);
   return hipErrorInvalidValue;
 }
 

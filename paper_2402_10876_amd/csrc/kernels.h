@@ -6,8 +6,8 @@
 namespace twg {
 
 struct GemmArgs {
-  const _Float16* A;   // K x M, element (i,k) at A[k*lda + i]
-  _Float16* C;         // N x M, element (i,n) at C[n*ldc + i]
+  const _Float16* A;   // KM kernels: K x M, element (i,k) at A[k*lda + i]; MK: A[i*lda + k]
+  _Float16* C;         // KM kernels: N x M, element (i,n) at C[n*ldc + i]; MK: C[i*ldc + n]
   int M, lda, ldc;
   // TW: condensed weight image [sum Kp_t][G]; dense: B, K x N row-major
   const _Float16* vals;
@@ -29,6 +29,9 @@ struct GemmArgs {
 // hipErrorInvalidValue when no instance exists for (G, tm).
 hipError_t launch_tw_km(int G, int tm, GemmArgs g, hipStream_t stream);
 hipError_t launch_dense_km(int tn, int tm, GemmArgs g, hipStream_t stream);
+// Row-major A (M x K) and C (M x N): compatibility path on the register-staged kernel.
+hipError_t launch_tw_mk(int G, GemmArgs g, hipStream_t stream);
+hipError_t launch_dense_mk(int tn, GemmArgs g, hipStream_t stream);
 // Asynchronous-copy pipeline (gemm_dma.hip): G / tn in {64, 128}, depth = stages
 // in flight (3 or 4); the dense variant needs K % 32 == 0.
 hipError_t launch_tw_km_dma(int G, int tm, int depth, GemmArgs g, hipStream_t stream);

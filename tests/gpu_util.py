@@ -52,3 +52,35 @@ def run_dense(tw, A16, B16, *, lda=None, ldb=None, ldc=None):
     torch.cuda.synchronize()
     raw = Ct.cpu().numpy()
     return raw[:, :M].T.astype(np.float64), raw
+
+
+def run_tw_mk(tw, packed, A16, N, *, lda=None, ldc=None, fill=float("nan")):
+    """Row-major layout: A is M x lda, C is M x ldc."""
+    torch = _torch()
+    M, K = A16.shape
+    lda = lda or (K + 7) // 8 * 8
+    ldc = ldc or (N + 7) // 8 * 8
+    Ap = np.full((M, lda), np.nan, np.float16)
+    Ap[:, :K] = A16
+    Ad = torch.from_numpy(Ap).cuda()
+    Cd = torch.full((M, ldc), fill, dtype=torch.float16, device="cuda")
+    tw.tw_gemm(Ad.data_ptr(), M, lda, tw.LAYOUT_MK, packed, Cd.data_ptr(), ldc,
+               torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    raw = Cd.cpu().numpy()
+    return raw[:, :N].astype(np.float64), raw
+
+
+def run_dense_mk(tw, A16, B16):
+    torch = _torch()
+    M, K = A16.shape
+    N = B16.shape[1]
+    lda, ldb, ldc = (K + 7) // 8 * 8, (N + 7) // 8 * 8, (N + 7) // 8 * 8
+    Ap = np.zeros((M, lda), np.float16); Ap[:, :K] = A16
+    Bp = np.zeros((K, ldb), np.float16); Bp[:, :N] = B16
+    Ad, Bd = torch.from_numpy(Ap).cuda(), torch.from_numpy(Bp).cuda()
+    Cd = torch.full((M, ldc), float("nan"), dtype=torch.float16, device="cuda")
+    tw.tw_dense_gemm(Ad.data_ptr(), Bd.data_ptr(), Cd.data_ptr(), M, K, N, lda, ldb, ldc,
+                     tw.LAYOUT_MK, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    return Cd.cpu().numpy()[:, :N].astype(np.float64)

@@ -1,0 +1,137 @@
+"""Row-major compatibility layout, both pipelines, and the remaining configured
+workloads (BERT-large sweep, VGG-16 im2col shapes) against the oracle (-m gpu)."""
+import numpy as np
+import pytest
+
+import paper_2402_10876_amd as tw
+from oracle import gemm as og
+from tests.helpers import assert_C_close, random_tw_mask
+from tests import gpu_util as gu
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _reset_options():
+    for k, v in (("tile_m", 0), ("xcd_map", 1), ("kernel", 0), ("depth", 3)):
+        tw.tw_set_option(k, v)
+    yield
+    for k, v in (("tile_m", 0), ("xcd_map", 1), ("kernel", 0), ("depth", 3)):
+        tw.tw_set_option(k, v)
+
+
+def _oracle(c, rows=None):
+    A = c.A if rows is None else c.A[rows]
+    return og.gemm_oracle(A, c.B, c.mask), og.abs_bound(A, c.B, c.mask)
+
+
+def _pack(c):
+    if c.pattern == "tvw":
+        return tw.tw_pack(c.B, c.mask, c.G, tw.PATTERN_TVW, tile_mask=c.tile_mask)
+    return tw.tw_pack(c.B, c.mask, c.G, tw.PATTERN_TW)
+
+
+@pytest.mark.parametrize("G", [32, 64, 128])
+def test_row_major_layout_tw(G):
+    rng = np.random.default_rng(50 + G)
+    M, K, N = 203, 150, 300
+    mask = random_tw_mask(rng, K, N, G, col_keep=0.8, row_keep=0.5)
+    A, B = wl.make_A(G, M, K), wl.make_B(G, K, N, 1.0)
+    print(f"case row-major G={G}", flush=True)
+    p = tw.tw_pack(B, mask, G, tw.PATTERN_TW)
+    C, raw = gu.run_tw_mk(tw, p, A, N, ldc=312, fill=5.0)
+    p.free()
+    assert_C_close(C, og.gemm_oracle(A, B, mask), og.abs_bound(A, B, mask))
+    assert not raw[:, :N][:, ~mask.any(0)].view(np.uint16).any()
+    assert (raw[:, N:] == 5.0).all()
+
+
+def test_row_major_equals_transposed_layout_bitwise():
+    c = wl.make_case(1, M=200)
+    p = _pack(c)
+    C_mk, _ = gu.run_tw_mk(tw, p, c.A, c.N)
+    tw.tw_set_option("kernel", 1)                 # same register-staged kernel, other layout
+    tw.tw_set_option("tile_m", 128)
+    C_km, _ = gu.run_tw(tw, p, c.A, c.N)
+    p.free()
+    assert np.array_equal(C_mk, C_km)
+
+
+def test_row_major_dense():
+    A, B = wl.make_A(3, 130, 96), wl.make_B(3, 96, 200, 0.1)
+    C = gu.run_dense_mk(tw, A, B)
+    ones = np.ones(B.shape, np.uint8)
+    assert_C_close(C, og.gemm_oracle(A, B, ones), og.abs_bound(A, B, ones))
+
+
+@pytest.mark.parametrize("kernel,depth", [(1, 3), (2, 3), (2, 4)])
+@pytest.mark.parametrize("tile_m", [64, 128, 256])
+def test_both_pipelines_agree_with_oracle(kernel, depth, tile_m):
+    tw.tw_set_option("kernel", kernel); tw.tw_set_option("depth", depth); tw.tw_set_option("tile_m", tile_m)
+    c = wl.make_case(2, 0, M=520, recipe="global")
+    print(f"case {c.name} kernel={kernel} depth={depth} tile_m={tile_m}", flush=True)
+    p = _pack(c)
+    C, _ = gu.run_tw(tw, p, c.A, c.N)
+    p.free()
+    ref, S = _oracle(c)
+    assert_C_close(C, ref, S)
+    # dense baseline on the same pipeline
+    Cd, _ = gu.run_dense(tw, c.A, c.B)
+    ones = np.ones_like(c.mask)
+    assert_C_close(Cd, og.gemm_oracle(c.A, c.B, ones), og.abs_bound(c.A, c.B, ones))
+
+
+@pytest.mark.parametrize("pattern,sparsity", [("tw", 0.0), ("tw", 0.5), ("tw", 0.75), ("tw", 0.875), ("tw", 0.9375),
+                                              ("tvw", 0.5), ("tvw", 0.75), ("tvw", 0.875), ("tvw", 0.9375)])
+@pytest.mark.parametrize("shape_index", [0, 1])
+def test_config4_bert_large_sweep_reduced_M(shape_index, pattern, sparsity):
+    cf = 0.0 if sparsity in (0.0,) or (pattern == "tvw" and sparsity == 0.5) else None
+    c = wl.make_case(4, shape_index, pattern=pattern, sparsity=sparsity, col_frac=cf, M=384)
+    print(f"case {c.name}", flush=True)
+    p = _pack(c)
+    C, _ = gu.run_tw(tw, p, c.A, c.N)
+    p.free()
+    ref, S = _oracle(c)
+    assert_C_close(C, ref, S)
+    if sparsity == 0.0:                           # 0 % is the dense GEMM
+        Cd, _ = gu.run_dense(tw, c.A, c.B)
+        assert_C_close(Cd, ref, S)
+
+
+def test_config4_full_size_sampled():
+    c = wl.make_case(4, 0)                       # M = 8192, 1024 x 4096, TW 75 %
+    print(f"case {c.name}", flush=True)
+    p = _pack(c)
+    C, raw = gu.run_tw(tw, p, c.A, c.N)
+    p.free()
+    rows = np.r_[0:8, 4090:4100, c.M - 8:c.M, np.arange(5, c.M, 511)]
+    ref, S = _oracle(c, rows)
+    assert_C_close(C[rows], ref, S)
+    assert np.isfinite(C).all() and not raw[~c.mask.any(0)].view(np.uint16).any()
+
+
+@pytest.mark.parametrize("pattern,sparsity,G", [("tw", 0.75, 64), ("tw", 0.75, 128), ("tvw", 0.875, 64), ("tvw", 0.875, 128)])
+def test_config5_vgg_conv_512_full_size(pattern, sparsity, G):
+    c = wl.make_case(5, 1, pattern=pattern, sparsity=sparsity, G=G)      # M = 1568: M tail
+    print(f"case {c.name}", flush=True)
+    p = _pack(c)
+    C, raw = gu.run_tw(tw, p, c.A, c.N)
+    p.free()
+    rows = np.r_[0:8, 1560:1568, np.arange(3, c.M, 97)]
+    ref, S = _oracle(c, rows)
+    assert_C_close(C[rows], ref, S)
+    assert np.isfinite(C).all()
+
+
+@pytest.mark.parametrize("pattern,sparsity,G", [("tw", 0.75, 64), ("tvw", 0.875, 64)])
+def test_config5_vgg_conv_256_full_size_sampled(pattern, sparsity, G):
+    c = wl.make_case(5, 0, pattern=pattern, sparsity=sparsity, G=G)      # M = 25088
+    print(f"case {c.name}", flush=True)
+    p = _pack(c)
+    C, raw = gu.run_tw(tw, p, c.A, c.N)
+    p.free()
+    rows = np.r_[0:8, 25080:25088, np.arange(11, c.M, 1571)]
+    ref, S = _oracle(c, rows)
+    assert_C_close(C[rows], ref, S)
+    assert np.isfinite(C).all()

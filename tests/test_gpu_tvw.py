@@ -38,9 +38,10 @@ def test_every_position_pair_bit_exact():
     assert np.array_equal(raw[:, :K].T.view(np.uint16), want.view(np.uint16))
 
 
-def test_identity_A_random_structure_bit_exact():
-    rng = np.random.default_rng(21)
-    K, N, G = 300, 330, 128
+@pytest.mark.parametrize("G", [64, 128])
+def test_identity_A_random_structure_bit_exact(G):
+    rng = np.random.default_rng(21 + G)
+    K, N = 300, 330
     mask, tm = random_tvw_mask(rng, K, N, G, full=False)
     B = wl.make_B(21, K, N, 1.0)
     print("case tvw identity random", flush=True)
@@ -58,10 +59,11 @@ def test_all_ones_counts_kept_elements():
     assert np.array_equal(C, np.broadcast_to(mask.sum(0).astype(np.float64), (M, N)))
 
 
+@pytest.mark.parametrize("G", [64, 128])
 @pytest.mark.parametrize("M", [1, 8, 129, 333])
-def test_random_masks_and_M_tails(M):
-    rng = np.random.default_rng(30 + M)
-    K, N, G = 410, 300, 128
+def test_random_masks_and_M_tails(M, G):
+    rng = np.random.default_rng(30 + M + G)
+    K, N = 410, 300
     mask, tm = random_tvw_mask(rng, K, N, G, full=(M % 2 == 1))
     A, B = wl.make_A(M, M, K), wl.make_B(M, K, N, 1.0)
     print(f"case tvw random M={M}", flush=True)
