@@ -31,6 +31,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0
 FP16_PEAK_TFLOPS = 2500.0
 PLAN = [(0, 4), (1, 1), (2, 1)]          # (shape index in the config, copies per layer)
+# HBM-side bytes per launch (average over the 6 launches of a step) from the two
+# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) summarised under profiles/, scaled by
+# what the same counters read for a plain 256 MiB device copy.  A measurement that
+# cannot be taken from inside this script: None where no such run has been made.
+MEASURED_TRAFFIC_BYTES = {"tw": 26.26e6, "tvw": None}
 
 
 def algorithmic_bytes(M, K, N, pattern, sum_kw, sum_k):
@@ -174,7 +179,7 @@ def main():
     achieved = alg_per_launch / (avg_launch_ms * 1e-3) / 1e9
     kern = "tw_gemm_km_dma_kernel" if args.pattern == "tw" else "tvw_gemm_km_kernel"
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=achieved / HBM_PEAK_GBS, traffic=None,
+                    frac=achieved / HBM_PEAK_GBS, traffic=MEASURED_TRAFFIC_BYTES[args.pattern],
                     kernel=f"{kern} (all {launches} launches of a step; the step runs nothing else)",
                     avg_launch_us=avg_launch_ms * 1e3, algorithmic_bytes_per_launch=alg_per_launch)
 
