@@ -166,6 +166,9 @@ const char* tw_status_str(int status);
  *              N-tiles of an M-band; 0 = plain order
  *   "kernel"   0 = automatic, 1 = register-staged pipeline, 2 = asynchronous
  *              global->LDS copy pipeline (TW_ERR_UNSUPPORTED where it has no instance)
+ *   "waves"    4 (default) or 8 waves per workgroup in the asynchronous pipeline
+ *   "ksplit"   0 = automatic, 1 = never, 2 = always split K between two wave groups
+ *              of a workgroup (long K, few tiles)
  *   "depth"    stages in flight of the asynchronous pipeline: 3 (default) or 4
  * tw_flop_counts: condensed multiply-add work of a handle:
  *   *sum_kw = sum over tiles of K_t * W_t (kept-row x width products).

@@ -15,6 +15,8 @@ std::atomic<int> opt_tile_m{0};
 std::atomic<int> opt_xcd_map{1};
 std::atomic<int> opt_kernel{0};   // 0 = automatic, 1 = register-staged, 2 = asynchronous copies
 std::atomic<int> opt_depth{3};
+std::atomic<int> opt_waves{4};
+std::atomic<int> opt_ksplit{0};   // 0 = automatic, 1 = off, 2 = two K groups per workgroup
 
 bool valid_G(int G) { return G == 32 || G == 64 || G == 128; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -36,6 +38,15 @@ int pick_tile_m(int M, int n_tiles, int G) {
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// K-split inside the workgroup pays when 128-row tiles cannot give every CU a
+// workgroup and the K loop is long enough to amortise the final reduction.
+bool use_ksplit(int M, int n_tiles, int max_k, int* tm) {
+  const long wgs128 = (long)((M + 127) / 128) * n_tiles;
+  if (max_k < 12 * 32 || wgs128 > 320) return false;
+  *tm = wgs128 <= 224 ? 64 : 128;
+  return true;
+}
 
 }  // namespace
 
@@ -135,6 +146,10 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
   g.zero_cols = h->img.d_zero_cols; g.n_zero = (int)h->img.zero_cols.size();
   g.meta = h->img.d_meta;
   g.n_tiles = h->n_tiles; g.K = h->K; g.N = h->N; g.xcd_map = opt_xcd_map.load();
+#ifdef TWG_TRACE
+  static int trace_launch = 0;
+  g.trace_slot = trace_launch++ & 1;
+#endif
   if (layout == TW_LAYOUT_MK) {
     hipError_t e = twg::launch_tw_mk(h->G, g, (hipStream_t)stream);
     if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
@@ -147,8 +162,20 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
   }
   const int tm = pick_tile_m(M, h->n_tiles > 0 ? h->n_tiles : 1, h->G);
   hipError_t e = hipErrorInvalidValue;
-  if (opt_kernel.load() != 1 && h->G != 32)
-    e = twg::launch_tw_km_dma(h->G, tm, opt_depth.load(), g, (hipStream_t)stream);
+  // the asynchronous kernel addresses A with 32-bit byte offsets
+  const bool a_fits32 = (unsigned long long)h->K * (unsigned long long)lda * 2ull < (1ull << 32);
+  if (opt_kernel.load() != 1 && h->G != 32 && a_fits32) {
+    // long K with too few tiles to fill the chip: split K inside the workgroup
+    int variant = opt_waves.load() == 8 ? twg::DMA_WAVES8 : twg::DMA_WAVES4;
+    int tmk = tm;
+    const int ks = opt_ksplit.load();
+    if (ks == 2 || (ks == 0 && use_ksplit(M, h->n_tiles, h->max_kp, &tmk))) variant = twg::DMA_KSPLIT2;
+    if (variant == twg::DMA_KSPLIT2 && ks == 2) tmk = tm == 256 ? 128 : tm;
+    e = twg::launch_tw_km_dma(h->G, variant == twg::DMA_KSPLIT2 ? tmk : tm, opt_depth.load(), variant, g,
+                              (hipStream_t)stream);
+    if (e == hipErrorInvalidValue && variant != twg::DMA_WAVES4)
+      e = twg::launch_tw_km_dma(h->G, tm, opt_depth.load(), twg::DMA_WAVES4, g, (hipStream_t)stream);
+  }
   if (e == hipErrorInvalidValue && opt_kernel.load() != 2)
     e = twg::launch_tw_km(h->G, tm, g, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
@@ -179,8 +206,19 @@ tw_status tw_dense_gemm(const void* A, const void* B, void* C, int M, int K, int
   }
   const int tm = pick_tile_m(M, g.n_tiles, tn);
   hipError_t e = hipErrorInvalidValue;
-  if (opt_kernel.load() != 1 && K % 32 == 0)
-    e = twg::launch_dense_km_dma(tn, tm, opt_depth.load(), g, (hipStream_t)stream);
+  const bool fits32 = (unsigned long long)K * (unsigned long long)lda * 2ull < (1ull << 32) &&
+                      (unsigned long long)K * (unsigned long long)ldb * 2ull < (1ull << 32);
+  if (opt_kernel.load() != 1 && K % 32 == 0 && fits32) {
+    int variant = opt_waves.load() == 8 ? twg::DMA_WAVES8 : twg::DMA_WAVES4;
+    int tmk = tm;
+    const int ks = opt_ksplit.load();
+    if (K % 64 == 0 && (ks == 2 || (ks == 0 && use_ksplit(M, g.n_tiles, K, &tmk)))) variant = twg::DMA_KSPLIT2;
+    if (variant == twg::DMA_KSPLIT2 && ks == 2) tmk = tm == 256 ? 128 : tm;
+    e = twg::launch_dense_km_dma(tn, variant == twg::DMA_KSPLIT2 ? tmk : tm, opt_depth.load(), variant, g,
+                                 (hipStream_t)stream);
+    if (e == hipErrorInvalidValue && variant != twg::DMA_WAVES4)
+      e = twg::launch_dense_km_dma(tn, tm, opt_depth.load(), twg::DMA_WAVES4, g, (hipStream_t)stream);
+  }
   if (e == hipErrorInvalidValue && opt_kernel.load() != 2)
     e = twg::launch_dense_km(tn, tm, g, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
@@ -219,6 +257,8 @@ tw_status tw_set_option(const char* name, int value) {
   if (!std::strcmp(name, "tile_m")) { opt_tile_m.store(value); return TW_OK; }
   if (!std::strcmp(name, "xcd_map")) { opt_xcd_map.store(value != 0); return TW_OK; }
   if (!std::strcmp(name, "kernel")) { opt_kernel.store(value); return TW_OK; }
+  if (!std::strcmp(name, "waves")) { opt_waves.store(value == 8 ? 8 : 4); return TW_OK; }
+  if (!std::strcmp(name, "ksplit")) { opt_ksplit.store(value); return TW_OK; }
   if (!std::strcmp(name, "depth")) { opt_depth.store(value == 4 ? 4 : 3); return TW_OK; }
   return TW_ERR_ARG;
 }

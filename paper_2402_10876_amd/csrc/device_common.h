@@ -24,18 +24,24 @@ constexpr int NTHREADS = 256;
 // constant-rate (100 MHz) timestamps at the phase boundaries of the main loop.
 #ifdef TWG_TRACE
 constexpr int TRACE_WGS = 2048, TRACE_SLOTS = 48;
-static __device__ unsigned long long twg_trace[TRACE_WGS * TRACE_SLOTS];  // one per source file
+static __device__ unsigned long long twg_trace[2 * TRACE_WGS * TRACE_SLOTS];  // one per source file; two launches
 #define TWG_TRACE_INIT()                                         \
   const bool trace_on = threadIdx.x == 0 && blockIdx.x < TRACE_WGS; \
   int trace_n = 0
 #define TWG_STAMP()                                                                   \
   do {                                                                                \
     if (trace_on && trace_n < TRACE_SLOTS)                                            \
-      twg_trace[blockIdx.x * TRACE_SLOTS + trace_n++] = __builtin_amdgcn_s_memrealtime(); \
+      twg_trace[(g.trace_slot * TRACE_WGS + blockIdx.x) * TRACE_SLOTS + trace_n++] = __builtin_amdgcn_s_memrealtime(); \
   } while (0)
+#if TWG_TRACE >= 2
+#define TWG_STAMP_FINE() TWG_STAMP()     // per-iteration stamps perturb the pipeline: level 2 only
+#else
+#define TWG_STAMP_FINE() do {} while (0)
+#endif
 #else
 #define TWG_TRACE_INIT() do {} while (0)
 #define TWG_STAMP() do {} while (0)
+#define TWG_STAMP_FINE() do {} while (0)
 #endif
 
 // XOR mask applied to the byte offset inside a row of a k-major LDS tile with
@@ -67,7 +73,7 @@ __device__ __forceinline__ void zero_fill_column(const GemmArgs& g, int which) {
   const int col = g.zero_cols[which];
   _Float16* row = g.C + (size_t)col * g.ldc;
   const u32x4 z = {0u, 0u, 0u, 0u};
-  for (int m = threadIdx.x * 8; m < g.M; m += NTHREADS * 8) {
+  for (int m = threadIdx.x * 8; m < g.M; m += (int)blockDim.x * 8) {
     if (m + 8 <= g.M) *(u32x4*)(row + m) = z;
     else for (int i = m; i < g.M; ++i) row[i] = (_Float16)0.f;
   }

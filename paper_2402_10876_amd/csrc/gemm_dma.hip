@@ -79,16 +79,25 @@ __device__ __forceinline__ void wait_vm() {
 
 }  // namespace
 
-template <int TM, int TN, int WAVES_M, int D, bool DENSE>
-__global__ __launch_bounds__(NTHREADS) void tw_gemm_km_dma_kernel(GemmArgs g) {
-  constexpr int WAVES_N = 4 / WAVES_M;
+// KSPLIT = 2: the workgroup has two groups of waves that own the same output
+// tile; a pipeline stage then holds 64 condensed rows, group g multiplies rows
+// 32g..32g+31 of it, and the two partial accumulators are added through LDS
+// (in fp32, before the single rounding).  It gives a tile two waves per SIMD,
+// which long-K problems with few tiles need to keep the matrix cores busy.
+template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KSPLIT = 1>
+__global__ __launch_bounds__(NWAVES * 64) void tw_gemm_km_dma_kernel(GemmArgs g) {
+  constexpr int NT = NWAVES * 64;          // threads of the workgroup
+  constexpr int WPG = NWAVES / KSPLIT;     // waves per group
+  constexpr int KSS = KS * KSPLIT;         // condensed rows per pipeline stage
+  constexpr int WAVES_N = WPG / WAVES_M;
   constexpr int WM = TM / WAVES_M, WN = TN / WAVES_N;
   constexpr int MB = WM / 32, NB = WN / 32;
   static_assert(MB >= 1 && NB >= 1, "wave tile must hold a 32x32 block");
   constexpr int RBA = TM * 2, RBB = TN * 2;            // LDS row bytes
-  constexpr int STAGE_A = KS * RBA, STAGE_B = KS * RBB, STAGE = STAGE_A + STAGE_B;
+  constexpr int STAGE_A = KSS * RBA, STAGE_B = KSS * RBB, STAGE = STAGE_A + STAGE_B;
   static_assert(STAGE_A % 4096 == 0 && STAGE_B % 4096 == 0, "a stage is a whole number of 1 KiB copies per wave");
-  constexpr int NIA = STAGE_A / 4096, NIB = STAGE_B / 4096;   // copy instructions per wave and stage
+  static_assert(STAGE_A % (1024 * NWAVES) == 0 && STAGE_B % (1024 * NWAVES) == 0, "");
+  constexpr int NIA = STAGE_A / (1024 * NWAVES), NIB = STAGE_B / (1024 * NWAVES);   // copy instructions per wave and stage
   constexpr int RPIA = 1024 / RBA, RPIB = 1024 / RBB;         // tile rows per copy instruction
   static_assert((RPIA == 2 || RPIA == 4 || RPIA == 8) && (NIA == 1 || NIA == 2 || NIA == 4), "");
   static_assert(D == 3 || D == 4, "the stage wait below handles up to two newer stages");
@@ -96,6 +105,8 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_dma_kernel(GemmArgs g) {
   constexpr int CA = TM / 8;
   constexpr int CS = (TM + 4) * 2;                     // epilogue row bytes: 66 dwords mod 64 banks = 2
   constexpr int PIPE_BYTES = D * STAGE, EPI_BYTES = TN * CS;
+  constexpr int RED_BYTES = KSPLIT > 1 ? TM * TN * 4 : 0;      // partial accumulators of group 1
+  static_assert(RED_BYTES <= PIPE_BYTES, "the reduction reuses the pipeline buffers");
   constexpr int LDS_BYTES = PIPE_BYTES > EPI_BYTES ? PIPE_BYTES : EPI_BYTES;
   __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
 
@@ -113,17 +124,18 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_dma_kernel(GemmArgs g) {
   int t = lid - mt * g.n_tiles;          // launch position of the tile, then the tile itself
   const int m0 = mt * TM;
 
-  int kp0, ns;
-  if constexpr (DENSE) { kp0 = 0; ns = g.K / KS; }     // host guarantees K % KS == 0
+  int kp0, ns32;                                       // ns32: stages of 32 rows
+  if constexpr (DENSE) { kp0 = 0; ns32 = g.K / KS; }   // host guarantees K % (32 KSPLIT) == 0
   else {
     const int4v rec = scalar_load4(g.tile_sched + 4 * t);
-    t = rec[0]; kp0 = rec[1]; ns = rec[2] / KS;
+    t = rec[0]; kp0 = rec[1]; ns32 = rec[2] / KS;
   }
+  const int ns = (ns32 + KSPLIT - 1) / KSPLIT;         // pipeline stages of KSS rows
   const _Float16* Bt = DENSE ? g.vals + (size_t)t * TN : g.vals + (size_t)kp0 * TN;
   const int ldb = DENSE ? g.ldb : TN;
 
   // kept-column indices of the rows of C^T this thread will store (CTO_n)
-  constexpr int ROWS_PER_PASS = NTHREADS / CA;
+  constexpr int ROWS_PER_PASS = NT / CA;
   constexpr int NPASS = TN / ROWS_PER_PASS;
   const int c = tid % CA, r0 = tid / CA;
   int cols[NPASS];
@@ -154,53 +166,64 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_dma_kernel(GemmArgs g) {
     b_el[j] = ((lb % RBB) ^ swz_mask<RBB>(row)) / 2;
     if constexpr (DENSE) { if (t * TN + b_el[j] >= g.N) b_el[j] = 0; }
   }
-  const _Float16* Abase = g.A + m0;
+  // Addresses are a wave-uniform base plus an unsigned 32-bit byte offset per
+  // lane (the host checks that A fits): one multiply-add per copy instruction.
+  const char* Abase = (const char*)(g.A + m0);
+  const char* Bbase = (const char*)Bt;
+  const uint32_t lda2 = (uint32_t)g.lda * 2u, ldb2 = (uint32_t)ldb * 2u;
+  uint32_t b_off[NIB];
+#pragma unroll
+  for (int j = 0; j < NIB; ++j)
+    b_off[j] = (uint32_t)((wave * NIB + j) * RPIB + b_rloc) * ldb2 + (uint32_t)b_el[j] * 2u;
 
-  // Row indices of stage s for copy instruction j: RPIA consecutive entries of
+  // Row indices of a stage for copy instruction j: RPIA consecutive entries of
   // the kept-row list at a wave-uniform address.  They are fetched with scalar
   // loads written in assembly: a vector load would share the in-order counter
   // of the asynchronous copies, and waiting for it would drain the pipeline.
+  // Scalar loads return out of order, so they are always waited for with a full
+  // lgkmcnt(0); each fetch is issued right after a stage barrier and waited for
+  // together with the first operand reads of that stage, one iteration before
+  // its rows are needed.
   typedef int sidx_t __attribute__((ext_vector_type(RPIA)));
-  sidx_t rows_next[NIA];
-  auto fetch_rows = [&](int s) {
+  struct Rows { sidx_t r[NIA]; };
+  auto fetch_rows = [&](int s, Rows& dst) {
     if constexpr (!DENSE) {
 #pragma unroll
       for (int j = 0; j < NIA; ++j) {
-        const int* rp = g.row_idx + kp0 + s * KS + (wave * NIA + j) * RPIA;
-        if constexpr (RPIA == 2) asm volatile("s_load_dwordx2 %0, %1, 0x0" : "=s"(rows_next[j]) : "s"(rp));
-        else if constexpr (RPIA == 4) asm volatile("s_load_dwordx4 %0, %1, 0x0" : "=s"(rows_next[j]) : "s"(rp));
-        else asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(rows_next[j]) : "s"(rp));
+        const int* rp = g.row_idx + kp0 + s * KSS + (wave * NIA + j) * RPIA;
+        if constexpr (RPIA == 2) asm volatile("s_load_dwordx2 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
+        else if constexpr (RPIA == 4) asm volatile("s_load_dwordx4 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
+        else asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
       }
     }
   };
-  auto issue = [&](int s) {        // uses rows_next (stage s), then prefetches stage s+1's
+  auto tie_rows = [&](Rows& x) {      // after a wait: no use of x may be moved above this point
+    if constexpr (!DENSE) {
+      if constexpr (NIA == 1) asm volatile("" : "+s"(x.r[0]));
+      else if constexpr (NIA == 2) asm volatile("" : "+s"(x.r[0]), "+s"(x.r[1]));
+      else asm volatile("" : "+s"(x.r[0]), "+s"(x.r[1]), "+s"(x.r[2]), "+s"(x.r[3]));
+    }
+  };
+  auto issue = [&](int s, const Rows& rows) {     // copies of stage s; rows = its kept-row indices
     char* dstA = lds + (s % D) * STAGE;
     char* dstB = dstA + STAGE_A;
+    const uint32_t bs = (uint32_t)s * (uint32_t)KSS * ldb2;
 #pragma unroll
-    for (int j = 0; j < NIB; ++j) {       // the weight block needs no index list: first
-      const int row = s * KS + (wave * NIB + j) * RPIB + b_rloc;
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(Bt + (size_t)row * ldb + b_el[j]),
+    for (int j = 0; j < NIB; ++j)
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(Bbase + (bs + b_off[j])),
                                        LDS_PTR(void, dstB + (wave * NIB + j) * 1024), 16, 0, 0);
-    }
-    if constexpr (!DENSE) {
-      // scalar loads return out of order: full wait, tied to the registers
-      if constexpr (NIA == 1) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(rows_next[0]));
-      else if constexpr (NIA == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(rows_next[0]), "+s"(rows_next[1]));
-      else asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(rows_next[0]), "+s"(rows_next[1]), "+s"(rows_next[2]), "+s"(rows_next[3]));
-    }
 #pragma unroll
     for (int j = 0; j < NIA; ++j) {
       int row;
-      if constexpr (DENSE) row = s * KS + (wave * NIA + j) * RPIA + a_rloc;
+      if constexpr (DENSE) row = s * KSS + (wave * NIA + j) * RPIA + a_rloc;
       else {
-        row = rows_next[j][0];
+        row = rows.r[j][0];
 #pragma unroll
-        for (int q = 1; q < RPIA; ++q) row = (a_rloc == q) ? rows_next[j][q] : row;
+        for (int q = 1; q < RPIA; ++q) row = (a_rloc == q) ? rows.r[j][q] : row;
       }
-      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(Abase + (size_t)row * g.lda + a_el[j]),
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(Abase + ((uint32_t)row * lda2 + (uint32_t)a_el[j] * 2u)),
                                        LDS_PTR(void, dstA + (wave * NIA + j) * 1024), 16, 0, 0);
     }
-    fetch_rows(s + 1 < ns ? s + 1 : ns - 1);
   };
 
   floatx16 acc[MB][NB];
@@ -211,7 +234,8 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_dma_kernel(GemmArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+  const int grp = wave / WPG, wl = wave % WPG;         // K-split group, wave inside the group
+  const int wm = wl % WAVES_M, wn = wl / WAVES_M;
   // per-lane LDS byte address of each operand block at stage buffer 0, k-step 0
   const uint32_t lds0 = (uint32_t)(uintptr_t)LDS_PTR(char, lds);
   const int p = lane & 15, q = lane >> 4;
@@ -219,10 +243,10 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_dma_kernel(GemmArgs g) {
   uint32_t fa[MB], fb[NB];
 #pragma unroll
   for (int i = 0; i < MB; ++i)
-    fa[i] = lds0 + swz<RBA>(frow, (wm * WM + i * 32 + 16 * (q & 1) + 4 * (p & 3)) * 2);
+    fa[i] = lds0 + grp * (KS * RBA) + swz<RBA>(frow, (wm * WM + i * 32 + 16 * (q & 1) + 4 * (p & 3)) * 2);
 #pragma unroll
   for (int j = 0; j < NB; ++j)
-    fb[j] = lds0 + STAGE_A + swz<RBB>(frow, (wn * WN + j * 32 + 16 * (q & 1) + 4 * (p & 3)) * 2);
+    fb[j] = lds0 + STAGE_A + grp * (KS * RBB) + swz<RBB>(frow, (wn * WN + j * 32 + 16 * (q & 1) + 4 * (p & 3)) * 2);
 
   constexpr int NF = MB + NB;
   Frag f0[NF], f1[NF];       // operands of k-steps 0 and 1 of a stage
@@ -250,12 +274,22 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_dma_kernel(GemmArgs g) {
   using K0 = std::integral_constant<int, 0>;
   using K16 = std::integral_constant<int, 16>;
 
+  Rows rows_cur, rows_next;
   if (ns > 0) {
-    fetch_rows(0);
+    // kept-row lists of the first D stages in one round trip, then D-1 stages of copies
+    Rows pro[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) fetch_rows(d < ns ? d : ns - 1, pro[d]);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int d = 0; d < D; ++d) tie_rows(pro[d]);
+#pragma unroll
     for (int d = 0; d < D - 1; ++d)
-      if (d < ns) issue(d);
+      if (d < ns) issue(d, pro[d]);
+    rows_cur = pro[D - 1];
   }
-  TWG_STAMP();
+  TWG_STAMP_FINE();
+  bool live_prev = false;
   for (int s = 0; s < ns; ++s) {
     // own copies of stage s have landed: at most the copies of the newer stages remain
     int newer = ns - 1 - s;
@@ -263,21 +297,28 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_dma_kernel(GemmArgs g) {
     if (newer >= 2) wait_vm<2 * NPS>();
     else if (newer == 1) wait_vm<NPS>();
     else wait_vm<0>();
+    TWG_STAMP_FINE();
     // everybody's copies of stage s have landed, everybody is done reading stage s-1
     asm volatile("s_barrier" ::: "memory");
+    TWG_STAMP_FINE();
+    fetch_rows(s + D < ns ? s + D : ns - 1, rows_next);   // needed by the next iteration
     const uint32_t boff = (uint32_t)((s % D) * STAGE);
     read_step(boff, K0{}, f0);
-    if (s > 0) mfma_step(f1);            // second k-step of the previous stage
+    if (s > 0 && live_prev) mfma_step(f1);   // second k-step of the previous stage
+    const bool live = s * KSPLIT + grp < ns32;   // false only for group 1 on an odd tail
+    wait_lds<NF>(f0);                    // full wait: the scalar loads above are in as well
+    tie_rows(rows_next);
     // the copies of stage s+D-1 go into the buffer of stage s-1, which every wave
-    // has finished reading; their address arithmetic hides behind the LDS reads
-    if (s + D - 1 < ns) issue(s + D - 1);
-    wait_lds<NF>(f0);
+    // has finished reading
+    if (s + D - 1 < ns) issue(s + D - 1, rows_cur);
     read_step(boff, K16{}, f1);
-    mfma_step(f0);
+    if (live) mfma_step(f0);
+    live_prev = live;
+    rows_cur = rows_next;
     wait_lds<NF>(f1);
-    TWG_STAMP();
+    TWG_STAMP_FINE();
   }
-  if (ns > 0) mfma_step(f1);
+  if (ns > 0 && live_prev) mfma_step(f1);
 
   // ---- epilogue: fp32 -> fp16 (RNE), stage as [n][m], store rows of C^T ----
   const int m = m0 + c * 8;
@@ -285,24 +326,48 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_dma_kernel(GemmArgs g) {
 #pragma unroll
   for (int i = 0; i < NPASS; ++i)
     dst_off[i] = (cols[i] < 0 || m >= g.M) ? -1 : (long long)cols[i] * g.ldc + m;
-  TWG_STAMP();
+  TWG_STAMP_FINE();
   __syncthreads();
+  if constexpr (KSPLIT > 1) {
+    // group 1 hands its fp32 partial sums to group 0: [wave in group][register][lane]
+    float* red = (float*)lds + wl * (MB * NB * 16 * 64) + lane;
+    if (grp == 1) {
 #pragma unroll
-  for (int i = 0; i < MB; ++i)
+      for (int i = 0; i < MB; ++i)
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
-      const int n = wn * WN + j * 32 + (lane & 31);
+        for (int j = 0; j < NB; ++j)
 #pragma unroll
-      for (int rq = 0; rq < 4; ++rq) {
-        const int mm = wm * WM + i * 32 + 8 * rq + 4 * (lane >> 5);
-        half4 v;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) v[r] = (_Float16)acc[i][j][rq * 4 + r];
-        *(half4*)(lds + n * CS + mm * 2) = v;
-      }
+          for (int r = 0; r < 16; ++r) red[((i * NB + j) * 16 + r) * 64] = acc[i][j][r];
     }
+    __syncthreads();
+    if (grp == 0) {
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][j][r] += red[((i * NB + j) * 16 + r) * 64];
+    }
+    __syncthreads();
+  }
+  if (grp == 0) {
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        const int n = wn * WN + j * 32 + (lane & 31);
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          const int mm = wm * WM + i * 32 + 8 * rq + 4 * (lane >> 5);
+          half4 v;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) v[r] = (_Float16)acc[i][j][rq * 4 + r];
+          *(half4*)(lds + n * CS + mm * 2) = v;
+        }
+      }
+  }
   __syncthreads();
-  TWG_STAMP();
+  TWG_STAMP_FINE();
   // all staged chunks into registers first, then the stores back to back
   union Chunk { uint2 h[2]; u32x4 v; };   // staging rows are 8-byte aligned only
   Chunk ck[NPASS];
@@ -326,18 +391,31 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_dma_kernel(GemmArgs g) {
   TWG_STAMP();
 }
 
-template <int TM, int TN, int WAVES_M, int D, bool DENSE>
+template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KSPLIT = 1>
 static hipError_t launch(const GemmArgs& g, hipStream_t stream) {
   const int grid = g.n_mtiles * g.n_tiles + g.n_zero;
   if (grid <= 0) return hipSuccess;
-  hipLaunchKernelGGL((tw_gemm_km_dma_kernel<TM, TN, WAVES_M, D, DENSE>), dim3(grid),
-                     dim3(NTHREADS), 0, stream, g);
+  hipLaunchKernelGGL((tw_gemm_km_dma_kernel<TM, TN, WAVES_M, D, DENSE, NWAVES, KSPLIT>), dim3(grid),
+                     dim3(NWAVES * 64), 0, stream, g);
   return hipGetLastError();
 }
 
 template <bool DENSE>
-static hipError_t dispatch(int G, int tm, int depth, GemmArgs& g, hipStream_t stream) {
+static hipError_t dispatch(int G, int tm, int depth, int variant, GemmArgs& g, hipStream_t stream) {
   g.n_mtiles = (g.M + tm - 1) / tm;
+  if (variant == DMA_KSPLIT2) {   // two K-split groups of four waves
+    if (G == 128 && tm == 128 && depth == 3) return launch<128, 128, 2, 3, DENSE, 8, 2>(g, stream);
+    if (G == 128 && tm == 64 && depth == 3) return launch<64, 128, 1, 3, DENSE, 8, 2>(g, stream);
+    if (G == 128 && tm == 64 && depth == 4) return launch<64, 128, 1, 4, DENSE, 8, 2>(g, stream);
+    if (G == 64 && tm == 128 && depth == 3) return launch<128, 64, 2, 3, DENSE, 8, 2>(g, stream);
+    return hipErrorInvalidValue;
+  }
+  if (variant == DMA_WAVES8) {    // 512-thread workgroups: 64 x 32 (m x n) per wave
+    if (G == 128 && tm == 128 && depth == 3) return launch<128, 128, 2, 3, DENSE, 8>(g, stream);
+    if (G == 128 && tm == 128 && depth == 4) return launch<128, 128, 2, 4, DENSE, 8>(g, stream);
+    if (G == 128 && tm == 256 && depth == 3) return launch<256, 128, 4, 3, DENSE, 8>(g, stream);
+    return hipErrorInvalidValue;
+  }
 #define TWG_CASE(TM_, TN_, WM_, D_) \
   if (G == TN_ && tm == TM_ && depth == D_) return launch<TM_, TN_, WM_, D_, DENSE>(g, stream);
   TWG_CASE(64, 128, 1, 3) TWG_CASE(128, 128, 2, 3) TWG_CASE(256, 128, 2, 3)
@@ -354,11 +432,11 @@ extern "C" int tw_debug_read_trace_dma(unsigned long long* out, int n) {
 }
 #endif
 
-hipError_t launch_tw_km_dma(int G, int tm, int depth, GemmArgs g, hipStream_t stream) {
-  return dispatch<false>(G, tm, depth, g, stream);
+hipError_t launch_tw_km_dma(int G, int tm, int depth, int variant, GemmArgs g, hipStream_t stream) {
+  return dispatch<false>(G, tm, depth, variant, g, stream);
 }
-hipError_t launch_dense_km_dma(int tn, int tm, int depth, GemmArgs g, hipStream_t stream) {
-  return dispatch<true>(tn, tm, depth, g, stream);
+hipError_t launch_dense_km_dma(int tn, int tm, int depth, int variant, GemmArgs g, hipStream_t stream) {
+  return dispatch<true>(tn, tm, depth, variant, g, stream);
 }
 
 }  // namespace twg

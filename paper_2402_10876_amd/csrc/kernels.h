@@ -23,6 +23,9 @@ struct GemmArgs {
   int n_tiles, n_mtiles;
   int K, N;                      // dense only
   int xcd_map;
+#ifdef TWG_TRACE
+  int trace_slot;                // developer build: which of two trace buffers this launch writes
+#endif
 };
 
 // G / tn: tile width (32, 64, 128); tm: M-tile (64, 128, 256).
@@ -34,8 +37,12 @@ hipError_t launch_tw_mk(int G, GemmArgs g, hipStream_t stream);
 hipError_t launch_dense_mk(int tn, GemmArgs g, hipStream_t stream);
 // Asynchronous-copy pipeline (gemm_dma.hip): G / tn in {64, 128}, depth = stages
 // in flight (3 or 4); the dense variant needs K % 32 == 0.
-hipError_t launch_tw_km_dma(int G, int tm, int depth, GemmArgs g, hipStream_t stream);
-hipError_t launch_dense_km_dma(int tn, int tm, int depth, GemmArgs g, hipStream_t stream);
+// variant: DMA_WAVES4 = 4 waves per workgroup; DMA_WAVES8 = 8 waves splitting the tile
+// (tm in {128, 256}, G = 128); DMA_KSPLIT2 = two groups of 4 waves splitting K inside
+// the workgroup (dense: K % 64 == 0).
+enum { DMA_WAVES4 = 0, DMA_WAVES8 = 1, DMA_KSPLIT2 = 2 };
+hipError_t launch_tw_km_dma(int G, int tm, int depth, int variant, GemmArgs g, hipStream_t stream);
+hipError_t launch_dense_km_dma(int tn, int tm, int depth, int variant, GemmArgs g, hipStream_t stream);
 // TVW (2:4 inside the kept rows) on the sparse matrix instruction (gemm_tvw.hip).
 hipError_t launch_tvw_km(int G, int tm, int depth, GemmArgs g, hipStream_t stream);
 

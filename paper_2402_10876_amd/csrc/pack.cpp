@@ -222,7 +222,9 @@ void build_device_image(tw_handle_s* h) {
     d.tile_kp_off[t + 1] = d.tile_kp_off[t] + kp;
     h->max_kp = std::max(h->max_kp, kp);
   }
-  d.row_idx.assign((size_t)d.tile_kp_off[nt], 0);
+  // one stage of slack behind the last tile: the K-split kernel copies stages of
+  // 64 rows and may run one 32-row stage past a tile's end (it never multiplies it)
+  d.row_idx.assign((size_t)d.tile_kp_off[nt] + KSTEP_TW, 0);
   for (int t = 0; t < nt; ++t) {
     const int k0 = h->tile_k_off[t], kt = h->tile_k_off[t + 1] - k0;
     const int kp0 = d.tile_kp_off[t], kp = d.tile_kp_off[t + 1] - kp0;
@@ -251,7 +253,7 @@ void build_device_image(tw_handle_s* h) {
     d.tile_sched[4 * pos + 3] = std::min(G, h->n_kept - t * G);
   }
   if (!tvw) {
-    d.vals.assign((size_t)d.tile_kp_off[nt] * G, 0);
+    d.vals.assign(((size_t)d.tile_kp_off[nt] + KSTEP_TW) * G, 0);
     for (int t = 0; t < nt; ++t) {
       const int kt = h->tile_k_off[t + 1] - h->tile_k_off[t];
       const int w = std::min(G, h->n_kept - t * G);

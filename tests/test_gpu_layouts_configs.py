@@ -14,10 +14,10 @@ pytestmark = pytest.mark.gpu
 
 @pytest.fixture(autouse=True)
 def _reset_options():
-    for k, v in (("tile_m", 0), ("xcd_map", 1), ("kernel", 0), ("depth", 3)):
+    for k, v in (("tile_m", 0), ("xcd_map", 1), ("kernel", 0), ("depth", 3), ("waves", 4), ("ksplit", 0)):
         tw.tw_set_option(k, v)
     yield
-    for k, v in (("tile_m", 0), ("xcd_map", 1), ("kernel", 0), ("depth", 3)):
+    for k, v in (("tile_m", 0), ("xcd_map", 1), ("kernel", 0), ("depth", 3), ("waves", 4), ("ksplit", 0)):
         tw.tw_set_option(k, v)
 
 
@@ -80,6 +80,44 @@ def test_both_pipelines_agree_with_oracle(kernel, depth, tile_m):
     Cd, _ = gu.run_dense(tw, c.A, c.B)
     ones = np.ones_like(c.mask)
     assert_C_close(Cd, og.gemm_oracle(c.A, c.B, ones), og.abs_bound(c.A, c.B, ones))
+
+
+@pytest.mark.parametrize("tile_m,depth", [(128, 3), (128, 4), (256, 3)])
+def test_eight_wave_workgroups(tile_m, depth):
+    for k, v in (("kernel", 2), ("waves", 8), ("tile_m", tile_m), ("depth", depth)):
+        tw.tw_set_option(k, v)
+    c = wl.make_case(2, 2, M=520, recipe="global")
+    print(f"case {c.name} waves=8 tile_m={tile_m} depth={depth}", flush=True)
+    p = _pack(c)
+    C, _ = gu.run_tw(tw, p, c.A, c.N)
+    p.free()
+    ref, S = _oracle(c)
+    assert_C_close(C, ref, S)
+    Cd, _ = gu.run_dense(tw, c.A, c.B)
+    ones = np.ones_like(c.mask)
+    assert_C_close(Cd, og.gemm_oracle(c.A, c.B, ones), og.abs_bound(c.A, c.B, ones))
+
+
+@pytest.mark.parametrize("tile_m,depth,G", [(128, 3, 128), (64, 3, 128), (64, 4, 128), (128, 3, 64)])
+@pytest.mark.parametrize("K_keep", ["odd", "even"])
+def test_k_split_inside_the_workgroup(tile_m, depth, G, K_keep):
+    """Two wave groups share one output tile; an odd number of 32-row stages
+    leaves the second group idle on the last stage."""
+    for k, v in (("kernel", 2), ("ksplit", 2), ("tile_m", tile_m), ("depth", depth)):
+        tw.tw_set_option(k, v)
+    rng = np.random.default_rng(70 + tile_m + G)
+    M, K, N = 333, 800, 300
+    mask = random_tw_mask(rng, K, N, G, col_keep=0.8, row_keep=0.42 if K_keep == "odd" else 0.5)
+    A, B = wl.make_A(7, M, K), wl.make_B(7, K, N, 0.1)
+    print(f"case ksplit tile_m={tile_m} depth={depth} G={G} {K_keep}", flush=True)
+    p = tw.tw_pack(B, mask, G, tw.PATTERN_TW)
+    C, _ = gu.run_tw(tw, p, A, N)
+    p.free()
+    assert_C_close(C, og.gemm_oracle(A, B, mask), og.abs_bound(A, B, mask))
+    A2, B2 = wl.make_A(8, 200, 448), wl.make_B(8, 448, 260, 0.1)     # dense, K % 64 == 0
+    Cd, _ = gu.run_dense(tw, A2, B2)
+    ones = np.ones(B2.shape, np.uint8)
+    assert_C_close(Cd, og.gemm_oracle(A2, B2, ones), og.abs_bound(A2, B2, ones))
 
 
 @pytest.mark.parametrize("pattern,sparsity", [("tw", 0.0), ("tw", 0.5), ("tw", 0.75), ("tw", 0.875), ("tw", 0.9375),

@@ -13,11 +13,11 @@ pytestmark = pytest.mark.gpu
 
 @pytest.fixture(autouse=True)
 def _reset_options():
-    tw.tw_set_option("tile_m", 0)
-    tw.tw_set_option("xcd_map", 1)
+    for k, v in (("tile_m", 0), ("xcd_map", 1), ("kernel", 0), ("depth", 3), ("waves", 4), ("ksplit", 0)):
+        tw.tw_set_option(k, v)
     yield
-    tw.tw_set_option("tile_m", 0)
-    tw.tw_set_option("xcd_map", 1)
+    for k, v in (("tile_m", 0), ("xcd_map", 1), ("kernel", 0), ("depth", 3), ("waves", 4), ("ksplit", 0)):
+        tw.tw_set_option(k, v)
 
 
 def _check_case(c, tile_m=0, **kw):
