@@ -163,6 +163,12 @@ def main():
                                                             shp.N, M, shp.N, M, tw.LAYOUT_KM, stream)) * 1e-3
             d.update(dense_us=t_d * 1e6, dense_tflops=2.0 * M * shp.K * shp.N / t_d / 1e12,
                      speedup_vs_dense=t_d / t_sp)
+            # context only, never the baseline: the vendor GEMM behind torch.matmul on the
+            # same shape (row-major A, M x K), timed the same way
+            Arm = [x[2].t().contiguous() for x in [y for y in sets[0] if y[0] == si][:1]][0]
+            out_rm = torch.empty((M, shp.N), dtype=torch.float16, device=dev)
+            t_v = time_shape(si, lambda o: torch.matmul(Arm, Bd, out=out_rm)) * 1e-3
+            d.update(vendor_gemm_us=t_v * 1e6)
         detail[shp.name] = d
     if not args.no_dense:
         detail["step_speedup_vs_own_dense"] = (

@@ -74,7 +74,7 @@ __device__ __forceinline__ void zero_fill_column(const GemmArgs& g, int which) {
   _Float16* row = g.C + (size_t)col * g.ldc;
   const u32x4 z = {0u, 0u, 0u, 0u};
   for (int m = threadIdx.x * 8; m < g.M; m += (int)blockDim.x * 8) {
-    if (m + 8 <= g.M) *(u32x4*)(row + m) = z;
+    if (m + 8 <= g.M) __builtin_nontemporal_store(z, (u32x4*)(row + m));
     else for (int i = m; i < g.M; ++i) row[i] = (_Float16)0.f;
   }
 }

@@ -368,7 +368,9 @@ __global__ __launch_bounds__(NWAVES * 64) void tw_gemm_km_dma_kernel(GemmArgs g)
   }
   __syncthreads();
   TWG_STAMP_FINE();
-  // all staged chunks into registers first, then the stores back to back
+  // all staged chunks into registers first, then the stores back to back; C is
+  // written once and not read again here: streaming (non-temporal) stores keep it
+  // from lingering dirty in L2 until the end-of-kernel write-back
   union Chunk { uint2 h[2]; u32x4 v; };   // staging rows are 8-byte aligned only
   Chunk ck[NPASS];
 #pragma unroll
@@ -381,7 +383,7 @@ __global__ __launch_bounds__(NWAVES * 64) void tw_gemm_km_dma_kernel(GemmArgs g)
   for (int i = 0; i < NPASS; ++i) {
     if (dst_off[i] < 0) continue;
     _Float16* dst = g.C + dst_off[i];
-    if (m + 8 <= g.M) *(u32x4*)dst = ck[i].v;
+    if (m + 8 <= g.M) __builtin_nontemporal_store(ck[i].v, (u32x4*)dst);
     else {
       const int n = r0 + i * ROWS_PER_PASS;
       const _Float16* e = (const _Float16*)(lds + n * CS + c * 16);

@@ -292,7 +292,7 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
       for (int q = 0; q < 8 && m + q < g.M; ++q) g.C[(size_t)(m + q) * g.ldc + cols[i]] = e[q];
     } else {
       _Float16* dst = g.C + dst_off[i];
-      if (m + 8 <= g.M) *(u32x4*)dst = u.v;
+      if (m + 8 <= g.M) __builtin_nontemporal_store(u.v, (u32x4*)dst);
       else {
         const _Float16* e = (const _Float16*)(lds + n * CS + c * 16);
         for (int q = 0; m + q < g.M; ++q) dst[q] = e[q];

@@ -291,7 +291,7 @@ __global__ __launch_bounds__(NTHREADS) void tvw_gemm_km_kernel(GemmArgs g) {
   for (int i = 0; i < NPASS; ++i) {
     if (dst_off[i] < 0) continue;
     _Float16* dst = g.C + dst_off[i];
-    if (m + 8 <= g.M) *(u32x4*)dst = ck[i].v;
+    if (m + 8 <= g.M) __builtin_nontemporal_store(ck[i].v, (u32x4*)dst);
     else {
       const int n = r0 + i * ROWS_PER_PASS;
       const _Float16* e = (const _Float16*)(lds + n * CS + c * 16);
