@@ -38,12 +38,12 @@ PLAN = [(0, 4), (1, 1), (2, 1)]          # (shape index in the config, copies pe
 MEASURED_TRAFFIC_BYTES = {"tw": 26.26e6, "tvw": None}
 
 
-def algorithmic_bytes(M, K, N, pattern, sum_kw, sum_k):
-    """Bytes one launch must move: A once, all of C (pruned columns are written
-    as zeros), the condensed weight (TVW: half the values plus 4 position bits
-    per group and column) and its kept-row list."""
+def algorithmic_bytes(M, K_union, N, pattern, sum_kw, sum_k):
+    """Bytes one launch must move: the rows of A that some tile keeps, once; all
+    of C (pruned columns are written as zeros); the condensed weight (TVW: half
+    the values plus 4 position bits per group and column) and its kept-row list."""
     w = 2 * sum_kw if pattern == "tw" else sum_kw + sum_kw // 8
-    return 2 * M * K + 2 * M * N + w + 4 * sum_k
+    return 2 * M * K_union + 2 * M * N + w + 4 * sum_k
 
 
 def main():
@@ -91,9 +91,9 @@ def main():
                 t0 = time.perf_counter()
                 packed = tw.tw_pack(c.B, c.mask, c.G, pat, tile_mask=c.tile_mask if args.pattern == "tvw" else None)
                 t_pack += time.perf_counter() - t0
-                skw, sk = packed.flop_counts()
-                meta[si] = dict(K=shp.K, N=shp.N, sum_kw=skw, sum_k=sk, name=shp.name,
-                                alg=algorithmic_bytes(M, shp.K, shp.N, args.pattern, skw, sk))
+                skw, sk, ku = packed.flop_counts()
+                meta[si] = dict(K=shp.K, N=shp.N, sum_kw=skw, sum_k=sk, k_union=ku, name=shp.name,
+                                alg=algorithmic_bytes(M, ku, shp.N, args.pattern, skw, sk))
                 At = torch.randn((shp.K, M), generator=gen, dtype=torch.float32).to(torch.float16).to(dev)
                 Ct = torch.empty((shp.N, M), dtype=torch.float16, device=dev)
                 ops.append((si, packed, At, Ct))

@@ -170,11 +170,14 @@ const char* tw_status_str(int status);
  *   "ksplit"   0 = automatic, 1 = never, 2 = always split K between two wave groups
  *              of a workgroup (long K, few tiles)
  *   "depth"    stages in flight of the asynchronous pipeline: 3 (default) or 4
- * tw_flop_counts: condensed multiply-add work of a handle:
- *   *sum_kw = sum over tiles of K_t * W_t (kept-row x width products).
+ * tw_flop_counts: condensed work of a handle (any pointer may be NULL):
+ *   *sum_kw  = sum over tiles of K_t * W_t (kept-row x width products),
+ *   *sum_k   = sum over tiles of K_t,
+ *   *k_union = number of K rows kept by at least one tile (the rows of A a
+ *              launch has to read).
  */
 tw_status tw_set_option(const char* name, int value);
-tw_status tw_flop_counts(tw_handle_t h, int64_t* sum_kw, int64_t* sum_k);
+tw_status tw_flop_counts(tw_handle_t h, int64_t* sum_kw, int64_t* sum_k, int64_t* k_union);
 
 #ifdef __cplusplus
 }

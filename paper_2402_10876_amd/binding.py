@@ -64,7 +64,7 @@ def lib():
         L.tw_unpack.argtypes = [vp, vp, vp]
         L.tw_free.argtypes = [vp]
         L.tw_set_option.argtypes = [C.c_char_p, i]
-        L.tw_flop_counts.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
+        L.tw_flop_counts.argtypes = [vp, C.POINTER(C.c_int64), C.POINTER(C.c_int64), C.POINTER(C.c_int64)]
         for name in EXPORTED_SYMBOLS:
             if name != "tw_status_str":
                 getattr(L, name).restype = i
@@ -141,9 +141,10 @@ class PackedWeight:
         return Bm, mask
 
     def flop_counts(self):
-        a, b = C.c_int64(), C.c_int64()
-        _check(lib().tw_flop_counts(self.handle, C.byref(a), C.byref(b)), "tw_flop_counts")
-        return a.value, b.value
+        """(sum K_t*W_t, sum K_t, rows of A kept by at least one tile)."""
+        a, b, u = C.c_int64(), C.c_int64(), C.c_int64()
+        _check(lib().tw_flop_counts(self.handle, C.byref(a), C.byref(b), C.byref(u)), "tw_flop_counts")
+        return a.value, b.value, u.value
 
     def free(self):
         if self._h is not None:

@@ -22,17 +22,19 @@ bool valid_G(int G) { return G == 32 || G == 64 || G == 128; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 // M-tile heuristic: the largest tile that still gives every CU (256 of them)
-// about two workgroups; small problems fall back to smaller tiles.
-int pick_tile_m(int M, int n_tiles, int G) {
+// about two workgroups; long K loops (matrix-core bound) accept fewer, larger
+// workgroups, small problems fall back to smaller tiles.
+int pick_tile_m(int M, int n_tiles, int G, int max_k) {
   const int forced = opt_tile_m.load();
   if (forced == 64 || forced == 128 || forced == 256) {
     if (!(G == 32 && forced == 64)) return forced;
   }
+  const long need = max_k >= 768 ? 320 : 512;
   const int cand[3] = {256, 128, 64};
   for (int tm : cand) {
     if (G == 32 && tm == 64) break;
     const long wgs = (long)((M + tm - 1) / tm) * n_tiles;
-    if (wgs >= 512) return tm;
+    if (wgs >= need) return tm;
   }
   return G == 32 ? 128 : 64;
 }
@@ -160,13 +162,15 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
     if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
     return e == hipSuccess ? TW_OK : TW_ERR_HIP;
   }
-  const int tm = pick_tile_m(M, h->n_tiles > 0 ? h->n_tiles : 1, h->G);
+  const int tm = pick_tile_m(M, h->n_tiles > 0 ? h->n_tiles : 1, h->G, h->max_kp);
   hipError_t e = hipErrorInvalidValue;
   // the asynchronous kernel addresses A with 32-bit byte offsets
   const bool a_fits32 = (unsigned long long)h->K * (unsigned long long)lda * 2ull < (1ull << 32);
   if (opt_kernel.load() != 1 && h->G != 32 && a_fits32) {
     // long K with too few tiles to fill the chip: split K inside the workgroup
-    int variant = opt_waves.load() == 8 ? twg::DMA_WAVES8 : twg::DMA_WAVES4;
+    // 256-row tiles run with 8 waves (64 x 64 per wave): half the registers per wave, two
+    // workgroups per CU
+    int variant = (opt_waves.load() == 8 || (tm == 256 && h->G == 128)) ? twg::DMA_WAVES8 : twg::DMA_WAVES4;
     int tmk = tm;
     const int ks = opt_ksplit.load();
     if (ks == 2 || (ks == 0 && use_ksplit(M, h->n_tiles, h->max_kp, &tmk))) variant = twg::DMA_KSPLIT2;
@@ -204,12 +208,12 @@ tw_status tw_dense_gemm(const void* A, const void* B, void* C, int M, int K, int
     hipError_t em = twg::launch_dense_mk(tn, g, (hipStream_t)stream);
     return em == hipSuccess ? TW_OK : TW_ERR_HIP;
   }
-  const int tm = pick_tile_m(M, g.n_tiles, tn);
+  const int tm = pick_tile_m(M, g.n_tiles, tn, K);
   hipError_t e = hipErrorInvalidValue;
   const bool fits32 = (unsigned long long)K * (unsigned long long)lda * 2ull < (1ull << 32) &&
                       (unsigned long long)K * (unsigned long long)ldb * 2ull < (1ull << 32);
   if (opt_kernel.load() != 1 && K % 32 == 0 && fits32) {
-    int variant = opt_waves.load() == 8 ? twg::DMA_WAVES8 : twg::DMA_WAVES4;
+    int variant = (opt_waves.load() == 8 || tm == 256) ? twg::DMA_WAVES8 : twg::DMA_WAVES4;
     int tmk = tm;
     const int ks = opt_ksplit.load();
     if (K % 64 == 0 && (ks == 2 || (ks == 0 && use_ksplit(M, g.n_tiles, K, &tmk)))) variant = twg::DMA_KSPLIT2;
@@ -263,10 +267,11 @@ tw_status tw_set_option(const char* name, int value) {
   return TW_ERR_ARG;
 }
 
-tw_status tw_flop_counts(tw_handle_t h, int64_t* sum_kw, int64_t* sum_k) {
+tw_status tw_flop_counts(tw_handle_t h, int64_t* sum_kw, int64_t* sum_k, int64_t* k_union) {
   if (!h) return TW_ERR_ARG;
   if (sum_kw) *sum_kw = h->sum_kw;
   if (sum_k) *sum_k = h->sum_k;
+  if (k_union) *k_union = h->k_union;
   return TW_OK;
 }
 

@@ -100,6 +100,12 @@ tw_status pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_
       h->meta_off[t + 1] = h->meta_off[t] + (int64_t)ng * w;
     }
   }
+  {
+    std::vector<uint8_t> used(K, 0);
+    for (int32_t r : h->row_idx) used[r] = 1;
+    h->k_union = 0;
+    for (int k = 0; k < K; ++k) h->k_union += used[k];
+  }
   h->values.assign((size_t)h->val_off[h->n_tiles], 0);
   if (!tvw) {
     for (int t = 0; t < h->n_tiles; ++t) {

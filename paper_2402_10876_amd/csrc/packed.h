@@ -49,6 +49,7 @@ struct tw_handle_s {
   std::vector<uint16_t> values;
   std::vector<uint8_t> meta, valid;
   int64_t sum_kw = 0, sum_k = 0;
+  int32_t k_union = 0;  // K rows kept by at least one tile
   int32_t max_kp = 0;  // largest padded K_t
   twg::DeviceImage img;
 };

@@ -1,0 +1,119 @@
+"""Timing sweep over the configured workloads: python -m paper_2402_10876_amd.sweep [--configs 2,3,4,5]
+
+For every (layer shape, pattern, sparsity, G) it times the sparse launch and our
+dense baseline back to back on rotating buffer sets (operands from HBM) and
+prints one JSON line with dense-equivalent TFLOP/s, condensed-FLOP matrix-core
+utilisation, speed-up over the dense baseline and the fraction of the binding
+roofline (vendor peaks: 8 TB/s, 2.5 PFLOP/s fp16 dense).  `--cube` adds the
+paper's 4096 x 4096 x 4096 sparsity sweep (Section VI-B).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import sys
+
+import numpy as np
+
+HBM = 8.0e12
+MFMA = 2.5e15
+
+
+def alg_bytes(M, K_union, N, pattern, skw, sk):
+    """A rows kept by some tile + all of C + condensed weight + kept-row lists."""
+    w = 2 * skw if pattern == "tw" else skw + skw // 8
+    return 2 * M * K_union + 2 * M * N + w + 4 * sk
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--configs", default="2,3,4,5")
+    ap.add_argument("--cube", action="store_true")
+    ap.add_argument("--reps", type=int, default=24)
+    ap.add_argument("--sets", type=int, default=6)
+    args = ap.parse_args()
+
+    import torch
+    import paper_2402_10876_amd as tw
+    import workloads as wl
+
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def timed(fn, reps, rounds=3):
+        vals = []
+        for _ in range(rounds):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for r in range(reps):
+                fn(r)
+            e1.record()
+            torch.cuda.synchronize()
+            vals.append(e0.elapsed_time(e1) / reps * 1e-3)
+        return float(np.median(vals))
+
+    plan = []
+    cfgs = [int(c) for c in args.configs.split(",") if c]
+    for cfg in cfgs:
+        for si in range(len(wl.SHAPES[cfg])):
+            if cfg == 2:
+                plan.append((cfg, si, "tw", 0.75, 128))
+            elif cfg == 3:
+                plan.append((cfg, si, "tvw", 0.875, 128))
+            elif cfg == 4:
+                for sp in (0.0, 0.5, 0.75, 0.875, 0.9375):
+                    plan.append((cfg, si, "tw", sp, 128))
+                for sp in (0.5, 0.75, 0.875, 0.9375):
+                    plan.append((cfg, si, "tvw", sp, 128))
+            elif cfg == 5:
+                plan += [(cfg, si, "tw", 0.75, 64), (cfg, si, "tw", 0.75, 128),
+                         (cfg, si, "tvw", 0.875, 64), (cfg, si, "tvw", 0.875, 128)]
+    if args.cube:
+        wl.SHAPES[6] = [wl.Shape("cube_4096", 4096, 4096, 4096, 0.02)]
+        wl.CONFIGS[6] = dict(G=128, pattern="tw", sparsity=0.75, col_frac=0.10)
+        for sp in (0.0, 0.1, 0.25, 0.5, 0.75, 0.875):
+            plan.append((6, 0, "tw", sp, 128))
+            plan.append((6, 0, "tw", sp, 64))
+        for sp in (0.5, 0.75, 0.875):
+            plan.append((6, 0, "tvw", sp, 128))
+
+    dense_cache = {}
+    for cfg, si, pattern, sp, G in plan:
+        shp = wl.SHAPES[cfg][si]
+        M, K, N = shp.M, shp.K, shp.N
+        nsets = max(2, min(args.sets, int(600e6 // (2 * M * (K + N)))))
+        cf = 0.0 if sp == 0.0 or (pattern == "tvw" and sp == 0.5) else None
+        c = wl.make_case(cfg, si, pattern=pattern, sparsity=sp, G=G, col_frac=cf, with_A=False)
+        pat = tw.PATTERN_TW if pattern == "tw" else tw.PATTERN_TVW
+        packed = [tw.tw_pack(c.B, c.mask, G, pat, tile_mask=c.tile_mask if pattern == "tvw" else None)
+                  for _ in range(nsets)]
+        A = [torch.randn((K, M), dtype=torch.float16, device=dev) for _ in range(nsets)]
+        C = [torch.empty((N, M), dtype=torch.float16, device=dev) for _ in range(nsets)]
+        skw, sk, ku = packed[0].flop_counts()
+        t = timed(lambda r: tw.tw_gemm(A[r % nsets].data_ptr(), M, M, tw.LAYOUT_KM, packed[r % nsets],
+                                       C[r % nsets].data_ptr(), M, stream), args.reps)
+        key = (cfg, si)
+        if key not in dense_cache:
+            Bd = torch.from_numpy(c.B).to(dev)
+            dense_cache[key] = timed(lambda r: tw.tw_dense_gemm(A[r % nsets].data_ptr(), Bd.data_ptr(),
+                                                                C[r % nsets].data_ptr(), M, K, N, M, N, M,
+                                                                tw.LAYOUT_KM, stream), args.reps)
+        td = dense_cache[key]
+        ab = alg_bytes(M, ku, N, pattern, skw, sk)
+        issued = 2.0 * M * skw if pattern == "tw" else 1.0 * M * skw
+        t_hbm, t_mfma = ab / HBM, issued / MFMA
+        print(json.dumps(dict(
+            shape=shp.name, M=M, K=K, N=N, G=G, pattern=pattern, sparsity=sp, K_union=ku,
+            us=round(t * 1e6, 2), dense_us=round(td * 1e6, 2), speedup_vs_dense=round(td / t, 3),
+            dense_eq_tflops=round(2.0 * M * K * N / t / 1e12, 1),
+            condensed_mfma_util=round(2.0 * M * skw / t / MFMA, 4),
+            alg_MB=round(ab / 1e6, 2), alg_GBps=round(ab / t / 1e9, 1),
+            bound="hbm" if t_hbm >= t_mfma else "mfma",
+            roofline_frac=round(max(t_hbm, t_mfma) / t, 4))), flush=True)
+        for p in packed:
+            p.free()
+        del A, C
+
+
+if __name__ == "__main__":
+    sys.exit(main())

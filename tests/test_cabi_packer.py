@@ -50,8 +50,9 @@ def test_tw_export_equals_oracle_pack(seed):
     Bm, m2 = p.unpack()
     assert np.array_equal(m2, mask)
     assert np.array_equal(Bm, np.where(mask != 0, B.view(np.uint16), 0))
-    skw, sk = p.flop_counts()
+    skw, sk, ku = p.flop_counts()
     assert skw == int(mask.sum()) and sk == sum(len(r) for r in p.export()["row_idx"])
+    assert ku == int(mask.any(axis=1).sum())
     p.free()
 
 
