@@ -35,7 +35,7 @@ PLAN = [(0, 4), (1, 1), (2, 1)]          # (shape index in the config, copies pe
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) summarised under profiles/, scaled by
 # what the same counters read for a plain 256 MiB device copy.  A measurement that
 # cannot be taken from inside this script: None where no such run has been made.
-MEASURED_TRAFFIC_BYTES = {"tw": 26.26e6, "tvw": None}
+MEASURED_TRAFFIC_BYTES = {"tw": 23.31e6, "tvw": None}
 
 
 def algorithmic_bytes(M, K_union, N, pattern, sum_kw, sum_k):
@@ -55,6 +55,8 @@ def main():
     ap.add_argument("--pattern", default="tw", choices=["tw", "tvw"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--xcd-map", type=int, default=1, choices=[0, 1],
+                    help="0 switches the XCD-aware workgroup order off (for counter comparisons)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain device copies of 256 MiB (counter calibration under rocprofv3 --pmc)")
     args = ap.parse_args()
@@ -68,6 +70,7 @@ def main():
     import workloads as wl
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    tw.tw_set_option("xcd_map", args.xcd_map)
     dev = torch.device("cuda:0")
     cfg = 2 if args.pattern == "tw" else 3
     shapes = wl.SHAPES[cfg]
