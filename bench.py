@@ -35,7 +35,7 @@ PLAN = [(0, 4), (1, 1), (2, 1)]          # (shape index in the config, copies pe
 # rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) summarised under profiles/, scaled by
 # what the same counters read for a plain 256 MiB device copy.  A measurement that
 # cannot be taken from inside this script: None where no such run has been made.
-MEASURED_TRAFFIC_BYTES = {"tw": 23.31e6, "tvw": None}
+MEASURED_TRAFFIC_BYTES = {"tw": 23.31e6, "tvw": 21.36e6}
 
 
 def algorithmic_bytes(M, K_union, N, pattern, sum_kw, sum_k):
