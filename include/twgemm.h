@@ -73,8 +73,11 @@ typedef enum { TW_LAYOUT_KM = 0, TW_LAYOUT_MK = 1 } tw_layout;
  *   tile_k_off[n_tiles+1] prefix sums of K_t, the kept-row count of tile t
  *   row_idx[sum K_t]      per tile, ascending original K indices        (CTO_k as indices)
  *   cto_k[sum K_t]        row_idx[tile t][j] - j
- *   Tile t covers condensed columns [t*G, min((t+1)*G, n_kept)), width W_t.
- *   TW : values at val_off[t]: K_t x W_t row-major, V[j][w] = B[row_idx[t][j]][col_idx[t*G+w]]
+ *   tile_col_off[n_tiles+1]  tile t covers condensed columns [tile_col_off[t],
+ *        tile_col_off[t+1]), width W_t <= G.  From tw_pack: tile_col_off[t] =
+ *        min(t*G, n_kept); a handle from tw_concat keeps its members' tile bounds.
+ *   TW : values at val_off[t]: K_t x W_t row-major,
+ *        V[j][w] = B[row_idx[t][j]][col_idx[tile_col_off[t]+w]]
  *   TVW: groups of 4 consecutive entries of row_idx[t]; n_g = ceil(K_t/4).
  *        values at val_off[t]: n_g x 2 x W_t; meta/valid at meta_off[t]: n_g x W_t bytes.
  *        meta  = p0 | p1<<2 with p0 < p1 the two stored positions of the group,
@@ -94,6 +97,7 @@ typedef struct {
   const int64_t* meta_off;  /* n_tiles+1, in bytes; NULL for TW */
   const uint8_t* meta;      /* NULL for TW */
   const uint8_t* valid;     /* NULL for TW */
+  const int32_t* tile_col_off;
 } tw_packed_view;
 
 /*
@@ -121,6 +125,21 @@ tw_status tw_upload(tw_handle_t h);
 tw_status tw_pack(const uint16_t* B_host, const uint8_t* mask_host,
                   const uint8_t* tile_mask_host, int K, int N, int G,
                   int pattern, tw_handle_t* out);
+
+/*
+ * tw_concat - one handle for the weights parts[0..n) side by side along N:
+ * B = [B_0 | B_1 | ...] (same K, G and pattern; N = sum of the members' N).
+ * A tw_gemm on it computes the members' products from one read of A in one
+ * launch, which is how independent GEMMs on the same input (the Q, K and V
+ * projections of an attention layer) fill the device together; Section V
+ * ("Tile Fusion") runs a weight's tiles concurrently for the same reason.
+ * The members' tiles are kept as they are (no tile spans two members), so
+ * rows [N_0 + .. + N_{i-1}, .. + N_i) of C (KM layout) are member i's C.
+ * The members stay valid and independent.  upload != 0 also copies the device
+ * image to the current device.  Errors: TW_ERR_ARG (null, n < 1, members
+ * differ in K, G or pattern), TW_ERR_ALLOC, TW_ERR_HIP.
+ */
+tw_status tw_concat(const tw_handle_t* parts, int n, int upload, tw_handle_t* out);
 
 /*
  * tw_gemm - C = A . (B (.) mask) for a packed weight (Listing 1 as one grouped

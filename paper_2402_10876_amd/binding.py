@@ -13,7 +13,7 @@ PATTERN_TW, PATTERN_TVW = 0, 1
 LAYOUT_KM, LAYOUT_MK = 0, 1
 
 EXPORTED_SYMBOLS = [
-    "tw_pack_host", "tw_upload", "tw_pack", "tw_gemm", "tw_dense_gemm", "tw_export",
+    "tw_pack_host", "tw_upload", "tw_pack", "tw_concat", "tw_gemm", "tw_dense_gemm", "tw_export",
     "tw_unpack", "tw_free", "tw_status_str", "tw_set_option", "tw_flop_counts",
 ]
 
@@ -33,7 +33,8 @@ class _View(C.Structure):
                 ("tile_k_off", C.POINTER(C.c_int32)), ("row_idx", C.POINTER(C.c_int32)),
                 ("cto_k", C.POINTER(C.c_int32)), ("val_off", C.POINTER(C.c_int64)),
                 ("values", C.POINTER(C.c_uint16)), ("meta_off", C.POINTER(C.c_int64)),
-                ("meta", C.POINTER(C.c_uint8)), ("valid", C.POINTER(C.c_uint8))]
+                ("meta", C.POINTER(C.c_uint8)), ("valid", C.POINTER(C.c_uint8)),
+                ("tile_col_off", C.POINTER(C.c_int32))]
 
 
 def lib_path() -> str:
@@ -58,6 +59,7 @@ def lib():
         L.tw_pack_host.argtypes = [vp, vp, vp, i, i, i, i, C.POINTER(vp)]
         L.tw_pack.argtypes = L.tw_pack_host.argtypes
         L.tw_upload.argtypes = [vp]
+        L.tw_concat.argtypes = [C.POINTER(vp), i, i, C.POINTER(vp)]
         L.tw_gemm.argtypes = [vp, i, i, i, vp, vp, i, vp]
         L.tw_dense_gemm.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, vp]
         L.tw_export.argtypes = [vp, C.POINTER(_View)]
@@ -118,7 +120,9 @@ class PackedWeight:
                    col_idx=arr(v.col_idx, nk, np.int32), cto_n=arr(v.cto_n, nk, np.int32),
                    row_idx=[rows[tko[t]:tko[t + 1]] for t in range(nt)],
                    cto_k=[ctok[tko[t]:tko[t + 1]] for t in range(nt)])
-        widths = [min(v.G, nk - t * v.G) for t in range(nt)]
+        tco = arr(v.tile_col_off, nt + 1, np.int32)
+        out["tile_col_off"] = tco
+        widths = [int(tco[t + 1] - tco[t]) for t in range(nt)]
         if v.pattern == PATTERN_TW:
             out["values"] = [vals[voff[t]:voff[t + 1]].reshape(int(tko[t + 1] - tko[t]), widths[t])
                              for t in range(nt)]
@@ -183,6 +187,14 @@ def tw_pack_host(B16, mask, G, pattern, tile_mask=None) -> PackedWeight:
 
 def tw_pack(B16, mask, G, pattern, tile_mask=None) -> PackedWeight:
     return _pack("tw_pack", B16, mask, G, pattern, tile_mask)
+
+
+def tw_concat(parts, upload: bool = True) -> PackedWeight:
+    """One handle for the packed weights `parts` side by side along N."""
+    arr = (C.c_void_p * len(parts))(*[p.handle for p in parts])
+    h = C.c_void_p()
+    _check(lib().tw_concat(arr, len(parts), int(bool(upload)), C.byref(h)), "tw_concat")
+    return PackedWeight(h)
 
 
 def tw_gemm(A_ptr: int, M: int, lda: int, layout: int, packed: PackedWeight, C_ptr: int,

@@ -127,6 +127,21 @@ tw_status tw_pack(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_ma
   return st;
 }
 
+tw_status tw_concat(const tw_handle_t* parts, int n, int upload, tw_handle_t* out) {
+  if (!out) return TW_ERR_ARG;
+  *out = nullptr;
+  if (!parts || n < 1) return TW_ERR_ARG;
+  for (int i = 0; i < n; ++i)
+    if (!parts[i]) return TW_ERR_ARG;
+  tw_handle_s* h = new (std::nothrow) tw_handle_s();
+  if (!h) return TW_ERR_ALLOC;
+  tw_status st = twg::concat_host(parts, n, h);
+  if (st == TW_OK && upload) st = tw_upload(h);
+  if (st != TW_OK) { tw_free(h); return st; }
+  *out = h;
+  return TW_OK;
+}
+
 tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void* C, int ldc,
                   void* stream) {
   if (!A || !C || !h || M < 1) return TW_ERR_ARG;
@@ -237,6 +252,7 @@ tw_status tw_export(tw_handle_t h, tw_packed_view* out) {
   out->col_idx = h->col_idx.data(); out->cto_n = h->cto_n.data();
   out->tile_k_off = h->tile_k_off.data(); out->row_idx = h->row_idx.data();
   out->cto_k = h->cto_k.data(); out->val_off = h->val_off.data(); out->values = h->values.data();
+  out->tile_col_off = h->tile_col_off.data();
   if (h->pattern == TW_PATTERN_TVW) {
     out->meta_off = h->meta_off.data(); out->meta = h->meta.data(); out->valid = h->valid.data();
   }

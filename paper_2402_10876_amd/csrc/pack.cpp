@@ -73,6 +73,8 @@ tw_status pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_
   structure_of(S, K, N, G, h->col_idx, h->tile_k_off, h->row_idx);
   h->n_kept = (int32_t)h->col_idx.size();
   h->n_tiles = (int32_t)h->tile_k_off.size() - 1;
+  h->tile_col_off.resize(h->n_tiles + 1);
+  for (int t = 0; t <= h->n_tiles; ++t) h->tile_col_off[t] = std::min(t * G, h->n_kept);
   if (!tvw || tile_mask) {
     if (!is_tile_wise(S, K, N, G, h->col_idx, h->tile_k_off)) return TW_ERR_MASK;
   }
@@ -88,7 +90,7 @@ tw_status pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_
   h->sum_kw = 0; h->sum_k = 0;
   for (int t = 0; t < h->n_tiles; ++t) {
     const int k0 = h->tile_k_off[t], kt = h->tile_k_off[t + 1] - k0;
-    const int w = std::min(G, h->n_kept - t * G);
+    const int w = h->tile_col_off[t + 1] - h->tile_col_off[t];
     for (int j = 0; j < kt; ++j) h->cto_k[k0 + j] = h->row_idx[k0 + j] - j;
     h->sum_kw += (int64_t)kt * w;
     h->sum_k += kt;
@@ -110,9 +112,9 @@ tw_status pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_
   if (!tvw) {
     for (int t = 0; t < h->n_tiles; ++t) {
       const int k0 = h->tile_k_off[t], kt = h->tile_k_off[t + 1] - k0;
-      const int w = std::min(G, h->n_kept - t * G);
+      const int w = h->tile_col_off[t + 1] - h->tile_col_off[t];
       uint16_t* v = h->values.data() + h->val_off[t];
-      const int32_t* cols = h->col_idx.data() + (size_t)t * G;
+      const int32_t* cols = h->col_idx.data() + h->tile_col_off[t];
       for (int j = 0; j < kt; ++j) {
         const uint16_t* brow = B + (size_t)h->row_idx[k0 + j] * N;
         for (int c = 0; c < w; ++c) v[(size_t)j * w + c] = brow[cols[c]];
@@ -123,12 +125,12 @@ tw_status pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_
     h->valid.assign((size_t)h->meta_off[h->n_tiles], 0);
     for (int t = 0; t < h->n_tiles; ++t) {
       const int k0 = h->tile_k_off[t], kt = h->tile_k_off[t + 1] - k0;
-      const int w = std::min(G, h->n_kept - t * G);
+      const int w = h->tile_col_off[t + 1] - h->tile_col_off[t];
       const int ng = (kt + 3) / 4;
       uint16_t* v = h->values.data() + h->val_off[t];
       uint8_t* me = h->meta.data() + h->meta_off[t];
       uint8_t* va = h->valid.data() + h->meta_off[t];
-      const int32_t* cols = h->col_idx.data() + (size_t)t * G;
+      const int32_t* cols = h->col_idx.data() + h->tile_col_off[t];
       for (int g = 0; g < ng; ++g) {
         const int glen = std::min(4, kt - 4 * g);
         for (int c = 0; c < w; ++c) {
@@ -168,9 +170,9 @@ tw_status unpack_host(const tw_handle_s* h, uint16_t* Bm, uint8_t* mask) {
   if (mask) std::memset(mask, 0, total);
   for (int t = 0; t < h->n_tiles; ++t) {
     const int k0 = h->tile_k_off[t], kt = h->tile_k_off[t + 1] - k0;
-    const int w = std::min(h->G, h->n_kept - t * h->G);
+    const int w = h->tile_col_off[t + 1] - h->tile_col_off[t];
     const uint16_t* v = h->values.data() + h->val_off[t];
-    const int32_t* cols = h->col_idx.data() + (size_t)t * h->G;
+    const int32_t* cols = h->col_idx.data() + h->tile_col_off[t];
     if (h->pattern == TW_PATTERN_TW) {
       for (int j = 0; j < kt; ++j) {
         const size_t row = (size_t)h->row_idx[k0 + j] * h->N;
@@ -197,6 +199,46 @@ tw_status unpack_host(const tw_handle_s* h, uint16_t* Bm, uint8_t* mask) {
   return TW_OK;
 }
 
+// Concatenation along N: the members' tiles, kept-row lists and condensed blocks
+// follow one another unchanged; only the column indices move by the summed N of
+// the members before.
+tw_status concat_host(const tw_handle_s* const* parts, int n, tw_handle_s* h) try {
+  const tw_handle_s* p0 = parts[0];
+  h->K = p0->K; h->G = p0->G; h->pattern = p0->pattern;
+  h->N = 0; h->n_kept = 0; h->n_tiles = 0; h->sum_kw = 0; h->sum_k = 0;
+  h->tile_col_off.assign(1, 0); h->tile_k_off.assign(1, 0);
+  h->val_off.assign(1, 0); h->meta_off.assign(1, 0);
+  for (int i = 0; i < n; ++i) {
+    const tw_handle_s* p = parts[i];
+    if (p->K != h->K || p->G != h->G || p->pattern != h->pattern) return TW_ERR_ARG;
+    if ((int64_t)h->N + p->N > INT32_MAX) return TW_ERR_ARG;
+    for (int32_t c : p->col_idx) h->col_idx.push_back(c + h->N);
+    for (int t = 0; t < p->n_tiles; ++t) {
+      h->tile_col_off.push_back(h->n_kept + p->tile_col_off[t + 1]);
+      h->tile_k_off.push_back((int32_t)h->sum_k + p->tile_k_off[t + 1]);
+      h->val_off.push_back((int64_t)h->values.size() + p->val_off[t + 1]);
+      h->meta_off.push_back((int64_t)h->meta.size() + p->meta_off[t + 1]);
+    }
+    h->row_idx.insert(h->row_idx.end(), p->row_idx.begin(), p->row_idx.end());
+    h->cto_k.insert(h->cto_k.end(), p->cto_k.begin(), p->cto_k.end());
+    h->values.insert(h->values.end(), p->values.begin(), p->values.end());
+    h->meta.insert(h->meta.end(), p->meta.begin(), p->meta.end());
+    h->valid.insert(h->valid.end(), p->valid.begin(), p->valid.end());
+    h->N += p->N; h->n_kept += p->n_kept; h->n_tiles += p->n_tiles;
+    h->sum_kw += p->sum_kw; h->sum_k += p->sum_k;
+  }
+  h->cto_n.resize(h->n_kept);
+  for (int j = 0; j < h->n_kept; ++j) h->cto_n[j] = h->col_idx[j] - j;
+  std::vector<uint8_t> used(h->K, 0);
+  for (int32_t r : h->row_idx) used[r] = 1;
+  h->k_union = 0;
+  for (int k = 0; k < h->K; ++k) h->k_union += used[k];
+  build_device_image(h);
+  return TW_OK;
+} catch (const std::bad_alloc&) {
+  return TW_ERR_ALLOC;
+}
+
 // ---------------------------------------------------------------------------
 // Device image.
 //
@@ -219,7 +261,9 @@ void build_device_image(tw_handle_s* h) {
   const bool tvw = h->pattern == TW_PATTERN_TVW;
   const int kstep = tvw ? KSTEP_TVW : KSTEP_TW;
   d.col_idx.assign((size_t)nt * G, -1);
-  std::copy(h->col_idx.begin(), h->col_idx.end(), d.col_idx.begin());
+  for (int t = 0; t < nt; ++t)
+    std::copy(h->col_idx.begin() + h->tile_col_off[t], h->col_idx.begin() + h->tile_col_off[t + 1],
+              d.col_idx.begin() + (size_t)t * G);
   d.tile_kp_off.assign(nt + 1, 0);
   h->max_kp = 0;
   for (int t = 0; t < nt; ++t) {
@@ -256,13 +300,13 @@ void build_device_image(tw_handle_s* h) {
     d.tile_sched[4 * pos + 0] = t;
     d.tile_sched[4 * pos + 1] = d.tile_kp_off[t];
     d.tile_sched[4 * pos + 2] = d.tile_kp_off[t + 1] - d.tile_kp_off[t];
-    d.tile_sched[4 * pos + 3] = std::min(G, h->n_kept - t * G);
+    d.tile_sched[4 * pos + 3] = h->tile_col_off[t + 1] - h->tile_col_off[t];
   }
   if (!tvw) {
     d.vals.assign(((size_t)d.tile_kp_off[nt] + KSTEP_TW) * G, 0);
     for (int t = 0; t < nt; ++t) {
       const int kt = h->tile_k_off[t + 1] - h->tile_k_off[t];
-      const int w = std::min(G, h->n_kept - t * G);
+      const int w = h->tile_col_off[t + 1] - h->tile_col_off[t];
       const uint16_t* v = h->values.data() + h->val_off[t];
       uint16_t* o = d.vals.data() + (size_t)d.tile_kp_off[t] * G;
       for (int j = 0; j < kt; ++j)
@@ -278,7 +322,7 @@ void build_device_image(tw_handle_s* h) {
   for (int t = 0; t < nt; ++t) {
     const int kt = h->tile_k_off[t + 1] - h->tile_k_off[t];
     const int ng = (kt + 3) / 4;
-    const int w = std::min(G, h->n_kept - t * G);
+    const int w = h->tile_col_off[t + 1] - h->tile_col_off[t];
     const int kp0 = d.tile_kp_off[t], kp = d.tile_kp_off[t + 1] - kp0;
     const uint16_t* v = h->values.data() + h->val_off[t];
     const uint8_t* me = h->meta.data() + h->meta_off[t];

@@ -44,7 +44,7 @@ struct DeviceImage {
 struct tw_handle_s {
   int32_t K = 0, N = 0, G = 0, pattern = 0;
   int32_t n_kept = 0, n_tiles = 0;
-  std::vector<int32_t> col_idx, cto_n, tile_k_off, row_idx, cto_k;
+  std::vector<int32_t> col_idx, cto_n, tile_col_off, tile_k_off, row_idx, cto_k;
   std::vector<int64_t> val_off, meta_off;
   std::vector<uint16_t> values;
   std::vector<uint8_t> meta, valid;
@@ -59,6 +59,8 @@ namespace twg {
 tw_status pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_mask,
                     int K, int N, int G, int pattern, tw_handle_s* h);
 tw_status unpack_host(const tw_handle_s* h, uint16_t* Bm, uint8_t* mask);
+// Fills *h with parts[0..n) side by side along N (same K, G and pattern).
+tw_status concat_host(const tw_handle_s* const* parts, int n, tw_handle_s* h);
 // Builds h->img host staging from the logical form.
 void build_device_image(tw_handle_s* h);
 }  // namespace twg
