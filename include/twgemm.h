@@ -182,7 +182,9 @@ const char* tw_status_str(int status);
  * tw_dense_gemm call.  Unknown names give TW_ERR_ARG.
  *   "tile_m"   0 = heuristic, else force the M-tile (64, 128 or 256)
  *   "xcd_map"  1 (default) = remap workgroup ids so that one XCD walks all
- *              N-tiles of an M-band; 0 = plain order
+ *              N-tiles of an M-band; 0 = plain order; 2 = as 1, and the
+ *              workgroups that start together on one CU share a weight tile
+ *              (measured within 2 % of mode 1 either way)
  *   "kernel"   0 = automatic, 1 = register-staged pipeline, 2 = asynchronous
  *              global->LDS copy pipeline (TW_ERR_UNSUPPORTED where it has no instance)
  *   "waves"    4 (default) or 8 waves per workgroup in the asynchronous pipeline

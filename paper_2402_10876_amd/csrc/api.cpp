@@ -275,7 +275,7 @@ tw_status tw_free(tw_handle_t h) {
 tw_status tw_set_option(const char* name, int value) {
   if (!name) return TW_ERR_ARG;
   if (!std::strcmp(name, "tile_m")) { opt_tile_m.store(value); return TW_OK; }
-  if (!std::strcmp(name, "xcd_map")) { opt_xcd_map.store(value != 0); return TW_OK; }
+  if (!std::strcmp(name, "xcd_map")) { opt_xcd_map.store(value < 0 || value > 2 ? 1 : value); return TW_OK; }
   if (!std::strcmp(name, "kernel")) { opt_kernel.store(value); return TW_OK; }
   if (!std::strcmp(name, "waves")) { opt_waves.store(value == 8 ? 8 : 4); return TW_OK; }
   if (!std::strcmp(name, "ksplit")) { opt_ksplit.store(value); return TW_OK; }

@@ -25,9 +25,19 @@ constexpr int NTHREADS = 256;
 #ifdef TWG_TRACE
 constexpr int TRACE_WGS = 2048, TRACE_SLOTS = 48;
 static __device__ unsigned long long twg_trace[2 * TRACE_WGS * TRACE_SLOTS];  // one per source file; two launches
+#if TWG_TRACE >= 2   // slot 0: where the workgroup runs (HW_ID, XCC_ID hardware registers)
+#define TWG_TRACE_INIT()                                         \
+  const bool trace_on = threadIdx.x == 0 && blockIdx.x < TRACE_WGS; \
+  int trace_n = 0;                                                  \
+  if (trace_on)                                                     \
+    twg_trace[(g.trace_slot * TRACE_WGS + blockIdx.x) * TRACE_SLOTS + trace_n++] =                    \
+        (unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 4) |                                \
+        ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32)
+#else
 #define TWG_TRACE_INIT()                                         \
   const bool trace_on = threadIdx.x == 0 && blockIdx.x < TRACE_WGS; \
   int trace_n = 0
+#endif
 #define TWG_STAMP()                                                                   \
   do {                                                                                \
     if (trace_on && trace_n < TRACE_SLOTS)                                            \
@@ -66,6 +76,30 @@ __device__ __forceinline__ int xcd_remap(int bid, int n) {
   const int xcd = bid & 7, slot = bid >> 3;
   const int per = n >> 3, rem = n & 7;
   return (xcd < rem) ? xcd * (per + 1) + slot : rem * (per + 1) + (xcd - rem) * per + slot;
+}
+
+// Workgroup id -> (M-tile, launch position of the N-tile).
+// mode 1: the XCD's contiguous range of logical ids, M-tile major.
+// mode 2 (when the M-tiles divide evenly among the 8 XCDs): inside the XCD the
+// ids are tile major and dealt so that the workgroups that start together on
+// one CU (an idle XCD places its workgroups round-robin over its 32 CUs, so
+// these are XCD-local slots s, s+32, s+64, ..) are consecutive: they work on
+// the same weight tile at the same pace, and its rows are fetched from L2 once
+// per CU rather than once per workgroup.
+__device__ __forceinline__ void tile_of_workgroup(const GemmArgs& g, int bid, int n_gemm, int& mt, int& t) {
+  if (g.xcd_map == 2 && (g.n_mtiles & 7) == 0) {
+    const int xcd = bid & 7, slot = bid >> 3;
+    const int mts = g.n_mtiles >> 3, cnt = mts * g.n_tiles;
+    const int cu = slot & 31, round = slot >> 5;
+    const int rf = cnt >> 5, rn = cnt & 31;
+    const int L = cu * rf + (cu < rn ? cu : rn) + round;
+    t = L / mts;
+    mt = xcd * mts + (L - t * mts);
+    return;
+  }
+  const int lid = g.xcd_map ? xcd_remap(bid, n_gemm) : bid;
+  mt = lid / g.n_tiles;
+  t = lid - mt * g.n_tiles;
 }
 
 // Extra workgroups of a launch write +0 into one pruned column of C each.

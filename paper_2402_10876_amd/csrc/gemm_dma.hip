@@ -119,9 +119,8 @@ __global__ __launch_bounds__(NWAVES * 64) void tw_gemm_km_dma_kernel(GemmArgs g)
     zero_fill_column(g, blockIdx.x - n_gemm);
     return;
   }
-  const int lid = g.xcd_map ? xcd_remap(blockIdx.x, n_gemm) : (int)blockIdx.x;
-  const int mt = lid / g.n_tiles;
-  int t = lid - mt * g.n_tiles;          // launch position of the tile, then the tile itself
+  int mt, t;                             // t: launch position of the tile, then the tile itself
+  tile_of_workgroup(g, blockIdx.x, n_gemm, mt, t);
   const int m0 = mt * TM;
 
   int kp0, ns32;                                       // ns32: stages of 32 rows

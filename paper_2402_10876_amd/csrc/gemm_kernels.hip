@@ -78,9 +78,8 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
 
   // ---- workgroup -> (M-tile, N-tile): one XCD walks all N-tiles of an M-band
   // out of its own L2.
-  const int lid = g.xcd_map ? xcd_remap(blockIdx.x, n_gemm) : (int)blockIdx.x;
-  const int mt = lid / g.n_tiles;
-  int t = lid - mt * g.n_tiles;
+  int mt, t;
+  tile_of_workgroup(g, blockIdx.x, n_gemm, mt, t);
   if (!DENSE && g.tile_order) t = g.tile_order[t];
   const int m0 = mt * TM;
 

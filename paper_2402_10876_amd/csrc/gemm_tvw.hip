@@ -104,9 +104,9 @@ __global__ __launch_bounds__(NTHREADS) void tvw_gemm_km_kernel(GemmArgs g) {
     zero_fill_column(g, blockIdx.x - n_gemm);
     return;
   }
-  const int lid = g.xcd_map ? xcd_remap(blockIdx.x, n_gemm) : (int)blockIdx.x;
-  const int mt = lid / g.n_tiles;
-  const int4v rec = scalar_load4(g.tile_sched + 4 * (lid - mt * g.n_tiles));
+  int mt, pos;
+  tile_of_workgroup(g, blockIdx.x, n_gemm, mt, pos);
+  const int4v rec = scalar_load4(g.tile_sched + 4 * pos);
   const int t = rec[0], kp0 = rec[1], ns = rec[2] / KS2;
   const int m0 = mt * TM;
   // this tile's compressed values and position words

@@ -118,12 +118,16 @@ def test_dense_baseline(M, K, N):
         assert_C_close(C, og.gemm_oracle(A, B, ones), og.abs_bound(A, B, ones))
 
 
-def test_xcd_map_off_gives_same_result():
-    c = wl.make_case(2, 0, M=1024)
+@pytest.mark.parametrize("M", [1024, 1000])      # M-tiles a multiple of 8 (tile-major order applies) and not
+def test_workgroup_orders_give_the_same_result(M):
+    c = wl.make_case(2, 0, M=M)
     raw1 = _check_case(c)
-    tw.tw_set_option("xcd_map", 0)
-    raw2 = _check_case(c)
-    assert np.array_equal(raw1.view(np.uint16), raw2.view(np.uint16))
+    for mode in (0, 2):
+        tw.tw_set_option("xcd_map", mode)
+        raw2 = _check_case(c)
+        assert np.array_equal(raw1.view(np.uint16), raw2.view(np.uint16))
+        if M == 1024:
+            assert np.array_equal(_check_case(c, tile_m=64).view(np.uint16), raw1.view(np.uint16))
 
 
 @pytest.mark.parametrize("recipe", ["per_tile", "global", "paper"])
