@@ -39,6 +39,12 @@ int pick_tile_m(int M, int n_tiles, int G, int max_k) {
   return G == 32 ? 128 : 64;
 }
 
+// TVW: 128-row tiles.  The 256-row instance (8 waves) measured within 3 % of it on
+// every configured shape (slower on most), so it is only used when asked for.
+int pick_tile_m_tvw(int G) {
+  return (G == 128 && opt_tile_m.load() == 256) ? 256 : 128;
+}
+
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // K-split inside the workgroup pays when 128-row tiles cannot give every CU a
@@ -173,7 +179,8 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
     return e == hipSuccess ? TW_OK : TW_ERR_HIP;
   }
   if (h->pattern == TW_PATTERN_TVW) {
-    hipError_t e = twg::launch_tvw_km(h->G, 128, opt_depth.load(), g, (hipStream_t)stream);
+    const int tvw_tm = pick_tile_m_tvw(h->G);
+    hipError_t e = twg::launch_tvw_km(h->G, tvw_tm, opt_depth.load(), g, (hipStream_t)stream);
     if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
     return e == hipSuccess ? TW_OK : TW_ERR_HIP;
   }

@@ -115,6 +115,7 @@ __global__ __launch_bounds__(NWAVES * 64) void tw_gemm_km_dma_kernel(GemmArgs g)
   const int n_gemm = g.n_mtiles * g.n_tiles;
   TWG_TRACE_INIT();
   TWG_STAMP();
+  TWG_STAMP_CLK(0);
   if ((int)blockIdx.x >= n_gemm) {
     zero_fill_column(g, blockIdx.x - n_gemm);
     return;
@@ -390,6 +391,7 @@ __global__ __launch_bounds__(NWAVES * 64) void tw_gemm_km_dma_kernel(GemmArgs g)
     }
   }
   TWG_STAMP();
+  TWG_STAMP_CLK(1);
 }
 
 template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KSPLIT = 1>

@@ -73,9 +73,10 @@ __device__ __forceinline__ void wait_vm() {
 
 constexpr int KS2 = 64;   // condensed rows per stage (two sparse instructions deep)
 
-template <int TM, int TN, int WAVES_N, int D>
-__global__ __launch_bounds__(NTHREADS) void tvw_gemm_km_kernel(GemmArgs g) {
-  constexpr int WAVES_M = 4 / WAVES_N;
+template <int TM, int TN, int WAVES_N, int D, int NW = 4>
+__global__ __launch_bounds__(NW * 64) void tvw_gemm_km_kernel(GemmArgs g) {
+  constexpr int NT = NW * 64;                            // threads of the workgroup
+  constexpr int WAVES_M = NW / WAVES_N;
   constexpr int WN = TN / WAVES_N, WM = TM / WAVES_M;
   constexpr int NB = WN / 32, MB = WM / 32;
   static_assert(NB == 2 && (MB == 1 || MB == 2), "wave tiles are 64 columns by 32 or 64 rows of C^T");
@@ -85,10 +86,10 @@ __global__ __launch_bounds__(NTHREADS) void tvw_gemm_km_kernel(GemmArgs g) {
   constexpr int STAGE_V = KS2 * TN;                      // compressed values: 2 halves x NBT KiB
   constexpr int STAGE_I = 1024;                          // position words (NBT x 256 B used)
   constexpr int STAGE = STAGE_A + STAGE_V + STAGE_I;
-  constexpr int NIA = STAGE_A / 4096, NIV = STAGE_V / 4096;
-  constexpr int RPIA = 1024 / RBA;
+  constexpr int NIA = STAGE_A / (1024 * NW), NIV = STAGE_V / (1024 * NW);   // copy instructions per wave and stage
+  constexpr int RPIA = 1024 / RBA;                       // A rows per copy instruction
   static_assert(NIA == 2 || NIA == 4, "");
-  static_assert(NIV >= 1 && RPIA == 4 || RPIA == 8, "");
+  static_assert(NIV >= 1 && (RPIA == 2 || RPIA == 4 || RPIA == 8), "");
   static_assert(D == 3 || D == 4, "");
   constexpr int NPS = NIA + NIV + 1;
   constexpr int CA = TM / 8;
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(NTHREADS) void tvw_gemm_km_kernel(GemmArgs g) {
   const char* Vt = (const char*)g.vals + (size_t)kp0 * TN;            // kp0/2 rows x TN x 2 B
   const char* It = (const char*)g.meta + (size_t)(kp0 / KS2) * (NBT * 256);
 
-  constexpr int ROWS_PER_PASS = NTHREADS / CA;
+  constexpr int ROWS_PER_PASS = NT / CA;
   constexpr int NPASS = TN / ROWS_PER_PASS;
   const int c = tid % CA, r0 = tid / CA;
   int cols[NPASS];
@@ -132,16 +133,21 @@ __global__ __launch_bounds__(NTHREADS) void tvw_gemm_km_kernel(GemmArgs g) {
   }
   const _Float16* Abase = g.A + m0;
   typedef int sidx_t __attribute__((ext_vector_type(RPIA)));
-  sidx_t rows_next[NIA];
-  auto fetch_rows = [&](int s) {
+  struct Rows { sidx_t r[NIA]; };
+  auto fetch_rows = [&](int s, Rows& dst) {
 #pragma unroll
     for (int j = 0; j < NIA; ++j) {
       const int* rp = g.row_idx + kp0 + s * KS2 + (wave * NIA + j) * RPIA;
-      if constexpr (RPIA == 4) asm volatile("s_load_dwordx4 %0, %1, 0x0" : "=s"(rows_next[j]) : "s"(rp));
-      else asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(rows_next[j]) : "s"(rp));
+      if constexpr (RPIA == 2) asm volatile("s_load_dwordx2 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
+      else if constexpr (RPIA == 4) asm volatile("s_load_dwordx4 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
+      else asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
     }
   };
-  auto issue = [&](int s) {
+  auto tie_rows = [&](Rows& x) {      // after a wait: no use of x may be moved above this point
+    if constexpr (NIA == 2) asm volatile("" : "+s"(x.r[0]), "+s"(x.r[1]));
+    else asm volatile("" : "+s"(x.r[0]), "+s"(x.r[1]), "+s"(x.r[2]), "+s"(x.r[3]));
+  };
+  auto issue = [&](int s, const Rows& rows) {     // copies of stage s; rows = its kept-row indices
     char* dstA = lds + (s % D) * STAGE;
     char* dstV = dstA + STAGE_A;
     char* dstI = dstV + STAGE_V;
@@ -152,22 +158,21 @@ __global__ __launch_bounds__(NTHREADS) void tvw_gemm_km_kernel(GemmArgs g) {
                                        LDS_PTR(void, dstV + kb * 1024), 16, 0, 0);
     }
     {                                     // position words of column block wave % NBT: 256 bytes
+      // (every wave issues one, so that all waves have the same number of copies per
+      // stage in flight; waves that share a block write the same bytes)
       const int nb = wave % NBT;
       if (lane < 16)
         __builtin_amdgcn_global_load_lds(GLOBAL_PTR(It + (size_t)s * (NBT * 256) + nb * 256 + lb),
                                          LDS_PTR(void, dstI + nb * 256), 16, 0, 0);
     }
-    if constexpr (NIA == 2) asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(rows_next[0]), "+s"(rows_next[1]));
-    else asm volatile("s_waitcnt lgkmcnt(0)" : "+s"(rows_next[0]), "+s"(rows_next[1]), "+s"(rows_next[2]), "+s"(rows_next[3]));
 #pragma unroll
     for (int j = 0; j < NIA; ++j) {
-      int row = rows_next[j][0];
+      int row = rows.r[j][0];
 #pragma unroll
-      for (int q = 1; q < RPIA; ++q) row = (a_rloc == q) ? rows_next[j][q] : row;
+      for (int q = 1; q < RPIA; ++q) row = (a_rloc == q) ? rows.r[j][q] : row;
       __builtin_amdgcn_global_load_lds(GLOBAL_PTR(Abase + (size_t)row * g.lda + a_el[j]),
                                        LDS_PTR(void, dstA + (wave * NIA + j) * 1024), 16, 0, 0);
     }
-    fetch_rows(s + 1 < ns ? s + 1 : ns - 1);
   };
 
   floatx16 acc[NB][MB];
@@ -231,10 +236,19 @@ __global__ __launch_bounds__(NTHREADS) void tvw_gemm_km_kernel(GemmArgs g) {
   using U0 = std::integral_constant<int, 0>;
   using U1 = std::integral_constant<int, 1>;
 
+  Rows rows_cur{}, rows_next{};
   if (ns > 0) {
-    fetch_rows(0);
+    // kept-row lists of the first D stages in one round trip, then D-1 stages of copies
+    Rows pro[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) fetch_rows(d < ns ? d : ns - 1, pro[d]);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int d = 0; d < D; ++d) tie_rows(pro[d]);
+#pragma unroll
     for (int d = 0; d < D - 1; ++d)
-      if (d < ns) issue(d);
+      if (d < ns) issue(d, pro[d]);
+    rows_cur = pro[D - 1];
   }
   int idx_prev[NB] = {0, 0};
   for (int s = 0; s < ns; ++s) {
@@ -244,17 +258,22 @@ __global__ __launch_bounds__(NTHREADS) void tvw_gemm_km_kernel(GemmArgs g) {
     else if (newer == 1) wait_vm<NPS>();
     else wait_vm<0>();
     asm volatile("s_barrier" ::: "memory");
+    fetch_rows(s + D < ns ? s + D : ns - 1, rows_next);   // needed by the next iteration
     const uint32_t boff = (uint32_t)((s % D) * STAGE);
     read_step(boff, U0{}, f0);
 #pragma unroll
     for (int i = 0; i < NB; ++i) idx[i] = lds_read32(fi[i] + boff);
     if (s > 0) smfmac_step(U1{}, f1, idx_prev);   // second half of the previous stage
-    if (s + D - 1 < ns) issue(s + D - 1);
-    wait_step(f0);
+    wait_step(f0);                       // full wait: the scalar loads above are in as well
+    tie_rows(rows_next);
+    if (s + D - 1 < ns) issue(s + D - 1, rows_cur);
     read_step(boff, U1{}, f1);
     smfmac_step(U0{}, f0, idx);
+    // explicit moves behind the wait: a plain copy would make idx loop-carried, and
+    // the compiler may then copy the read's destination before the wait
 #pragma unroll
-    for (int i = 0; i < NB; ++i) idx_prev[i] = idx[i];
+    for (int i = 0; i < NB; ++i) asm volatile("v_mov_b32 %0, %1" : "=v"(idx_prev[i]) : "v"(idx[i]));
+    rows_cur = rows_next;
     wait_step(f1);
   }
   if (ns > 0) smfmac_step(U1{}, f1, idx_prev);
@@ -300,11 +319,11 @@ __global__ __launch_bounds__(NTHREADS) void tvw_gemm_km_kernel(GemmArgs g) {
   }
 }
 
-template <int TM, int TN, int WAVES_N, int D>
+template <int TM, int TN, int WAVES_N, int D, int NW = 4>
 static hipError_t launch(const GemmArgs& g, hipStream_t stream) {
   const int grid = g.n_mtiles * g.n_tiles + g.n_zero;
   if (grid <= 0) return hipSuccess;
-  hipLaunchKernelGGL((tvw_gemm_km_kernel<TM, TN, WAVES_N, D>), dim3(grid), dim3(NTHREADS), 0,
+  hipLaunchKernelGGL((tvw_gemm_km_kernel<TM, TN, WAVES_N, D, NW>), dim3(grid), dim3(NW * 64), 0,
                      stream, g);
   return hipGetLastError();
 }
@@ -313,6 +332,7 @@ hipError_t launch_tvw_km(int G, int tm, int depth, GemmArgs g, hipStream_t strea
   g.n_mtiles = (g.M + tm - 1) / tm;
   if (G == 128 && tm == 128 && depth == 3) return launch<128, 128, 2, 3>(g, stream);
   if (G == 128 && tm == 128 && depth == 4) return launch<128, 128, 2, 4>(g, stream);
+  if (G == 128 && tm == 256) return launch<256, 128, 2, 3, 8>(g, stream);   // 8 waves, 64 x 64 per wave
   if (G == 64 && tm == 128 && depth == 3) return launch<128, 64, 1, 3>(g, stream);
   if (G == 64 && tm == 128 && depth == 4) return launch<128, 64, 1, 4>(g, stream);
   return hipErrorInvalidValue;

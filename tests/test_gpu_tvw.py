@@ -11,6 +11,13 @@ import workloads as wl
 pytestmark = pytest.mark.gpu
 
 
+@pytest.fixture(autouse=True)
+def _reset_options():
+    tw.tw_set_option("tile_m", 0)
+    yield
+    tw.tw_set_option("tile_m", 0)
+
+
 def _run(A, B, mask, tile_mask, G, **kw):
     p = tw.tw_pack(B, mask, G, tw.PATTERN_TVW, tile_mask=tile_mask)
     C, raw = gu.run_tw(tw, p, A, B.shape[1], **kw)
@@ -57,6 +64,31 @@ def test_all_ones_counts_kept_elements():
     print("case tvw all ones", flush=True)
     C, _ = _run(np.ones((M, K), np.float16), np.ones((K, N), np.float16), mask, tm, G)
     assert np.array_equal(C, np.broadcast_to(mask.sum(0).astype(np.float64), (M, N)))
+
+
+@pytest.mark.parametrize("M", [8, 300, 520])
+def test_256_row_tiles_eight_waves(M):
+    """The 256 x 128 instance (8 waves): identity A pins the layout bit for bit,
+    random A goes against the oracle; M below, across and beyond one tile."""
+    rng = np.random.default_rng(40 + M)
+    K, N, G = 330, 300, 128
+    mask, tm = random_tvw_mask(rng, K, N, G, full=(M != 300))
+    B = wl.make_B(40, K, N, 1.0)
+    tw.tw_set_option("tile_m", 256)
+    print(f"case tvw 256-row tiles M={M}", flush=True)
+    A = wl.make_A(M, M, K)
+    C, raw = _run(A, B, mask, tm, G, fill=3.0, ldc=(M + 7) // 8 * 8 + 8)
+    assert_C_close(C, og.gemm_oracle(A, B, mask), og.abs_bound(A, B, mask))
+    assert not raw[~mask.any(0), :M].view(np.uint16).any()
+    assert (raw[:, M:] == 3.0).all()
+    C, raw = _run(np.eye(K, dtype=np.float16), B, mask, tm, G)
+    want = np.where(mask != 0, B, np.float16(0)).astype(np.float16)
+    assert np.array_equal(raw[:, :K].T.view(np.uint16), want.view(np.uint16))
+    tw.tw_set_option("tile_m", 128)
+    _, raw128 = _run(A, B, mask, tm, G)
+    tw.tw_set_option("tile_m", 256)
+    _, raw256 = _run(A, B, mask, tm, G)
+    assert np.array_equal(raw128[:, :M].view(np.uint16), raw256[:, :M].view(np.uint16))
 
 
 @pytest.mark.parametrize("G", [64, 128])
