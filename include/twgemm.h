@@ -191,6 +191,9 @@ const char* tw_status_str(int status);
  *   "ksplit"   0 = automatic, 1 = never, 2 = always split K between two wave groups
  *              of a workgroup (long K, few tiles)
  *   "depth"    stages in flight of the asynchronous pipeline: 3 (default) or 4
+ *   "tile_order"  read by tw_pack / tw_concat: 1 (default) = tiles are launched longest
+ *              kept-row list first (uneven tiles, Section V "load imbalance"); 0 = in
+ *              column order
  * tw_flop_counts: condensed work of a handle (any pointer may be NULL):
  *   *sum_kw  = sum over tiles of K_t * W_t (kept-row x width products),
  *   *sum_k   = sum over tiles of K_t,

@@ -286,6 +286,7 @@ tw_status tw_set_option(const char* name, int value) {
   if (!std::strcmp(name, "kernel")) { opt_kernel.store(value); return TW_OK; }
   if (!std::strcmp(name, "waves")) { opt_waves.store(value == 8 ? 8 : 4); return TW_OK; }
   if (!std::strcmp(name, "ksplit")) { opt_ksplit.store(value); return TW_OK; }
+  if (!std::strcmp(name, "tile_order")) { twg::longest_first.store(value != 0); return TW_OK; }
   if (!std::strcmp(name, "depth")) { opt_depth.store(value == 4 ? 4 : 3); return TW_OK; }
   return TW_ERR_ARG;
 }

@@ -7,12 +7,15 @@
 // columns before cutting tiles of G.  Integer work only; results are unique
 // and compared bit for bit in the tests.
 #include <algorithm>
+#include <atomic>
 #include <cstring>
 #include <new>
 
 #include "packed.h"
 
 namespace twg {
+
+std::atomic<int> longest_first{1};
 
 namespace {
 
@@ -291,9 +294,10 @@ void build_device_image(tw_handle_s* h) {
   }
   d.tile_order.resize(nt);
   for (int t = 0; t < nt; ++t) d.tile_order[t] = t;
-  std::stable_sort(d.tile_order.begin(), d.tile_order.end(), [&](int a, int b) {
-    return h->tile_k_off[a + 1] - h->tile_k_off[a] > h->tile_k_off[b + 1] - h->tile_k_off[b];
-  });
+  if (longest_first.load())
+    std::stable_sort(d.tile_order.begin(), d.tile_order.end(), [&](int a, int b) {
+      return h->tile_k_off[a + 1] - h->tile_k_off[a] > h->tile_k_off[b + 1] - h->tile_k_off[b];
+    });
   d.tile_sched.resize((size_t)nt * 4);
   for (int pos = 0; pos < nt; ++pos) {
     const int t = d.tile_order[pos];

@@ -2,6 +2,7 @@
 // tw_export shows), the host staging copy of the device image, and the device
 // pointers once uploaded.
 #pragma once
+#include <atomic>
 #include <cstdint>
 #include <vector>
 
@@ -61,6 +62,8 @@ tw_status pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_
 tw_status unpack_host(const tw_handle_s* h, uint16_t* Bm, uint8_t* mask);
 // Fills *h with parts[0..n) side by side along N (same K, G and pattern).
 tw_status concat_host(const tw_handle_s* const* parts, int n, tw_handle_s* h);
+// Launch order of the tiles, read when a device image is built: 1 = longest K_t first.
+extern std::atomic<int> longest_first;
 // Builds h->img host staging from the logical form.
 void build_device_image(tw_handle_s* h);
 }  // namespace twg

@@ -5,7 +5,11 @@ dense baseline back to back on rotating buffer sets (operands from HBM) and
 prints one JSON line with dense-equivalent TFLOP/s, condensed-FLOP matrix-core
 utilisation, speed-up over the dense baseline and the fraction of the binding
 roofline (vendor peaks: 8 TB/s, 2.5 PFLOP/s fp16 dense).  `--cube` adds the
-paper's 4096 x 4096 x 4096 sparsity sweep (Section VI-B).
+paper's 4096 x 4096 x 4096 sparsity sweep (Section VI-B; TVW at 50 % is plain
+2:4).  `--imbalance` times uneven tiles (one magnitude threshold over all
+tile rows of the matrix instead of one per tile: Section IV "global weight
+pruning", Section V "load imbalance") with the tiles launched longest first and
+in column order.
 """
 from __future__ import annotations
 
@@ -29,6 +33,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--configs", default="2,3,4,5")
     ap.add_argument("--cube", action="store_true")
+    ap.add_argument("--imbalance", action="store_true")
     ap.add_argument("--reps", type=int, default=24)
     ap.add_argument("--sets", type=int, default=6)
     args = ap.parse_args()
@@ -76,6 +81,43 @@ def main():
             plan.append((6, 0, "tw", sp, 64))
         for sp in (0.5, 0.75, 0.875):
             plan.append((6, 0, "tvw", sp, 128))
+
+    if args.cube or args.imbalance:
+        wl.SHAPES[6] = [wl.Shape("cube_4096", 4096, 4096, 4096, 0.02)]
+        wl.CONFIGS[6] = dict(G=128, pattern="tw", sparsity=0.75, col_frac=0.10)
+    if args.imbalance:
+        for cfg, si in ((4, 0), (4, 1), (6, 0)):
+            shp = wl.SHAPES[cfg][si]
+            M, K, N = shp.M, shp.K, shp.N
+            nsets = max(2, min(args.sets, int(600e6 // (2 * M * (K + N)))))
+            A = [torch.randn((K, M), dtype=torch.float16, device=dev) for _ in range(nsets)]
+            C = [torch.empty((N, M), dtype=torch.float16, device=dev) for _ in range(nsets)]
+            for recipe in ("per_tile", "global", "global, column blocks rescaled"):
+                if recipe.startswith("global,"):
+                    # i.i.d. weights give nearly even tiles under one threshold; trained layers do
+                    # not: rescale each block of 128 columns by exp(N(0, 0.6^2)) before thresholding
+                    Bs = wl.make_B(wl.seed_for(cfg, si), K, N, shp.sigma).astype(np.float32)
+                    f = np.exp(0.6 * np.random.default_rng(wl.seed_for(cfg, si) + 7).standard_normal((N + 127) // 128))
+                    Bs = (Bs * np.repeat(f, 128)[:N]).astype(np.float16)
+                    mask = wl.tw_mask(Bs, 128, density=0.25, col_frac=0.10, recipe="global")
+                    c = wl.Case("rescaled", M, K, N, 128, "tw", 0.75, 0, None, Bs, mask, mask)
+                else:
+                    c = wl.make_case(cfg, si, pattern="tw", sparsity=0.75, G=128, recipe=recipe, with_A=False)
+                row = dict(shape=shp.name, M=M, K=K, N=N, G=128, pattern="tw", sparsity=0.75, recipe=recipe)
+                for order in (1, 0):
+                    tw.tw_set_option("tile_order", order)
+                    packed = [tw.tw_pack(c.B, c.mask, 128, tw.PATTERN_TW) for _ in range(nsets)]
+                    t = timed(lambda r: tw.tw_gemm(A[r % nsets].data_ptr(), M, M, tw.LAYOUT_KM, packed[r % nsets],
+                                                   C[r % nsets].data_ptr(), M, stream), args.reps)
+                    e = packed[0].export()
+                    kt = np.array([len(r) for r in e["row_idx"]])
+                    row.update({("us_longest_first" if order else "us_column_order"): round(t * 1e6, 2),
+                                "K_t_min": int(kt.min()), "K_t_mean": round(float(kt.mean()), 1), "K_t_max": int(kt.max())})
+                    for p in packed:
+                        p.free()
+                tw.tw_set_option("tile_order", 1)
+                print(json.dumps(row), flush=True)
+            del A, C
 
     dense_cache = {}
     for cfg, si, pattern, sp, G in plan:
