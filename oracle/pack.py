@@ -1,4 +1,4 @@
-"""Canonical logical packed form of a TW / TVW pruned weight, on the CPU.
+"""Canonical logical packed form of a TW / TVW / TEW pruned weight, on the CPU.
 
 TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
 
@@ -21,6 +21,14 @@ vectors by the indices of the unpruned rows/columns, then by offsets
                meta[t][g][w] = p0 | p1 << 2, valid[t][g][w] = v0 | v1 << 1,
                values V2[t][g][i][w], i in {0,1}.
 
+  TEW          the TW form of the TW-level `tile_mask`, plus the restored
+               elements (mask set, tile_mask clear) in compressed sparse column
+               form over the ORIGINAL columns (Section III-A, "TEW": the EW
+               part is kept in CSC; here one CSC for the matrix, which also
+               covers restored elements in columns the TW step dropped):
+               ew_col_ptr[N+1], ew_row[nnz] ascending inside a column,
+               ew_val[nnz] fp16 bits.
+
 A mask is TW-conformant when mask[k,n] == (n kept) and (k in row_idx[tile(n)]).
 For TVW the kept rows/columns come from the TW-level `tile_mask` when given,
 else from the element mask itself; the element mask must lie inside it with at
@@ -32,6 +40,7 @@ import numpy as np
 
 PATTERN_TW = 0
 PATTERN_TVW = 1
+PATTERN_TEW = 2
 
 
 class MaskError(ValueError):
@@ -77,6 +86,14 @@ def ref_pack(B16: np.ndarray, mask: np.ndarray, G: int, pattern: int,
             _check_tw(tm, col_idx, tiles, row_idx)
             if (m & ~tm).any():
                 raise MaskError("element mask has bits outside the tile mask")
+    elif pattern == PATTERN_TEW:
+        if tile_mask is None:
+            raise ValueError("TEW needs the TW-level tile_mask")
+        tm = tile_mask != 0
+        col_idx, tiles, row_idx = _structure(tm, G)
+        _check_tw(tm, col_idx, tiles, row_idx)
+        if (tm & ~m).any():
+            raise MaskError("tile mask has bits outside the element mask")
     else:
         raise ValueError("pattern")
     out = dict(K=K, N=N, G=G, pattern=pattern, col_idx=np.array(col_idx, np.int32),
@@ -84,10 +101,20 @@ def ref_pack(B16: np.ndarray, mask: np.ndarray, G: int, pattern: int,
                row_idx=[np.array(r, np.int32) for r in row_idx],
                cto_n=np.array(cto(col_idx), np.int32),
                cto_k=[np.array(cto(r), np.int32) for r in row_idx])
-    if pattern == PATTERN_TW:
+    if pattern in (PATTERN_TW, PATTERN_TEW):
         out["values"] = [bits[np.ix_(rows, cols)].copy() if rows else
                          np.zeros((0, len(cols)), np.uint16)
                          for cols, rows in zip(tiles, row_idx)]
+        if pattern == PATTERN_TEW:
+            ptr, rows_e, vals_e = [0], [], []
+            for n in range(N):
+                for k in range(K):
+                    if m[k, n] and not tm[k, n]:
+                        rows_e.append(k)
+                        vals_e.append(int(bits[k, n]))
+                ptr.append(len(rows_e))
+            out.update(ew_col_ptr=np.array(ptr, np.int32), ew_row=np.array(rows_e, np.int32),
+                       ew_val=np.array(vals_e, np.uint16))
         return out
     vals, metas, valids = [], [], []
     for cols, rows in zip(tiles, row_idx):
@@ -127,7 +154,7 @@ def ref_unpack(p: dict):
     for t in range(p["n_tiles"]):
         cols = col_idx[t * G:(t + 1) * G]
         rows = p["row_idx"][t]
-        if p["pattern"] == PATTERN_TW:
+        if p["pattern"] in (PATTERN_TW, PATTERN_TEW):
             if len(rows):
                 Bm[np.ix_(rows, cols)] = p["values"][t]
                 mask[np.ix_(rows, cols)] = 1
@@ -140,4 +167,10 @@ def ref_unpack(p: dict):
                         k = rows[4 * g + ((me[g, w] >> (2 * i)) & 3)]
                         Bm[k, n] = v[g, i, w]
                         mask[k, n] = 1
+    if p["pattern"] == PATTERN_TEW:
+        ptr = p["ew_col_ptr"]
+        for n in range(N):
+            for e in range(ptr[n], ptr[n + 1]):
+                Bm[p["ew_row"][e], n] = p["ew_val"][e]
+                mask[p["ew_row"][e], n] = 1
     return Bm, mask

@@ -1,4 +1,4 @@
-"""One-shot TW / VW(2:4) / TVW pruning masks, following Algorithms 2 and 3.
+"""One-shot TW / VW(2:4) / TVW / TEW pruning masks, following Algorithms 2 and 3.
 
 TEST INFRASTRUCTURE ONLY (see oracle/__init__.py).
 
@@ -18,6 +18,12 @@ Readings where the algorithms are silent:
     equal magnitudes the lower position is kept.
   * a last tile narrower than G scores its rows by the mean, not the sum, when
     one threshold is shared by all tiles.
+  * TEW's remedy step ("restore delta percent of the weight elements with the
+    highest importance scores", Section III-A; Algorithm 3, TEW: scores of kept
+    elements zeroed, threshold at the (1 - delta) percentile over all K*N
+    scores) is made deterministic as: of the elements the TW step pruned,
+    restore the floor(delta * K * N) highest by (score descending, flat index
+    ascending); fewer if fewer were pruned.
 """
 from __future__ import annotations
 
@@ -128,6 +134,23 @@ def tvw_paper(w: np.ndarray, s_t: float, G: int):
     """Algorithm 3, TVW: TW at 1-2(1-s_t), then 2:4.  Returns (mask, tile_mask)."""
     tile_mask = tw_paper(w, tvw_tw_sparsity(s_t), G)
     return vw24_condensed(w, tile_mask, G), tile_mask
+
+
+def tew(w: np.ndarray, G: int, s_t: float, delta: float, tw_fn=None):
+    """Algorithm 3, TEW: TW at sparsity s_t + delta, then the remedy step puts
+    back the delta * K * N pruned elements with the highest scores.
+    `tw_fn(w, s, G)` is the TW step (default: Algorithm 3's TW as listed).
+    Returns (mask, tile_mask): the element mask and the TW-level mask inside it."""
+    K, N = w.shape
+    tile_mask = (tw_fn or tw_paper)(w, s_t + delta, G)
+    scores = (w.astype(np.float64) ** 2).reshape(-1).tolist()
+    flat_tm = tile_mask.reshape(-1)
+    pruned = [i for i in range(K * N) if not flat_tm[i]]
+    pruned.sort(key=lambda i: (-scores[i], i))
+    mask = tile_mask.copy().reshape(-1)
+    for i in pruned[:int(math.floor(delta * K * N))]:
+        mask[i] = 1
+    return mask.reshape(K, N), tile_mask
 
 
 def rows_per_tile(K: int, N: int, n_kept: int, density: float, multiple: int = 1) -> int:

@@ -157,3 +157,76 @@ def test_configured_masks_are_conformant():
     p = opk.ref_pack(c.B, c.mask, c.G, opk.PATTERN_TVW, tile_mask=c.tile_mask)
     assert [len(r) for r in p["row_idx"]] == [212] * 6       # 2*(1-.875)*768/692*768 = 213.1 -> multiple of 4
     assert all((v & 3).min() == 3 for v in p["valid"])        # every group full
+
+
+# ---- TEW: TW form + restored elements in compressed sparse column form -----------------
+def _random_tew(rng, K, N, G, extra=0.08):
+    tm = random_tw_mask(rng, K, N, G)
+    m = tm | ((rng.random((K, N)) < extra) & (tm == 0)).astype(np.uint8)
+    return m, tm
+
+
+def test_tew_hand_example():
+    """4 x 5, G = 2: columns 0, 1, 3 kept by the TW step (tile 0 = {0, 1} rows {0, 2};
+    tile 1 = {3} rows {1}); restored elements (3,0), (1,1), (0,2), (3,2), (0,3)."""
+    tm = np.zeros((4, 5), np.uint8)
+    tm[np.ix_([0, 2], [0, 1])] = 1
+    tm[1, 3] = 1
+    m = tm.copy()
+    for k, n in [(3, 0), (1, 1), (0, 2), (3, 2), (0, 3)]:
+        m[k, n] = 1
+    B = (np.arange(20, dtype=np.float32).reshape(4, 5) + 1).astype(np.float16)
+    p = opk.ref_pack(B, m, 2, opk.PATTERN_TEW, tile_mask=tm)
+    assert p["col_idx"].tolist() == [0, 1, 3] and p["n_tiles"] == 2
+    assert [r.tolist() for r in p["row_idx"]] == [[0, 2], [1]]
+    assert p["ew_col_ptr"].tolist() == [0, 1, 2, 4, 5, 5]
+    assert p["ew_row"].tolist() == [3, 1, 0, 3, 0]
+    assert p["ew_val"].view(np.float16).tolist() == [16.0, 7.0, 3.0, 18.0, 4.0]
+    assert p["values"][0].view(np.float16).tolist() == [[1.0, 2.0], [11.0, 12.0]]
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_tew_round_trip_and_csc_invariants(seed):
+    rng = np.random.default_rng(200 + seed)
+    K, N, G = int(rng.integers(1, 60)), int(rng.integers(1, 150)), int(rng.choice([32, 64, 128]))
+    m, tm = _random_tew(rng, K, N, G)
+    B = wl.rng_fp16(seed, (K, N))
+    p = opk.ref_pack(B, m, G, opk.PATTERN_TEW, tile_mask=tm)
+    tw_part = opk.ref_pack(B, tm, G, opk.PATTERN_TW)
+    for key in ("col_idx", "cto_n"):
+        assert np.array_equal(p[key], tw_part[key])
+    for a, b in zip(p["values"], tw_part["values"]):
+        assert np.array_equal(a, b)
+    ptr = p["ew_col_ptr"]
+    assert ptr[0] == 0 and ptr[-1] == int((m & ~tm & 1).sum()) == len(p["ew_row"]) == len(p["ew_val"])
+    assert (np.diff(ptr) >= 0).all()
+    for n in range(N):
+        r = p["ew_row"][ptr[n]:ptr[n + 1]]
+        assert (np.diff(r) > 0).all()                                    # ascending, no duplicates
+        assert np.array_equal(r, np.flatnonzero((m[:, n] != 0) & (tm[:, n] == 0)))
+    Bm, m2 = opk.ref_unpack(p)
+    assert np.array_equal(m2, m)
+    assert np.array_equal(Bm, np.where(m != 0, B.view(np.uint16), 0))
+
+
+def test_tew_without_restored_elements_is_the_tw_form():
+    rng = np.random.default_rng(9)
+    tm = random_tw_mask(rng, 30, 70, 32)
+    B = wl.rng_fp16(9, tm.shape)
+    p = opk.ref_pack(B, tm, 32, opk.PATTERN_TEW, tile_mask=tm)
+    assert p["ew_col_ptr"].tolist() == [0] * 71 and len(p["ew_row"]) == 0
+
+
+def test_tew_rejects_bad_masks():
+    rng = np.random.default_rng(10)
+    m, tm = _random_tew(rng, 20, 40, 32)
+    B = wl.rng_fp16(10, m.shape)
+    with pytest.raises(ValueError):
+        opk.ref_pack(B, m, 32, opk.PATTERN_TEW)                          # no tile mask
+    bad = m.copy()
+    k, n = np.argwhere(tm != 0)[0]
+    bad[k, n] = 0                                                        # a TW element missing from the mask
+    with pytest.raises(opk.MaskError):
+        opk.ref_pack(B, bad, 32, opk.PATTERN_TEW, tile_mask=tm)
+    with pytest.raises(opk.MaskError):
+        opk.ref_pack(B, m, 32, opk.PATTERN_TEW, tile_mask=m)             # tile mask that is not tile-wise

@@ -168,3 +168,71 @@ def test_global_recipe_gives_uneven_tiles():
     kt = [int(c.mask[:, cols[i:i + 128]].any(1).sum()) for i in range(0, cols.size, 128)]
     assert len(set(kt)) > 1
     assert 1 - c.mask.mean() == pytest.approx(0.75, abs=1e-2)
+
+
+# ---- TEW (Algorithm 3, TEW; Section III-A "TEW") -------------------------------------
+def test_tew_with_delta_zero_is_tw():
+    w = wl.rng_fp16(3, (24, 20))
+    m, tm = op.tew(w, 4, 0.5, 0.0)
+    assert np.array_equal(m, tm) and np.array_equal(m, op.tw_paper(w, 0.5, 4))
+
+
+def test_tew_worked_by_hand():
+    """K = N = 4, G = 2, integer weights.  TW at s_t + delta = 0.4375 + 0.3125 = 0.75:
+    s = 1 - sqrt(0.25) = 0.5 -> the two columns with the smallest sums of squares go
+    (columns 2 and 3: 1+1+1+4 = 7 and 1+1+4+9 = 15 against 101 and 62), one tile of two
+    columns is left, and its two weakest rows go (rows 1, 3: 1+4 = 5 and 1+16 = 17 against
+    100+16 and 0+25).  delta * 16 = 5 elements come back: the five largest squares among the
+    pruned ones, 16 (3,1), 9 (3,3), 4 (1,1), 4 (2,3) and 4 (3,2): all three 4s fit."""
+    w = np.array([[10, 4, 1, 1],
+                  [1, 2, 1, 1],
+                  [0, 5, 1, 2],
+                  [1, 4, 2, 3]], np.float16)
+    m, tm = op.tew(w, 2, 0.4375, 0.3125)
+    want_tm = np.zeros((4, 4), np.uint8)
+    want_tm[np.ix_([0, 2], [0, 1])] = 1
+    assert np.array_equal(tm, want_tm)
+    want = want_tm.copy()
+    for k, n in [(3, 1), (3, 3), (1, 1), (2, 3), (3, 2)]:
+        want[k, n] = 1
+    assert np.array_equal(m, want)
+
+
+@pytest.mark.parametrize("seed,K,N,G,s_t,delta", [(0, 40, 36, 8, 0.6, 0.05), (1, 33, 50, 16, 0.75, 0.015),
+                                                   (2, 16, 16, 4, 0.5, 0.25), (3, 30, 30, 8, 0.9, 0.1)])
+def test_tew_invariants(seed, K, N, G, s_t, delta):
+    w = wl.rng_fp16(seed, (K, N))
+    m, tm = op.tew(w, G, s_t, delta)
+    assert np.array_equal(tm, op.tw_paper(w, s_t + delta, G))        # the TW part is TW at s_t + delta
+    assert not (tm & ~m).any()                                        # nothing the TW step kept is lost
+    n_back = int(m.sum() - tm.sum())
+    assert n_back == min(int(math.floor(delta * K * N)), int((tm == 0).sum()))
+    sq = w.astype(np.float64) ** 2
+    back, gone = (m == 1) & (tm == 0), m == 0
+    if back.any() and gone.any():
+        assert sq[back].min() >= sq[gone].max()                       # the highest scores came back
+    # equal scores at the cut: the lower flat index is restored first
+    cut = sq[back].min() if back.any() else None
+    if cut is not None:
+        tied_gone = np.flatnonzero((gone & (sq == cut)).reshape(-1))
+        tied_back = np.flatnonzero((back & (sq == cut)).reshape(-1))
+        if tied_gone.size and tied_back.size:
+            assert tied_back.max() < tied_gone.min()
+
+
+def test_tew_tie_at_the_cut_keeps_lower_index():
+    w = np.ones((4, 4), np.float16)
+    w[0, :] = 3
+    m, tm = op.tew(w, 4, 0.5, 0.125, tw_fn=lambda w_, s, G: np.repeat((np.arange(4) == 0)[:, None], 4, 1).astype(np.uint8))
+    assert np.array_equal(np.flatnonzero(m.reshape(-1))[:6], [0, 1, 2, 3, 4, 5])   # row 0 + flat 4, 5
+    assert m.sum() == 6
+
+
+@pytest.mark.parametrize("K,N,G,sp,delta,cf", [(64, 96, 32, 0.75, 0.015, 0.1), (40, 70, 16, 0.5, 0.05, 0.0)])
+def test_workloads_tew_equals_oracle(K, N, G, sp, delta, cf):
+    """The generator's vectorised TEW against the oracle's, same TW step."""
+    w = wl.rng_fp16(5, (K, N))
+    m, tm = wl.tew_mask(w, G, sparsity=sp, delta=delta, col_frac=cf)
+    m2, tm2 = op.tew(w, G, sp, delta,
+                     tw_fn=lambda w_, s, G_: wl.tw_mask(w_, G_, density=1.0 - s, col_frac=cf))
+    assert np.array_equal(tm, tm2) and np.array_equal(m, m2)

@@ -160,6 +160,21 @@ def tvw_mask(B16: np.ndarray, G: int, *, sparsity: float, col_frac: float | None
     return _two_of_four(B16, tile_mask, G), tile_mask
 
 
+def tew_mask(B16: np.ndarray, G: int, *, sparsity: float, delta: float, col_frac: float | None,
+             recipe: str = "per_tile"):
+    """TEW mask (Algorithm 3, TEW): TW at sparsity s_t + delta, then the
+    floor(delta*K*N) largest-magnitude pruned elements are put back (equal
+    magnitudes: lower flat index first).  Returns (mask, tile_mask)."""
+    K, N = B16.shape
+    tile_mask = tw_mask(B16, G, density=1.0 - sparsity - delta, col_frac=col_frac, recipe=recipe)
+    score = B16.astype(np.float64).reshape(-1) ** 2
+    pruned = np.flatnonzero(tile_mask.reshape(-1) == 0)
+    order = pruned[np.argsort(-score[pruned], kind="stable")]
+    mask = tile_mask.copy().reshape(-1)
+    mask[order[:int(np.floor(delta * K * N))]] = 1
+    return mask.reshape(K, N), tile_mask
+
+
 # --------------------------------------------------------------------------
 # named workloads
 # --------------------------------------------------------------------------
@@ -206,7 +221,7 @@ class Case:
     K: int
     N: int
     G: int
-    pattern: str          # "tw" | "tvw"
+    pattern: str          # "tw" | "tvw" | "tew"
     sparsity: float
     seed: int
     A: np.ndarray = field(repr=False)          # M x K fp16
@@ -218,7 +233,8 @@ class Case:
 def make_case(config: int, shape_index: int = 0, *, pattern: str | None = None,
               sparsity: float | None = None, G: int | None = None,
               col_frac: float | None = None, recipe: str = "per_tile",
-              variant: int = 0, M: int | None = None, with_A: bool = True) -> Case:
+              variant: int = 0, M: int | None = None, with_A: bool = True,
+              delta: float = 0.015) -> Case:
     """One (A, B, mask) triple of a configured workload.  Sparsity 0 gives the
     all-ones mask (the dense case).  `M` may shrink the activation count."""
     shp = SHAPES[config][shape_index]
@@ -239,6 +255,8 @@ def make_case(config: int, shape_index: int = 0, *, pattern: str | None = None,
         tile_mask = mask.copy()
     elif pattern == "tvw":
         mask, tile_mask = tvw_mask(B, G, sparsity=sparsity, col_frac=col_frac, recipe=recipe)
+    elif pattern == "tew":
+        mask, tile_mask = tew_mask(B, G, sparsity=sparsity, delta=delta, col_frac=col_frac, recipe=recipe)
     else:
         raise ValueError(pattern)
     return Case(f"{shp.name}_{pattern}{int(round(sparsity * 10000)) / 100:g}_G{G}_{recipe}",
