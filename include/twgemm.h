@@ -7,7 +7,10 @@
  * columns are dropped (TW-C), the kept columns are cut into tiles of G, and
  * every tile drops its own set of K-rows (TW-R).  TVW additionally keeps only
  * 2 of every 4 consecutive kept rows per column (Section III-A, "TVW";
- * Algorithm 3).  The library keeps B condensed per tile together with the
+ * Algorithm 3).  TEW puts single elements back on top of a TW mask (Section
+ * III-A, "TEW"; Algorithm 3, TEW); they are kept in compressed sparse column
+ * form next to the TW part and, by linearity, added to the same fp32 sums
+ * before the one rounding.  The library keeps B condensed per tile together with the
  * indices of the unpruned rows / columns (Section V, "Tile Fusion and
  * Compressed Tile Offset"; Listing 1's CTO_k / CTO_n) and computes
  *
@@ -52,7 +55,7 @@ typedef enum {
   TW_ERR_STATE = 6        /* handle has no device copy yet / already freed                */
 } tw_status;
 
-typedef enum { TW_PATTERN_TW = 0, TW_PATTERN_TVW = 1 } tw_pattern;
+typedef enum { TW_PATTERN_TW = 0, TW_PATTERN_TVW = 1, TW_PATTERN_TEW = 2 } tw_pattern;
 
 /*
  * Memory layout of A and C.  Section V ("Memory Accesses Coalesce") stores the
@@ -83,6 +86,10 @@ typedef enum { TW_LAYOUT_KM = 0, TW_LAYOUT_MK = 1 } tw_layout;
  *        meta  = p0 | p1<<2 with p0 < p1 the two stored positions of the group,
  *        valid = v0 | v1<<1, v_i = 1 if stored value i is a kept element of the
  *        mask (else it is a +0 filler).
+ *   TEW: the TW fields describe the TW-level tile mask; the restored elements
+ *        (mask set, tile mask clear) follow in compressed sparse column form over
+ *        the ORIGINAL columns, pruned ones included: ew_col_ptr[N+1],
+ *        ew_row[ew_nnz] ascending inside a column, ew_val[ew_nnz] fp16 bits.
  */
 typedef struct {
   int32_t K, N, G, pattern;
@@ -98,6 +105,10 @@ typedef struct {
   const uint8_t* meta;      /* NULL for TW */
   const uint8_t* valid;     /* NULL for TW */
   const int32_t* tile_col_off;
+  int64_t ew_nnz;              /* 0 unless TEW */
+  const int32_t* ew_col_ptr;   /* NULL unless TEW */
+  const int32_t* ew_row;
+  const uint16_t* ew_val;
 } tw_packed_view;
 
 /*
@@ -105,13 +116,15 @@ typedef struct {
  * "offline before the model inference starts"; Algorithm 3's Condense).
  *   B_host     K x N row-major fp16 bit patterns (ldb = N)
  *   mask_host  K x N bytes, non-zero = kept
- *   tile_mask_host  TVW only, may be NULL: the TW-level mask the 2:4 step was
+ *   tile_mask_host  TVW, may be NULL: the TW-level mask the 2:4 step was
  *              applied to.  When NULL the kept rows/columns are the ones with
- *              any mask bit.  Ignored for TW.
+ *              any mask bit.  TEW, required: the TW-level mask; mask_host must
+ *              contain it, what it adds are the restored elements.  Ignored for TW.
  *   G          tile width along N: 32, 64 or 128
- * Errors: TW_ERR_ARG (null / K,N < 1 / bad G or pattern), TW_ERR_MASK (a kept
- * row of a tile has a hole, the element mask leaves the tile mask, or a 2:4
- * group keeps more than two), TW_ERR_ALLOC.  Touches no GPU.
+ * Errors: TW_ERR_ARG (null / K,N < 1 / bad G or pattern / TEW without tile mask),
+ * TW_ERR_MASK (a kept row of a tile has a hole, the element mask leaves the
+ * tile mask (TVW) or does not contain it (TEW), or a 2:4 group keeps more than
+ * two), TW_ERR_UNSUPPORTED (TEW with K > 65536), TW_ERR_ALLOC.  Touches no GPU.
  */
 tw_status tw_pack_host(const uint16_t* B_host, const uint8_t* mask_host,
                        const uint8_t* tile_mask_host, int K, int N, int G,
@@ -149,7 +162,8 @@ tw_status tw_concat(const tw_handle_t* parts, int n, int upload, tw_handle_t* ou
  *   M             >= 1
  * Asynchronous on `stream`; allocates nothing; concurrent calls must use
  * distinct C.  Errors: TW_ERR_ARG, TW_ERR_STATE (not uploaded),
- * TW_ERR_UNSUPPORTED (layout without a kernel), TW_ERR_HIP (launch failed).
+ * TW_ERR_UNSUPPORTED (layout without a kernel: TVW and TEW exist for
+ * TW_LAYOUT_KM only, TEW for G = 64 and 128), TW_ERR_HIP (launch failed).
  */
 tw_status tw_gemm(const void* A_dev, int M, int lda, int layout, tw_handle_t h,
                   void* C_dev, int ldc, void* stream);

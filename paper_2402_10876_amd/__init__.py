@@ -2,5 +2,5 @@
 over the C-ABI library libtwgemm.so (see include/twgemm.h)."""
 from .binding import (  # noqa: F401
     TwError, PackedWeight, lib, lib_path, tw_pack, tw_pack_host, tw_concat, tw_gemm, tw_dense_gemm,
-    tw_set_option, PATTERN_TW, PATTERN_TVW, LAYOUT_KM, LAYOUT_MK, EXPORTED_SYMBOLS,
+    tw_set_option, PATTERN_TW, PATTERN_TVW, PATTERN_TEW, LAYOUT_KM, LAYOUT_MK, EXPORTED_SYMBOLS,
 )

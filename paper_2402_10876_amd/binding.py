@@ -9,7 +9,7 @@ import os
 
 import numpy as np
 
-PATTERN_TW, PATTERN_TVW = 0, 1
+PATTERN_TW, PATTERN_TVW, PATTERN_TEW = 0, 1, 2
 LAYOUT_KM, LAYOUT_MK = 0, 1
 
 EXPORTED_SYMBOLS = [
@@ -34,7 +34,9 @@ class _View(C.Structure):
                 ("cto_k", C.POINTER(C.c_int32)), ("val_off", C.POINTER(C.c_int64)),
                 ("values", C.POINTER(C.c_uint16)), ("meta_off", C.POINTER(C.c_int64)),
                 ("meta", C.POINTER(C.c_uint8)), ("valid", C.POINTER(C.c_uint8)),
-                ("tile_col_off", C.POINTER(C.c_int32))]
+                ("tile_col_off", C.POINTER(C.c_int32)), ("ew_nnz", C.c_int64),
+                ("ew_col_ptr", C.POINTER(C.c_int32)), ("ew_row", C.POINTER(C.c_int32)),
+                ("ew_val", C.POINTER(C.c_uint16))]
 
 
 def lib_path() -> str:
@@ -123,9 +125,13 @@ class PackedWeight:
         tco = arr(v.tile_col_off, nt + 1, np.int32)
         out["tile_col_off"] = tco
         widths = [int(tco[t + 1] - tco[t]) for t in range(nt)]
-        if v.pattern == PATTERN_TW:
+        if v.pattern in (PATTERN_TW, PATTERN_TEW):
             out["values"] = [vals[voff[t]:voff[t + 1]].reshape(int(tko[t + 1] - tko[t]), widths[t])
                              for t in range(nt)]
+            if v.pattern == PATTERN_TEW:
+                out["ew_col_ptr"] = arr(v.ew_col_ptr, v.N + 1, np.int32)
+                out["ew_row"] = arr(v.ew_row, int(v.ew_nnz), np.int32)
+                out["ew_val"] = arr(v.ew_val, int(v.ew_nnz), np.uint16)
         else:
             moff = arr(v.meta_off, nt + 1, np.int64)
             meta = arr(v.meta, int(moff[-1]) if moff.size else 0, np.uint8)

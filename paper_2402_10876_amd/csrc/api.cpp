@@ -78,7 +78,9 @@ tw_status tw_pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* ti
   if (!out) return TW_ERR_ARG;
   *out = nullptr;
   if (!B || !mask || K < 1 || N < 1 || !valid_G(G)) return TW_ERR_ARG;
-  if (pattern != TW_PATTERN_TW && pattern != TW_PATTERN_TVW) return TW_ERR_ARG;
+  if (pattern != TW_PATTERN_TW && pattern != TW_PATTERN_TVW && pattern != TW_PATTERN_TEW) return TW_ERR_ARG;
+  if (pattern == TW_PATTERN_TEW && !tile_mask) return TW_ERR_ARG;
+  if (pattern == TW_PATTERN_TEW && K > 65536) return TW_ERR_UNSUPPORTED;   // restored rows travel as 16 bits
   tw_handle_s* h = new (std::nothrow) tw_handle_s();
   if (!h) return TW_ERR_ALLOC;
   tw_status st = twg::pack_host(B, mask, tile_mask, K, N, G, pattern, h);
@@ -95,11 +97,12 @@ tw_status tw_upload(tw_handle_t h) {
   if (hipGetDevice(&dev) != hipSuccess) return TW_ERR_HIP;
   // one allocation, 256-byte aligned parts
   struct Part { const void* src; size_t bytes; size_t off; };
-  Part parts[8] = {
+  Part parts[10] = {
       {d.col_idx.data(), d.col_idx.size() * 4, 0},   {d.tile_kp_off.data(), d.tile_kp_off.size() * 4, 0},
       {d.row_idx.data(), d.row_idx.size() * 4, 0},   {d.zero_cols.data(), d.zero_cols.size() * 4, 0},
       {d.tile_order.data(), d.tile_order.size() * 4, 0}, {d.vals.data(), d.vals.size() * 2, 0},
-      {d.meta.data(), d.meta.size() * 4, 0}, {d.tile_sched.data(), d.tile_sched.size() * 4, 0}};
+      {d.meta.data(), d.meta.size() * 4, 0}, {d.tile_sched.data(), d.tile_sched.size() * 4, 0},
+      {d.ew_ptr.data(), d.ew_ptr.size() * 4, 0}, {d.ew_pairs.data(), d.ew_pairs.size() * 4, 0}};
   size_t total = 0;
   for (auto& p : parts) { p.off = total; total += align_up(p.bytes ? p.bytes : 1, 256); }
   void* blob = nullptr;
@@ -120,6 +123,8 @@ tw_status tw_upload(tw_handle_t h) {
   d.d_vals = (const uint16_t*)(b + parts[5].off);
   d.d_meta = (const uint32_t*)(b + parts[6].off);
   d.d_tile_sched = (const int32_t*)(b + parts[7].off);
+  d.d_ew_ptr = (const int32_t*)(b + parts[8].off);
+  d.d_ew_pairs = (const uint32_t*)(b + parts[9].off);
   d.blob = blob; d.blob_bytes = total; d.device = dev;
   return TW_OK;
 }
@@ -156,7 +161,7 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
   if (!h->img.blob) return TW_ERR_STATE;
   if (layout == TW_LAYOUT_MK) {
     if (lda < h->K || ldc < h->N) return TW_ERR_ARG;
-    if (h->pattern == TW_PATTERN_TVW) return TW_ERR_UNSUPPORTED;   // TVW exists for K x M only
+    if (h->pattern != TW_PATTERN_TW) return TW_ERR_UNSUPPORTED;   // TVW and TEW exist for K x M only
   } else if (lda < M || ldc < M) {
     return TW_ERR_ARG;
   }
@@ -168,6 +173,7 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
   g.tile_sched = h->img.d_tile_sched;
   g.zero_cols = h->img.d_zero_cols; g.n_zero = (int)h->img.zero_cols.size();
   g.meta = h->img.d_meta;
+  g.ew_ptr = h->img.d_ew_ptr; g.ew_pairs = h->img.d_ew_pairs;
   g.n_tiles = h->n_tiles; g.K = h->K; g.N = h->N; g.xcd_map = opt_xcd_map.load();
 #ifdef TWG_TRACE
   static int trace_launch = 0;
@@ -184,11 +190,16 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
     if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
     return e == hipSuccess ? TW_OK : TW_ERR_HIP;
   }
-  const int tm = pick_tile_m(M, h->n_tiles > 0 ? h->n_tiles : 1, h->G, h->max_kp);
+  int tm = pick_tile_m(M, h->n_tiles > 0 ? h->n_tiles : 1, h->G, h->max_kp);
+  if (h->pattern == TW_PATTERN_TEW && h->G == 64 && tm == 64) tm = 128;   // no 64 x 64 instance there
   hipError_t e = hipErrorInvalidValue;
+  // TEW: the same kernels with the restored elements added in the epilogue (3 stages only)
+  const bool tew = h->pattern == TW_PATTERN_TEW;
+  auto launch_dma = tew ? twg::launch_tew_km_dma : twg::launch_tw_km_dma;
+  const int depth = tew ? 3 : opt_depth.load();
   // the asynchronous kernel addresses A with 32-bit byte offsets
   const bool a_fits32 = (unsigned long long)h->K * (unsigned long long)lda * 2ull < (1ull << 32);
-  if (opt_kernel.load() != 1 && h->G != 32 && a_fits32) {
+  if ((opt_kernel.load() != 1 || tew) && h->G != 32 && a_fits32) {
     // long K with too few tiles to fill the chip: split K inside the workgroup
     // 256-row tiles run with 8 waves (64 x 64 per wave): half the registers per wave, two
     // workgroups per CU
@@ -197,12 +208,11 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
     const int ks = opt_ksplit.load();
     if (ks == 2 || (ks == 0 && use_ksplit(M, h->n_tiles, h->max_kp, &tmk))) variant = twg::DMA_KSPLIT2;
     if (variant == twg::DMA_KSPLIT2 && ks == 2) tmk = tm == 256 ? 128 : tm;
-    e = twg::launch_tw_km_dma(h->G, variant == twg::DMA_KSPLIT2 ? tmk : tm, opt_depth.load(), variant, g,
-                              (hipStream_t)stream);
+    e = launch_dma(h->G, variant == twg::DMA_KSPLIT2 ? tmk : tm, depth, variant, g, (hipStream_t)stream);
     if (e == hipErrorInvalidValue && variant != twg::DMA_WAVES4)
-      e = twg::launch_tw_km_dma(h->G, tm, opt_depth.load(), twg::DMA_WAVES4, g, (hipStream_t)stream);
+      e = launch_dma(h->G, tm, depth, twg::DMA_WAVES4, g, (hipStream_t)stream);
   }
-  if (e == hipErrorInvalidValue && opt_kernel.load() != 2)
+  if (e == hipErrorInvalidValue && opt_kernel.load() != 2 && !tew)
     e = twg::launch_tw_km(h->G, tm, g, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;
@@ -260,6 +270,10 @@ tw_status tw_export(tw_handle_t h, tw_packed_view* out) {
   out->tile_k_off = h->tile_k_off.data(); out->row_idx = h->row_idx.data();
   out->cto_k = h->cto_k.data(); out->val_off = h->val_off.data(); out->values = h->values.data();
   out->tile_col_off = h->tile_col_off.data();
+  if (h->pattern == TW_PATTERN_TEW) {
+    out->ew_nnz = (int64_t)h->ew_row.size();
+    out->ew_col_ptr = h->ew_col_ptr.data(); out->ew_row = h->ew_row.data(); out->ew_val = h->ew_val.data();
+  }
   if (h->pattern == TW_PATTERN_TVW) {
     out->meta_off = h->meta_off.data(); out->meta = h->meta.data(); out->valid = h->valid.data();
   }

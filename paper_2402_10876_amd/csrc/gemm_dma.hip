@@ -84,7 +84,55 @@ __device__ __forceinline__ void wait_vm() {
 // 32g..32g+31 of it, and the two partial accumulators are added through LDS
 // (in fp32, before the single rounding).  It gives a tile two waves per SIMD,
 // which long-K problems with few tiles need to keep the matrix cores busy.
-template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KSPLIT = 1>
+
+// ---- TEW: restored elements (Section III-A "TEW": the element-wise part is kept in
+// compressed sparse column form and, the product being linear, computed apart from the
+// TW part).  Here it is added to the fp32 sums of the thread that stores the 8 values
+// C^T[col][m .. m+8): for every restored (k, v) of the column, s += v * A^T[k][m .. m+8).
+// Pairs travel as k << 16 | fp16 bits; the list is padded in registers with
+// (row 0, +0), which adds nothing.  A rows are lda >= round-up-8(M) halves long, so the
+// 16-byte read at m < M stays inside the row; lanes at or past M are not stored.
+__device__ __forceinline__ void ew_accumulate(const GemmArgs& g, int lo, int hi, const _Float16* A_m,
+                                              float (&s)[8]) {
+  for (int e = lo; e < hi; e += 4) {
+    uint32_t pr[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) pr[u] = e + u < hi ? g.ew_pairs[e + u] : 0u;
+    half8 a[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) a[u] = *(const half8*)(A_m + (size_t)(pr[u] >> 16) * g.lda);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      union { uint16_t b; _Float16 h; } cv;
+      cv.b = (uint16_t)(pr[u] & 0xffffu);
+      const float v = (float)cv.h;
+#pragma unroll
+      for (int q = 0; q < 8; ++q) s[q] = __builtin_fmaf(v, (float)a[u][q], s[q]);
+    }
+  }
+}
+
+__device__ __forceinline__ void store_row_chunk(const GemmArgs& g, _Float16* dst, int m, const float (&s)[8]) {
+  half8 h;
+#pragma unroll
+  for (int q = 0; q < 8; ++q) h[q] = (_Float16)s[q];
+  if (m + 8 <= g.M) __builtin_nontemporal_store(h, (half8*)dst);
+  else for (int q = 0; m + q < g.M; ++q) dst[q] = h[q];
+}
+
+// A column the TW step dropped: nothing but its restored elements (usually none: +0).
+__device__ __forceinline__ void ew_fill_column(const GemmArgs& g, int which) {
+  const int col = g.zero_cols[which];
+  const int lo = g.ew_ptr[col], hi = g.ew_ptr[col + 1];
+  _Float16* row = g.C + (size_t)col * g.ldc;
+  for (int m = threadIdx.x * 8; m < g.M; m += (int)blockDim.x * 8) {
+    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    ew_accumulate(g, lo, hi, g.A + m, s);
+    store_row_chunk(g, row + m, m, s);
+  }
+}
+
+template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KSPLIT = 1, bool EW = false>
 __global__ __launch_bounds__(NWAVES * 64) void tw_gemm_km_dma_kernel(GemmArgs g) {
   constexpr int NT = NWAVES * 64;          // threads of the workgroup
   constexpr int WPG = NWAVES / KSPLIT;     // waves per group
@@ -103,7 +151,10 @@ __global__ __launch_bounds__(NWAVES * 64) void tw_gemm_km_dma_kernel(GemmArgs g)
   static_assert(D == 3 || D == 4, "the stage wait below handles up to two newer stages");
   constexpr int NPS = NIA + NIB;
   constexpr int CA = TM / 8;
-  constexpr int CS = (TM + 4) * 2;                     // epilogue row bytes: 66 dwords mod 64 banks = 2
+  // epilogue row bytes: fp16, 66 dwords mod 64 banks = 2; with restored elements to add (EW) the
+  // tile is staged in fp32 so that their products join the sum before the one rounding
+  constexpr int CS = EW ? (TM + 4) * 4 : (TM + 4) * 2;
+  static_assert(!(EW && DENSE), "");
   constexpr int PIPE_BYTES = D * STAGE, EPI_BYTES = TN * CS;
   constexpr int RED_BYTES = KSPLIT > 1 ? TM * TN * 4 : 0;      // partial accumulators of group 1
   static_assert(RED_BYTES <= PIPE_BYTES, "the reduction reuses the pipeline buffers");
@@ -117,7 +168,8 @@ __global__ __launch_bounds__(NWAVES * 64) void tw_gemm_km_dma_kernel(GemmArgs g)
   TWG_STAMP();
   TWG_STAMP_CLK(0);
   if ((int)blockIdx.x >= n_gemm) {
-    zero_fill_column(g, blockIdx.x - n_gemm);
+    if constexpr (EW) ew_fill_column(g, blockIdx.x - n_gemm);
+    else zero_fill_column(g, blockIdx.x - n_gemm);
     return;
   }
   int mt, t;                             // t: launch position of the tile, then the tile itself
@@ -144,6 +196,15 @@ __global__ __launch_bounds__(NWAVES * 64) void tw_gemm_km_dma_kernel(GemmArgs g)
     const int n = r0 + i * ROWS_PER_PASS;
     if constexpr (DENSE) { cols[i] = t * TN + n; if (cols[i] >= g.N) cols[i] = -1; }
     else cols[i] = g.col_idx[t * TN + n];
+  }
+  // restored elements of those columns (TEW): [ew_lo, ew_hi) in the pair list
+  int ew_lo[EW ? NPASS : 1], ew_hi[EW ? NPASS : 1];
+  if constexpr (EW) {
+#pragma unroll
+    for (int i = 0; i < NPASS; ++i) {
+      ew_lo[i] = cols[i] >= 0 ? g.ew_ptr[cols[i]] : 0;
+      ew_hi[i] = cols[i] >= 0 ? g.ew_ptr[cols[i] + 1] : 0;
+    }
   }
 
   // ---- geometry of the asynchronous copies --------------------------------
@@ -350,57 +411,108 @@ __global__ __launch_bounds__(NWAVES * 64) void tw_gemm_km_dma_kernel(GemmArgs g)
     }
     __syncthreads();
   }
-  if (grp == 0) {
+  if constexpr (EW) {
+    // fp32 staging, then every thread finishes its (column, 8 x m) pieces: restored
+    // elements added, one rounding, streaming store
+    if (grp == 0) {
 #pragma unroll
-    for (int i = 0; i < MB; ++i)
+      for (int i = 0; i < MB; ++i)
 #pragma unroll
-      for (int j = 0; j < NB; ++j) {
-        const int n = wn * WN + j * 32 + (lane & 31);
+        for (int j = 0; j < NB; ++j) {
+          const int n = wn * WN + j * 32 + (lane & 31);
 #pragma unroll
-        for (int rq = 0; rq < 4; ++rq) {
-          const int mm = wm * WM + i * 32 + 8 * rq + 4 * (lane >> 5);
-          half4 v;
+          for (int rq = 0; rq < 4; ++rq) {
+            const int mm = wm * WM + i * 32 + 8 * rq + 4 * (lane >> 5);
+            floatx4 v;
 #pragma unroll
-          for (int r = 0; r < 4; ++r) v[r] = (_Float16)acc[i][j][rq * 4 + r];
-          *(half4*)(lds + n * CS + mm * 2) = v;
+            for (int r = 0; r < 4; ++r) v[r] = acc[i][j][rq * 4 + r];
+            *(floatx4*)(lds + n * CS + mm * 4) = v;
+          }
         }
-      }
-  }
-  __syncthreads();
-  TWG_STAMP_FINE();
-  // all staged chunks into registers first, then the stores back to back; C is
-  // written once and not read again here: streaming (non-temporal) stores keep it
-  // from lingering dirty in L2 until the end-of-kernel write-back
-  union Chunk { uint2 h[2]; u32x4 v; };   // staging rows are 8-byte aligned only
-  Chunk ck[NPASS];
+    }
+    __syncthreads();
 #pragma unroll
-  for (int i = 0; i < NPASS; ++i) {
-    const int n = r0 + i * ROWS_PER_PASS;
-    ck[i].h[0] = *(const uint2*)(lds + n * CS + c * 16);
-    ck[i].h[1] = *(const uint2*)(lds + n * CS + c * 16 + 8);
-  }
-#pragma unroll
-  for (int i = 0; i < NPASS; ++i) {
-    if (dst_off[i] < 0) continue;
-    _Float16* dst = g.C + dst_off[i];
-    if (m + 8 <= g.M) __builtin_nontemporal_store(ck[i].v, (u32x4*)dst);
-    else {
+    for (int i = 0; i < NPASS; ++i) {
+      if (dst_off[i] < 0) continue;
       const int n = r0 + i * ROWS_PER_PASS;
-      const _Float16* e = (const _Float16*)(lds + n * CS + c * 16);
-      for (int qq = 0; m + qq < g.M; ++qq) dst[qq] = e[qq];
+      const floatx4 lo4 = *(const floatx4*)(lds + n * CS + c * 32);
+      const floatx4 hi4 = *(const floatx4*)(lds + n * CS + c * 32 + 16);
+      float sum[8] = {lo4[0], lo4[1], lo4[2], lo4[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+      ew_accumulate(g, ew_lo[i], ew_hi[i], g.A + m, sum);
+      store_row_chunk(g, g.C + dst_off[i], m, sum);
+    }
+  } else {
+    if (grp == 0) {
+  #pragma unroll
+      for (int i = 0; i < MB; ++i)
+  #pragma unroll
+        for (int j = 0; j < NB; ++j) {
+          const int n = wn * WN + j * 32 + (lane & 31);
+  #pragma unroll
+          for (int rq = 0; rq < 4; ++rq) {
+            const int mm = wm * WM + i * 32 + 8 * rq + 4 * (lane >> 5);
+            half4 v;
+  #pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] = (_Float16)acc[i][j][rq * 4 + r];
+            *(half4*)(lds + n * CS + mm * 2) = v;
+          }
+        }
+    }
+    __syncthreads();
+    TWG_STAMP_FINE();
+    // all staged chunks into registers first, then the stores back to back; C is
+    // written once and not read again here: streaming (non-temporal) stores keep it
+    // from lingering dirty in L2 until the end-of-kernel write-back
+    union Chunk { uint2 h[2]; u32x4 v; };   // staging rows are 8-byte aligned only
+    Chunk ck[NPASS];
+  #pragma unroll
+    for (int i = 0; i < NPASS; ++i) {
+      const int n = r0 + i * ROWS_PER_PASS;
+      ck[i].h[0] = *(const uint2*)(lds + n * CS + c * 16);
+      ck[i].h[1] = *(const uint2*)(lds + n * CS + c * 16 + 8);
+    }
+  #pragma unroll
+    for (int i = 0; i < NPASS; ++i) {
+      if (dst_off[i] < 0) continue;
+      _Float16* dst = g.C + dst_off[i];
+      if (m + 8 <= g.M) __builtin_nontemporal_store(ck[i].v, (u32x4*)dst);
+      else {
+        const int n = r0 + i * ROWS_PER_PASS;
+        const _Float16* e = (const _Float16*)(lds + n * CS + c * 16);
+        for (int qq = 0; m + qq < g.M; ++qq) dst[qq] = e[qq];
+      }
     }
   }
   TWG_STAMP();
   TWG_STAMP_CLK(1);
 }
 
-template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KSPLIT = 1>
+template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KSPLIT = 1, bool EW = false>
 static hipError_t launch(const GemmArgs& g, hipStream_t stream) {
   const int grid = g.n_mtiles * g.n_tiles + g.n_zero;
   if (grid <= 0) return hipSuccess;
-  hipLaunchKernelGGL((tw_gemm_km_dma_kernel<TM, TN, WAVES_M, D, DENSE, NWAVES, KSPLIT>), dim3(grid),
+  hipLaunchKernelGGL((tw_gemm_km_dma_kernel<TM, TN, WAVES_M, D, DENSE, NWAVES, KSPLIT, EW>), dim3(grid),
                      dim3(NWAVES * 64), 0, stream, g);
   return hipGetLastError();
+}
+
+// TEW instances: three stages in flight only.
+static hipError_t dispatch_ew(int G, int tm, int variant, GemmArgs& g, hipStream_t stream) {
+  g.n_mtiles = (g.M + tm - 1) / tm;
+  if (variant == DMA_KSPLIT2) {
+    if (G == 128 && tm == 128) return launch<128, 128, 2, 3, false, 8, 2, true>(g, stream);
+    if (G == 128 && tm == 64) return launch<64, 128, 1, 3, false, 8, 2, true>(g, stream);
+    return hipErrorInvalidValue;
+  }
+  if (variant == DMA_WAVES8) {
+    if (G == 128 && tm == 256) return launch<256, 128, 4, 3, false, 8, 1, true>(g, stream);
+    return hipErrorInvalidValue;
+  }
+  if (G == 128 && tm == 64) return launch<64, 128, 1, 3, false, 4, 1, true>(g, stream);
+  if (G == 128 && tm == 128) return launch<128, 128, 2, 3, false, 4, 1, true>(g, stream);
+  if (G == 64 && tm == 128) return launch<128, 64, 2, 3, false, 4, 1, true>(g, stream);
+  if (G == 64 && tm == 256) return launch<256, 64, 4, 3, false, 4, 1, true>(g, stream);
+  return hipErrorInvalidValue;
 }
 
 template <bool DENSE>
@@ -437,6 +549,10 @@ extern "C" int tw_debug_read_trace_dma(unsigned long long* out, int n) {
 
 hipError_t launch_tw_km_dma(int G, int tm, int depth, int variant, GemmArgs g, hipStream_t stream) {
   return dispatch<false>(G, tm, depth, variant, g, stream);
+}
+hipError_t launch_tew_km_dma(int G, int tm, int depth, int variant, GemmArgs g, hipStream_t stream) {
+  if (depth != 3) return hipErrorInvalidValue;
+  return dispatch_ew(G, tm, variant, g, stream);
 }
 hipError_t launch_dense_km_dma(int tn, int tm, int depth, int variant, GemmArgs g, hipStream_t stream) {
   return dispatch<true>(tn, tm, depth, variant, g, stream);

@@ -19,6 +19,8 @@ struct GemmArgs {
   const int32_t* tile_sched;     // TW: per launch position {tile, kp offset, Kp_t, width}, 16-byte records
   const int32_t* zero_cols;      // pruned columns of C, written as +0
   const uint32_t* meta;          // TVW: 2:4 position words
+  const int32_t* ew_ptr;         // TEW: N+1 offsets into ew_pairs by original column of C
+  const uint32_t* ew_pairs;      // TEW: restored elements, K row << 16 | fp16 bits
   int n_zero;
   int n_tiles, n_mtiles;
   int K, N;                      // dense only
@@ -42,6 +44,8 @@ hipError_t launch_dense_mk(int tn, GemmArgs g, hipStream_t stream);
 // the workgroup (dense: K % 64 == 0).
 enum { DMA_WAVES4 = 0, DMA_WAVES8 = 1, DMA_KSPLIT2 = 2 };
 hipError_t launch_tw_km_dma(int G, int tm, int depth, int variant, GemmArgs g, hipStream_t stream);
+// The same with the restored elements of a TEW weight added in the epilogue (g.ew_*).
+hipError_t launch_tew_km_dma(int G, int tm, int depth, int variant, GemmArgs g, hipStream_t stream);
 hipError_t launch_dense_km_dma(int tn, int tm, int depth, int variant, GemmArgs g, hipStream_t stream);
 // TVW (2:4 inside the kept rows) on the sparse matrix instruction (gemm_tvw.hip).
 hipError_t launch_tvw_km(int G, int tm, int depth, GemmArgs g, hipStream_t stream);

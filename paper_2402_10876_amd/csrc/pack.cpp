@@ -71,8 +71,8 @@ bool is_tile_wise(const uint8_t* S, int K, int N, int G, const std::vector<int32
 tw_status pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_mask, int K,
                     int N, int G, int pattern, tw_handle_s* h) try {
   h->K = K; h->N = N; h->G = G; h->pattern = pattern;
-  const bool tvw = pattern == TW_PATTERN_TVW;
-  const uint8_t* S = (tvw && tile_mask) ? tile_mask : mask;
+  const bool tvw = pattern == TW_PATTERN_TVW, tew = pattern == TW_PATTERN_TEW;
+  const uint8_t* S = ((tvw || tew) && tile_mask) ? tile_mask : mask;
   structure_of(S, K, N, G, h->col_idx, h->tile_k_off, h->row_idx);
   h->n_kept = (int32_t)h->col_idx.size();
   h->n_tiles = (int32_t)h->tile_k_off.size() - 1;
@@ -84,6 +84,18 @@ tw_status pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_
   if (tvw && tile_mask) {
     for (size_t i = 0, e = (size_t)K * N; i < e; ++i)
       if (mask[i] && !tile_mask[i]) return TW_ERR_MASK;
+  }
+  if (tew) {   // the restored elements: in the mask, not in the tile mask; column by column
+    for (size_t i = 0, e = (size_t)K * N; i < e; ++i)
+      if (tile_mask[i] && !mask[i]) return TW_ERR_MASK;
+    h->ew_col_ptr.assign(N + 1, 0);
+    for (int n = 0; n < N; ++n) {
+      for (int k = 0; k < K; ++k) {
+        const size_t i = (size_t)k * N + n;
+        if (mask[i] && !tile_mask[i]) { h->ew_row.push_back(k); h->ew_val.push_back(B[i]); }
+      }
+      h->ew_col_ptr[n + 1] = (int32_t)h->ew_row.size();
+    }
   }
   h->cto_n.resize(h->n_kept);
   for (int j = 0; j < h->n_kept; ++j) h->cto_n[j] = h->col_idx[j] - j;
@@ -108,6 +120,7 @@ tw_status pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_
   {
     std::vector<uint8_t> used(K, 0);
     for (int32_t r : h->row_idx) used[r] = 1;
+    for (int32_t r : h->ew_row) used[r] = 1;
     h->k_union = 0;
     for (int k = 0; k < K; ++k) h->k_union += used[k];
   }
@@ -176,7 +189,7 @@ tw_status unpack_host(const tw_handle_s* h, uint16_t* Bm, uint8_t* mask) {
     const int w = h->tile_col_off[t + 1] - h->tile_col_off[t];
     const uint16_t* v = h->values.data() + h->val_off[t];
     const int32_t* cols = h->col_idx.data() + h->tile_col_off[t];
-    if (h->pattern == TW_PATTERN_TW) {
+    if (h->pattern != TW_PATTERN_TVW) {
       for (int j = 0; j < kt; ++j) {
         const size_t row = (size_t)h->row_idx[k0 + j] * h->N;
         for (int c = 0; c < w; ++c) {
@@ -199,6 +212,12 @@ tw_status unpack_host(const tw_handle_s* h, uint16_t* Bm, uint8_t* mask) {
           }
     }
   }
+  for (int n = 0; n + 1 < (int)h->ew_col_ptr.size(); ++n)
+    for (int e = h->ew_col_ptr[n]; e < h->ew_col_ptr[n + 1]; ++e) {
+      const size_t at = (size_t)h->ew_row[e] * h->N + n;
+      if (Bm) Bm[at] = h->ew_val[e];
+      if (mask) mask[at] = 1;
+    }
   return TW_OK;
 }
 
@@ -211,6 +230,7 @@ tw_status concat_host(const tw_handle_s* const* parts, int n, tw_handle_s* h) tr
   h->N = 0; h->n_kept = 0; h->n_tiles = 0; h->sum_kw = 0; h->sum_k = 0;
   h->tile_col_off.assign(1, 0); h->tile_k_off.assign(1, 0);
   h->val_off.assign(1, 0); h->meta_off.assign(1, 0);
+  if (h->pattern == TW_PATTERN_TEW) h->ew_col_ptr.assign(1, 0);
   for (int i = 0; i < n; ++i) {
     const tw_handle_s* p = parts[i];
     if (p->K != h->K || p->G != h->G || p->pattern != h->pattern) return TW_ERR_ARG;
@@ -227,6 +247,11 @@ tw_status concat_host(const tw_handle_s* const* parts, int n, tw_handle_s* h) tr
     h->values.insert(h->values.end(), p->values.begin(), p->values.end());
     h->meta.insert(h->meta.end(), p->meta.begin(), p->meta.end());
     h->valid.insert(h->valid.end(), p->valid.begin(), p->valid.end());
+    if (h->pattern == TW_PATTERN_TEW) {
+      for (int c = 1; c <= p->N; ++c) h->ew_col_ptr.push_back((int32_t)h->ew_row.size() + p->ew_col_ptr[c]);
+      h->ew_row.insert(h->ew_row.end(), p->ew_row.begin(), p->ew_row.end());
+      h->ew_val.insert(h->ew_val.end(), p->ew_val.begin(), p->ew_val.end());
+    }
     h->N += p->N; h->n_kept += p->n_kept; h->n_tiles += p->n_tiles;
     h->sum_kw += p->sum_kw; h->sum_k += p->sum_k;
   }
@@ -234,6 +259,7 @@ tw_status concat_host(const tw_handle_s* const* parts, int n, tw_handle_s* h) tr
   for (int j = 0; j < h->n_kept; ++j) h->cto_n[j] = h->col_idx[j] - j;
   std::vector<uint8_t> used(h->K, 0);
   for (int32_t r : h->row_idx) used[r] = 1;
+  for (int32_t r : h->ew_row) used[r] = 1;
   h->k_union = 0;
   for (int k = 0; k < h->K; ++k) h->k_union += used[k];
   build_device_image(h);
@@ -292,6 +318,10 @@ void build_device_image(tw_handle_s* h) {
       d.zero_cols.push_back(n);
     }
   }
+  d.ew_ptr = h->ew_col_ptr;
+  d.ew_pairs.resize(h->ew_row.size());
+  for (size_t e = 0; e < h->ew_row.size(); ++e)
+    d.ew_pairs[e] = (uint32_t)h->ew_row[e] << 16 | h->ew_val[e];
   d.tile_order.resize(nt);
   for (int t = 0; t < nt; ++t) d.tile_order[t] = t;
   if (longest_first.load())

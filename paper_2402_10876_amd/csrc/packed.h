@@ -26,6 +26,8 @@ struct DeviceImage {
   std::vector<int32_t> tile_sched;   // per launch position: {tile, kp offset, Kp_t, width}
   std::vector<uint16_t> vals;        // TW: [sum Kp_t][G]; TVW: swizzled compressed values
   std::vector<uint32_t> meta;        // TVW: swizzled 2-bit position words
+  std::vector<int32_t> ew_ptr;       // TEW: N+1 offsets into ew_pairs, by original column
+  std::vector<uint32_t> ew_pairs;    // TEW: restored elements, row << 16 | fp16 bits
   // device copies (one allocation, sub-pointers)
   void* blob = nullptr;
   size_t blob_bytes = 0;
@@ -38,6 +40,8 @@ struct DeviceImage {
   const int32_t* d_tile_sched = nullptr;
   const uint16_t* d_vals = nullptr;
   const uint32_t* d_meta = nullptr;
+  const int32_t* d_ew_ptr = nullptr;
+  const uint32_t* d_ew_pairs = nullptr;
 };
 
 }  // namespace twg
@@ -49,6 +53,8 @@ struct tw_handle_s {
   std::vector<int64_t> val_off, meta_off;
   std::vector<uint16_t> values;
   std::vector<uint8_t> meta, valid;
+  std::vector<int32_t> ew_col_ptr, ew_row;   // TEW: restored elements, CSC over original columns
+  std::vector<uint16_t> ew_val;
   int64_t sum_kw = 0, sum_k = 0;
   int32_t k_union = 0;  // K rows kept by at least one tile
   int32_t max_kp = 0;  // largest padded K_t
