@@ -94,15 +94,22 @@ __device__ __forceinline__ void wait_vm() {
 // 16-byte read at m < M stays inside the row; lanes at or past M are not stored.
 __device__ __forceinline__ void ew_accumulate(const GemmArgs& g, int lo, int hi, const _Float16* A_m,
                                               float (&s)[8]) {
-  for (int e = lo; e < hi; e += 4) {
-    uint32_t pr[4];
+  constexpr int U = 8;     // elements per round trip; the next U pairs are fetched while these U rows arrive
+  uint32_t nx[U];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) pr[u] = e + u < hi ? g.ew_pairs[e + u] : 0u;
-    half8 a[4];
+  for (int u = 0; u < U; ++u) nx[u] = lo + u < hi ? g.ew_pairs[lo + u] : 0u;
+  for (int e = lo; e < hi; e += U) {
+    uint32_t pr[U];
+    half8 a[U];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) a[u] = *(const half8*)(A_m + (size_t)(pr[u] >> 16) * g.lda);
+    for (int u = 0; u < U; ++u) {
+      pr[u] = nx[u];
+      a[u] = *(const half8*)(A_m + (size_t)(pr[u] >> 16) * g.lda);
+    }
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < U; ++u) nx[u] = e + U + u < hi ? g.ew_pairs[e + U + u] : 0u;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
       union { uint16_t b; _Float16 h; } cv;
       cv.b = (uint16_t)(pr[u] & 0xffffu);
       const float v = (float)cv.h;

@@ -9,7 +9,7 @@ paper's 4096 x 4096 x 4096 sparsity sweep (Section VI-B; TVW at 50 % is plain
 2:4).  `--imbalance` times uneven tiles (one magnitude threshold over all
 tile rows of the matrix instead of one per tile: Section IV "global weight
 pruning", Section V "load imbalance") with the tiles launched longest first and
-in column order.
+in column order.  `--tew` adds the TEW pattern (TW plus delta restored elements).
 """
 from __future__ import annotations
 
@@ -34,6 +34,8 @@ def main():
     ap.add_argument("--configs", default="2,3,4,5")
     ap.add_argument("--cube", action="store_true")
     ap.add_argument("--imbalance", action="store_true")
+    ap.add_argument("--tew", action="store_true",
+                    help="TEW at 75 % with delta = 0.5, 1.5 and 5 % on the BERT shapes (Section VI, impact of delta)")
     ap.add_argument("--reps", type=int, default=24)
     ap.add_argument("--sets", type=int, default=6)
     args = ap.parse_args()
@@ -119,16 +121,24 @@ def main():
                 print(json.dumps(row), flush=True)
             del A, C
 
+    if args.tew:
+        for cfg, si in ((2, 0), (2, 1), (2, 2), (4, 0), (4, 1)):
+            for delta in (0.005, 0.015, 0.05):
+                plan.append((cfg, si, "tew", 0.75, 128, delta))
+
     dense_cache = {}
-    for cfg, si, pattern, sp, G in plan:
+    for entry in plan:
+        cfg, si, pattern, sp, G = entry[:5]
+        delta = entry[5] if len(entry) > 5 else 0.0
         shp = wl.SHAPES[cfg][si]
         M, K, N = shp.M, shp.K, shp.N
         nsets = max(2, min(args.sets, int(600e6 // (2 * M * (K + N)))))
         cf = 0.0 if sp == 0.0 or (pattern == "tvw" and sp == 0.5) else None
-        c = wl.make_case(cfg, si, pattern=pattern, sparsity=sp, G=G, col_frac=cf, with_A=False)
-        pat = tw.PATTERN_TW if pattern == "tw" else tw.PATTERN_TVW
-        packed = [tw.tw_pack(c.B, c.mask, G, pat, tile_mask=c.tile_mask if pattern == "tvw" else None)
+        c = wl.make_case(cfg, si, pattern=pattern, sparsity=sp, G=G, col_frac=cf, with_A=False, delta=delta)
+        pat = {"tw": tw.PATTERN_TW, "tvw": tw.PATTERN_TVW, "tew": tw.PATTERN_TEW}[pattern]
+        packed = [tw.tw_pack(c.B, c.mask, G, pat, tile_mask=c.tile_mask if pattern != "tw" else None)
                   for _ in range(nsets)]
+        nnz_ew = int(c.mask.sum() - c.tile_mask.sum()) if pattern == "tew" else 0
         A = [torch.randn((K, M), dtype=torch.float16, device=dev) for _ in range(nsets)]
         C = [torch.empty((N, M), dtype=torch.float16, device=dev) for _ in range(nsets)]
         skw, sk, ku = packed[0].flop_counts()
@@ -141,11 +151,12 @@ def main():
                                                                 C[r % nsets].data_ptr(), M, K, N, M, N, M,
                                                                 tw.LAYOUT_KM, stream), args.reps)
         td = dense_cache[key]
-        ab = alg_bytes(M, ku, N, pattern, skw, sk)
-        issued = 2.0 * M * skw if pattern == "tw" else 1.0 * M * skw
+        ab = alg_bytes(M, ku, N, "tw" if pattern == "tew" else pattern, skw, sk) + 4 * nnz_ew + (4 * (N + 1) if nnz_ew else 0)
+        issued = 1.0 * M * skw if pattern == "tvw" else 2.0 * M * skw
         t_hbm, t_mfma = ab / HBM, issued / MFMA
         print(json.dumps(dict(
             shape=shp.name, M=M, K=K, N=N, G=G, pattern=pattern, sparsity=sp, K_union=ku,
+            **(dict(delta=delta, restored=nnz_ew, ew_gather_MB=round(2.0 * M * nnz_ew / 1e6, 1)) if pattern == "tew" else {}),
             us=round(t * 1e6, 2), dense_us=round(td * 1e6, 2), speedup_vs_dense=round(td / t, 3),
             dense_eq_tflops=round(2.0 * M * K * N / t / 1e12, 1),
             condensed_mfma_util=round(2.0 * M * skw / t / MFMA, 4),
