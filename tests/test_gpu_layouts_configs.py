@@ -173,3 +173,47 @@ def test_config5_vgg_conv_256_full_size_sampled(pattern, sparsity, G):
     ref, S = _oracle(c, rows)
     assert_C_close(C[rows], ref, S)
     assert np.isfinite(C).all()
+
+
+@pytest.mark.parametrize("pattern", ["tw", "tvw", "dense"])
+def test_A_beyond_4_GiB_takes_the_64_bit_path(pattern):
+    """K * lda * 2 bytes >= 2^32: the asynchronous TW kernel (32-bit byte offsets into A) must
+    not be chosen; the kernels with 64-bit addressing give the oracle's values on sampled m."""
+    import torch
+    from tests.helpers import random_tvw_mask
+    K, N, G = 1032, 130, 128
+    M = (1 << 21) + 8
+    assert K * M * 2 >= 1 << 32
+    rng = np.random.default_rng(3)
+    if pattern == "dense":
+        mask = np.ones((K, N), np.uint8)
+        tm, pat = mask, None
+    elif pattern == "tw":
+        mask = random_tw_mask(rng, K, N, G, col_keep=0.8, row_keep=0.3)
+        tm, pat = mask, tw.PATTERN_TW
+    else:
+        mask, tm = random_tvw_mask(rng, K, N, G, col_keep=0.8, row_keep=0.3)
+        pat = tw.PATTERN_TVW
+    B = wl.make_B(3, K, N, 1.0)
+    print(f"case A beyond 4 GiB, {pattern}", flush=True)
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    At = torch.empty((K, M), dtype=torch.float16, device="cuda")
+    for k0 in range(0, K, 129):                       # in slabs: no 8 GiB fp32 temporary
+        At[k0:k0 + 129].copy_(torch.randn((min(129, K - k0), M), generator=gen, device="cuda", dtype=torch.float32))
+    Ct = torch.full((N, M), float("nan"), dtype=torch.float16, device="cuda")
+    st = torch.cuda.current_stream().cuda_stream
+    if pattern == "dense":
+        Bd = torch.from_numpy(np.ascontiguousarray(np.pad(B, ((0, 0), (0, 6))))).cuda()     # ldb = 136
+        tw.tw_dense_gemm(At.data_ptr(), Bd.data_ptr(), Ct.data_ptr(), M, K, N, M, 136, M, tw.LAYOUT_KM, st)
+        torch.cuda.synchronize()
+    else:
+        p = tw.tw_pack(B, mask, G, pat, tile_mask=tm if pattern == "tvw" else None)
+        tw.tw_gemm(At.data_ptr(), M, M, tw.LAYOUT_KM, p, Ct.data_ptr(), M, st)
+        torch.cuda.synchronize()
+        p.free()
+    idx = torch.from_numpy(np.concatenate([[0, 1, M - 1, M - 8, (1 << 20) + 3],
+                                           rng.integers(0, M, 43)])).cuda()
+    A_s = At[:, idx].T.contiguous().cpu().numpy()          # 48 x K
+    C_s = Ct[:, idx].T.contiguous().cpu().numpy().astype(np.float64)
+    del At, Ct
+    assert_C_close(C_s, og.gemm_oracle(A_s, B, mask), og.abs_bound(A_s, B, mask))
