@@ -54,6 +54,22 @@ def _prune_lowest(scores, count):
     return set(ranked[:count])
 
 
+def exact_square_scores(w16: np.ndarray):
+    """Element scores w^2 as exact Python integers in units of 2^-48.  An fp16
+    value is an integer multiple of 2^-24 (below 2^40 in those units), so its
+    square and any sum of squares are exact integers: ranking by them does not
+    depend on the order of summation."""
+    bits = w16.astype(np.float16).view(np.uint16).reshape(-1).tolist()
+    out = []
+    for h in bits:
+        e, m = (h >> 10) & 31, h & 1023
+        if e == 31:
+            raise ValueError("non-finite weight")
+        mag = m if e == 0 else (m | 1024) << (e - 1)
+        out.append(mag * mag)
+    return out
+
+
 def ew(w: np.ndarray, s_t: float) -> np.ndarray:
     """Algorithm 2, EW: element scores, one global threshold."""
     sc = (w.astype(np.float64) ** 2).reshape(-1).tolist()
@@ -65,18 +81,27 @@ def ew(w: np.ndarray, s_t: float) -> np.ndarray:
 
 
 def tw(w: np.ndarray, G: int, *, s_cols: float | None = None, n_cols_pruned: int | None = None,
-       s_rows: float | None = None, rows_kept_per_tile: int | None = None) -> np.ndarray:
+       s_rows: float | None = None, rows_kept_per_tile: int | None = None,
+       exact: bool = False) -> np.ndarray:
     """Algorithm 3, TW, with the two steps parameterised separately.
 
     TW-C: columns (K,1) scored and pruned, either a fraction s_cols or a count.
     Condense, then TW-R: the kept columns are cut into tiles of G and every
     (1,G) row piece is a unit; either one global threshold prunes a fraction
     s_rows of all units, or every tile keeps its `rows_kept_per_tile` best.
-    Returns the 0/1 mask (K x N).
+    `exact` scores with integers (exact_square_scores) instead of fp64 sums; only
+    with rows_kept_per_tile (a shared threshold over tiles of different width
+    needs the mean).  Returns the 0/1 mask (K x N).
     """
     K, N = w.shape
-    sq = w.astype(np.float64) ** 2
-    col_scores = [float(sq[:, n].sum()) for n in range(N)]
+    if exact:
+        if rows_kept_per_tile is None:
+            raise ValueError("exact scores are defined for the per-tile row count only")
+        sq = np.array(exact_square_scores(w), dtype=object).reshape(K, N)
+        col_scores = [sum(sq[:, n].tolist()) for n in range(N)]
+    else:
+        sq = w.astype(np.float64) ** 2
+        col_scores = [float(sq[:, n].sum()) for n in range(N)]
     if n_cols_pruned is None:
         n_cols_pruned = int(math.floor((s_cols or 0.0) * N))
     pruned_cols = _prune_lowest(col_scores, n_cols_pruned)
@@ -85,7 +110,7 @@ def tw(w: np.ndarray, G: int, *, s_cols: float | None = None, n_cols_pruned: int
     mask = np.zeros((K, N), dtype=np.uint8)
     if rows_kept_per_tile is not None:
         for cols in tiles:
-            sc = [float(sq[k, cols].sum()) for k in range(K)]
+            sc = [sum(sq[k, cols].tolist()) if exact else float(sq[k, cols].sum()) for k in range(K)]
             gone = _prune_lowest(sc, K - rows_kept_per_tile)
             for k in range(K):
                 if k not in gone:

@@ -236,3 +236,38 @@ def test_workloads_tew_equals_oracle(K, N, G, sp, delta, cf):
     m2, tm2 = op.tew(w, G, sp, delta,
                      tw_fn=lambda w_, s, G_: wl.tw_mask(w_, G_, density=1.0 - s, col_frac=cf))
     assert np.array_equal(tm, tm2) and np.array_equal(m, m2)
+
+
+# ---- exact integer scores (used where a GPU pruner has to take the same decisions) ------------
+def test_exact_square_scores_are_the_squares():
+    vals = np.array([0.0, -0.0, 6e-8, -6.1e-5, 1.0, -1.5, 0.333, 65504.0, -65504.0, 2.0 ** -24, 1023 * 2.0 ** -24],
+                    np.float16)
+    got = op.exact_square_scores(vals)
+    for v, s in zip(vals.tolist(), got):
+        assert s == int(round(float(v) * 2 ** 24)) ** 2          # float(v) * 2^24 is an exact integer
+        assert s * 2.0 ** -48 == float(v) ** 2 or s >= 2 ** 53    # and agrees with the fp64 square where that is exact
+
+
+@pytest.mark.parametrize("seed,K,N,G,cp,rk", [(0, 40, 36, 8, 4, 10), (1, 33, 50, 16, 0, 7), (2, 64, 70, 32, 9, 16)])
+def test_exact_scores_give_the_float_mask_on_generic_data(seed, K, N, G, cp, rk):
+    w = wl.rng_fp16(seed, (K, N))
+    assert np.array_equal(op.tw(w, G, n_cols_pruned=cp, rows_kept_per_tile=rk, exact=True),
+                          op.tw(w, G, n_cols_pruned=cp, rows_kept_per_tile=rk))
+
+
+def test_exact_scores_resolve_what_fp64_cannot():
+    """Column 0 holds one 64 and many tiny values whose squares fall below half an ulp of 4096 in
+    fp64 one by one; column 1 holds 64 alone.  Exactly, column 0 scores higher; a sequential fp64
+    sum cannot see it.  With exact scores column 1 is the one pruned."""
+    K = 40
+    w = np.zeros((K, 2), np.float16)
+    w[0, :] = 64.0
+    w[1:, 0] = 2.0 ** -24
+    s = op.exact_square_scores(w)
+    assert sum(s[0::2]) > sum(s[1::2])
+    acc = 0.0
+    for k in range(K):
+        acc += float(w[k, 0]) ** 2
+    assert acc == 4096.0                                          # the fp64 running sum lost them
+    m = op.tw(w, 1, n_cols_pruned=1, rows_kept_per_tile=K, exact=True)
+    assert m[:, 0].all() and not m[:, 1].any()
