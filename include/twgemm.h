@@ -140,6 +140,37 @@ tw_status tw_pack(const uint16_t* B_host, const uint8_t* mask_host,
                   int pattern, tw_handle_t* out);
 
 /*
+ * tw_prune_dev - one-shot pruning of a weight that lives on the device into a TW
+ * or TVW mask, also on the device (Algorithm 3, TW and TVW, with the sum of
+ * squares as importance score; the multi-stage schedule of Algorithm 1 and the
+ * Taylor score of Section IV need training data and are not part of this).
+ *   TW-C: the n_cols_pruned columns with the lowest scores are dropped.
+ *   TW-R: the kept columns are cut into tiles of G; in every tile the
+ *         rows_per_tile rows with the highest scores are kept.
+ *   TVW : in every tile, every run of 4 consecutive kept rows keeps per column
+ *         the 2 largest |w| (equal magnitudes: the lower position stays).
+ * Scores are exact integers (squares in units of 2^-48, 128-bit sums), ranked by
+ * (score, index): the result does not depend on summation order.
+ *   B_dev       K x N fp16 row-major, ldb >= N, finite values
+ *   mask_dev    K x N bytes, written 0/1;  tile_mask_dev  the TW-level mask, may be NULL
+ *   workspace_dev, workspace_bytes   scratch of at least tw_prune_workspace_bytes(K, N, G),
+ *               16-byte aligned, owned by the caller
+ * Only enqueues kernels on `stream`; allocates nothing.  Errors: TW_ERR_ARG,
+ * TW_ERR_UNSUPPORTED (TEW), TW_ERR_HIP.
+ */
+tw_status tw_prune_workspace_bytes(int K, int N, int G, size_t* bytes);
+tw_status tw_prune_dev(const void* B_dev, int K, int N, int ldb, int G, int pattern,
+                       int n_cols_pruned, int rows_per_tile, uint8_t* mask_dev,
+                       uint8_t* tile_mask_dev, void* workspace_dev, size_t workspace_bytes,
+                       void* stream);
+
+/* tw_pack_dev - tw_pack for a weight and masks in device memory: copies them to the
+ * host on `stream`, waits for the copies, packs and uploads. */
+tw_status tw_pack_dev(const void* B_dev, int ldb, const uint8_t* mask_dev,
+                      const uint8_t* tile_mask_dev, int K, int N, int G, int pattern,
+                      void* stream, tw_handle_t* out);
+
+/*
  * tw_concat - one handle for the weights parts[0..n) side by side along N:
  * B = [B_0 | B_1 | ...] (same K, G and pattern; N = sum of the members' N).
  * A tw_gemm on it computes the members' products from one read of A in one

@@ -1,6 +1,7 @@
 """Tile-wise / tile-vector-wise sparse GEMM for MI355X: thin Python binding
 over the C-ABI library libtwgemm.so (see include/twgemm.h)."""
 from .binding import (  # noqa: F401
-    TwError, PackedWeight, lib, lib_path, tw_pack, tw_pack_host, tw_concat, tw_gemm, tw_dense_gemm,
+    TwError, PackedWeight, lib, lib_path, tw_pack, tw_pack_host, tw_pack_dev, tw_prune_dev, tw_prune_workspace_bytes, tw_concat, tw_gemm,
+    tw_dense_gemm,
     tw_set_option, PATTERN_TW, PATTERN_TVW, PATTERN_TEW, LAYOUT_KM, LAYOUT_MK, EXPORTED_SYMBOLS,
 )

@@ -13,7 +13,8 @@ PATTERN_TW, PATTERN_TVW, PATTERN_TEW = 0, 1, 2
 LAYOUT_KM, LAYOUT_MK = 0, 1
 
 EXPORTED_SYMBOLS = [
-    "tw_pack_host", "tw_upload", "tw_pack", "tw_concat", "tw_gemm", "tw_dense_gemm", "tw_export",
+    "tw_pack_host", "tw_upload", "tw_pack", "tw_pack_dev", "tw_prune_dev",
+    "tw_prune_workspace_bytes", "tw_concat", "tw_gemm", "tw_dense_gemm", "tw_export",
     "tw_unpack", "tw_free", "tw_status_str", "tw_set_option", "tw_flop_counts",
 ]
 
@@ -62,6 +63,9 @@ def lib():
         L.tw_pack.argtypes = L.tw_pack_host.argtypes
         L.tw_upload.argtypes = [vp]
         L.tw_concat.argtypes = [C.POINTER(vp), i, i, C.POINTER(vp)]
+        L.tw_prune_workspace_bytes.argtypes = [i, i, i, C.POINTER(C.c_size_t)]
+        L.tw_prune_dev.argtypes = [vp, i, i, i, i, i, i, i, vp, vp, vp, C.c_size_t, vp]
+        L.tw_pack_dev.argtypes = [vp, i, vp, vp, i, i, i, i, vp, C.POINTER(vp)]
         L.tw_gemm.argtypes = [vp, i, i, i, vp, vp, i, vp]
         L.tw_dense_gemm.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, vp]
         L.tw_export.argtypes = [vp, C.POINTER(_View)]
@@ -193,6 +197,28 @@ def tw_pack_host(B16, mask, G, pattern, tile_mask=None) -> PackedWeight:
 
 def tw_pack(B16, mask, G, pattern, tile_mask=None) -> PackedWeight:
     return _pack("tw_pack", B16, mask, G, pattern, tile_mask)
+
+
+def tw_prune_workspace_bytes(K: int, N: int, G: int) -> int:
+    n = C.c_size_t()
+    _check(lib().tw_prune_workspace_bytes(K, N, G, C.byref(n)), "tw_prune_workspace_bytes")
+    return n.value
+
+
+def tw_prune_dev(B_ptr: int, K: int, N: int, ldb: int, G: int, pattern: int, n_cols_pruned: int,
+                 rows_per_tile: int, mask_ptr: int, tile_mask_ptr, workspace_ptr: int, workspace_bytes: int,
+                 stream: int = 0):
+    """Device addresses in, K x N byte masks out (device); see include/twgemm.h."""
+    _check(lib().tw_prune_dev(B_ptr, K, N, ldb, G, int(pattern), n_cols_pruned, rows_per_tile, mask_ptr,
+                              tile_mask_ptr, workspace_ptr, workspace_bytes, stream), "tw_prune_dev")
+
+
+def tw_pack_dev(B_ptr: int, ldb: int, mask_ptr: int, tile_mask_ptr, K: int, N: int, G: int, pattern: int,
+                stream: int = 0) -> PackedWeight:
+    h = C.c_void_p()
+    _check(lib().tw_pack_dev(B_ptr, ldb, mask_ptr, tile_mask_ptr, K, N, int(G), int(pattern), stream, C.byref(h)),
+           "tw_pack_dev")
+    return PackedWeight(h)
 
 
 def tw_concat(parts, upload: bool = True) -> PackedWeight:

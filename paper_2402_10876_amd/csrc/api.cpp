@@ -8,6 +8,7 @@
 
 #include "kernels.h"
 #include "packed.h"
+#include "prune.h"
 
 namespace {
 
@@ -136,6 +137,47 @@ tw_status tw_pack(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_ma
   st = tw_upload(*out);
   if (st != TW_OK) { tw_free(*out); *out = nullptr; }
   return st;
+}
+
+tw_status tw_prune_workspace_bytes(int K, int N, int G, size_t* bytes) {
+  if (!bytes || K < 1 || N < 1 || !valid_G(G)) return TW_ERR_ARG;
+  *bytes = twg::prune_workspace_bytes(K, N, G);
+  return TW_OK;
+}
+
+tw_status tw_prune_dev(const void* B_dev, int K, int N, int ldb, int G, int pattern, int n_cols_pruned,
+                       int rows_per_tile, uint8_t* mask_dev, uint8_t* tile_mask_dev, void* workspace_dev,
+                       size_t workspace_bytes, void* stream) {
+  if (!B_dev || !mask_dev || !workspace_dev || K < 1 || N < 1 || ldb < N || !valid_G(G)) return TW_ERR_ARG;
+  if (n_cols_pruned < 0 || n_cols_pruned > N || rows_per_tile < 0 || rows_per_tile > K) return TW_ERR_ARG;
+  if (pattern == TW_PATTERN_TEW) return TW_ERR_UNSUPPORTED;
+  if (pattern != TW_PATTERN_TW && pattern != TW_PATTERN_TVW) return TW_ERR_ARG;
+  if (((uintptr_t)workspace_dev & 15) || workspace_bytes < twg::prune_workspace_bytes(K, N, G)) return TW_ERR_ARG;
+  hipError_t e = twg::prune_device((const uint16_t*)B_dev, K, N, ldb, G, pattern == TW_PATTERN_TVW, n_cols_pruned,
+                                   rows_per_tile, mask_dev, tile_mask_dev, workspace_dev, (hipStream_t)stream);
+  return e == hipSuccess ? TW_OK : TW_ERR_HIP;
+}
+
+tw_status tw_pack_dev(const void* B_dev, int ldb, const uint8_t* mask_dev, const uint8_t* tile_mask_dev, int K,
+                      int N, int G, int pattern, void* stream, tw_handle_t* out) try {
+  if (!out) return TW_ERR_ARG;
+  *out = nullptr;
+  if (!B_dev || !mask_dev || K < 1 || N < 1 || ldb < N) return TW_ERR_ARG;
+  std::vector<uint16_t> B((size_t)K * N);
+  std::vector<uint8_t> mask((size_t)K * N), tmask(tile_mask_dev ? (size_t)K * N : 0);
+  hipStream_t s = (hipStream_t)stream;
+  if (hipMemcpy2DAsync(B.data(), (size_t)N * 2, B_dev, (size_t)ldb * 2, (size_t)N * 2, K, hipMemcpyDeviceToHost, s) !=
+          hipSuccess ||
+      hipMemcpyAsync(mask.data(), mask_dev, mask.size(), hipMemcpyDeviceToHost, s) != hipSuccess ||
+      (tile_mask_dev &&
+       hipMemcpyAsync(tmask.data(), tile_mask_dev, tmask.size(), hipMemcpyDeviceToHost, s) != hipSuccess) ||
+      hipStreamSynchronize(s) != hipSuccess) {
+    (void)hipGetLastError();
+    return TW_ERR_HIP;
+  }
+  return tw_pack(B.data(), mask.data(), tile_mask_dev ? tmask.data() : nullptr, K, N, G, pattern, out);
+} catch (const std::bad_alloc&) {
+  return TW_ERR_ALLOC;
 }
 
 tw_status tw_concat(const tw_handle_t* parts, int n, int upload, tw_handle_t* out) {

@@ -1,0 +1,187 @@
+// One-shot magnitude pruning of a device-resident weight into a TW / TVW mask
+// (Algorithm 3: TW-C on whole columns, Condense, TW-R on the (1,G) row pieces of
+// every tile of kept columns; TVW: then 2 of every 4 consecutive kept rows per
+// column, Algorithm 2's VW with vectors of 4 and 50 %).  The importance score
+// is the sum of squares (Section IV calls magnitude the most intuitive score;
+// the paper's Taylor score needs gradients).
+//
+// Scores are exact: an fp16 value is an integer multiple of 2^-24, its square
+// an integer multiple of 2^-48 below 2^80, and the sums are kept in 128-bit
+// integers, so the ranking does not depend on the order of summation and a
+// host implementation with big integers takes the same decisions.  Ranking is
+// by (score, index): the lowest n are pruned, equal scores lose the lower index
+// first.  This runs once per weight; the kernels are simple on purpose.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "prune.h"
+
+namespace twg {
+
+namespace {
+
+typedef unsigned __int128 u128;
+
+__device__ __forceinline__ uint64_t magnitude24(uint16_t h) {   // |value| in units of 2^-24
+  const uint32_t e = (h >> 10) & 31u, m = h & 1023u;
+  return e == 0 ? (uint64_t)m : (uint64_t)(m | 1024u) << (e - 1);
+}
+__device__ __forceinline__ u128 square48(uint16_t h) {
+  const uint64_t a = magnitude24(h);
+  return (u128)a * (u128)a;
+}
+__device__ __forceinline__ bool before(u128 sa, int ia, u128 sb, int ib) {   // (score, index) order
+  return sa < sb || (sa == sb && ia < ib);
+}
+
+// TW-C scores: one thread per column, rows in order (coalesced across the threads).
+__global__ void column_scores(const uint16_t* B, int K, int N, int ldb, u128* score) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N) return;
+  u128 s = 0;
+  for (int k = 0; k < K; ++k) s += square48(B[(size_t)k * ldb + n]);
+  score[n] = s;
+}
+
+// keep[i] = 1 unless i is among the `n_pruned` lowest of its segment by (score, index).
+// grid.y = segment (one for the columns, one per tile for the rows), segment length `len`.
+__global__ void keep_all_but_lowest(const u128* score, int len, int n_pruned, int32_t* keep) {
+  const u128* s = score + (size_t)blockIdx.y * len;
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= len) return;
+  const u128 mine = s[i];
+  int rank = 0;
+  for (int j = 0; j < len; ++j) rank += before(s[j], j, mine, i);
+  keep[(size_t)blockIdx.y * len + i] = rank >= n_pruned;
+}
+
+// Condense: positions of the kept entries of each segment, in ascending order.
+// One workgroup per segment; pos[i] = index among the kept (or -1), list[pos] = i.
+__global__ void compact(const int32_t* keep, int len, int32_t* pos, int32_t* list) {
+  __shared__ int part[1024];
+  __shared__ int base;
+  const int32_t* kp = keep + (size_t)blockIdx.x * len;
+  int32_t* ps = pos + (size_t)blockIdx.x * len;
+  int32_t* ls = list + (size_t)blockIdx.x * len;
+  if (threadIdx.x == 0) base = 0;
+  __syncthreads();
+  for (int c0 = 0; c0 < len; c0 += (int)blockDim.x) {
+    const int i = c0 + threadIdx.x;
+    const int v = i < len ? kp[i] : 0;
+    part[threadIdx.x] = v;
+    __syncthreads();
+    for (int d = 1; d < (int)blockDim.x; d <<= 1) {          // inclusive scan
+      const int add = (int)threadIdx.x >= d ? part[threadIdx.x - d] : 0;
+      __syncthreads();
+      part[threadIdx.x] += add;
+      __syncthreads();
+    }
+    if (i < len) {
+      const int p = base + part[threadIdx.x] - v;
+      ps[i] = v ? p : -1;
+      if (v) ls[p] = i;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) base += part[blockDim.x - 1];
+    __syncthreads();
+  }
+}
+
+// TW-R scores: tile t = kept columns [t*G, min((t+1)*G, n_kept)); one thread per (tile, row).
+__global__ void tile_row_scores(const uint16_t* B, int K, int ldb, int G, int n_kept,
+                                const int32_t* kept_cols, u128* score) {
+  const int t = blockIdx.y, k = blockIdx.x * blockDim.x + threadIdx.x;
+  if (k >= K) return;
+  const int c0 = t * G, c1 = min(c0 + G, n_kept);
+  u128 s = 0;
+  for (int c = c0; c < c1; ++c) s += square48(B[(size_t)k * ldb + kept_cols[c]]);
+  score[(size_t)t * K + k] = s;
+}
+
+// tile_mask[k][n] = column n kept and row k kept in n's tile; `mask` (TVW) starts as zeros.
+__global__ void emit_tile_mask(int K, int N, int G, const int32_t* col_pos, const int32_t* row_keep,
+                               uint8_t* tile_mask, uint8_t* zeroed) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= (size_t)K * N) return;
+  const int k = (int)(i / N), n = (int)(i % N);
+  const int p = col_pos[n];
+  const uint8_t v = p >= 0 && row_keep[(size_t)(p / G) * K + k];
+  if (tile_mask) tile_mask[i] = v;
+  if (zeroed) zeroed[i] = 0;
+}
+
+// 2:4 along the condensed kept rows of a tile: in every group of 4 consecutive kept rows
+// and every column keep the 2 largest |w|; equal magnitudes: the lower position stays.
+__global__ void two_of_four(const uint16_t* B, int K, int N, int ldb, int G, int n_kept, int rows_kept,
+                            const int32_t* kept_cols, const int32_t* row_list, uint8_t* mask) {
+  const int t = blockIdx.z, g = blockIdx.y, c = t * G + blockIdx.x * blockDim.x + threadIdx.x;
+  if (c >= min((t + 1) * G, n_kept) || (int)(blockIdx.x * blockDim.x + threadIdx.x) >= G) return;
+  const int n = kept_cols[c];
+  const int32_t* rows = row_list + (size_t)t * K + 4 * g;
+  const int cnt = min(4, rows_kept - 4 * g);
+  uint64_t mag[4];
+  for (int p = 0; p < cnt; ++p) mag[p] = magnitude24(B[(size_t)rows[p] * ldb + n]);
+  for (int p = 0; p < cnt; ++p) {
+    int larger = 0;     // positions that come first: larger magnitude, or equal and lower
+    for (int q = 0; q < cnt; ++q) larger += q != p && (mag[q] > mag[p] || (mag[q] == mag[p] && q < p));
+    if (larger < 2) mask[(size_t)rows[p] * N + n] = 1;
+  }
+}
+
+size_t align_up(size_t x) { return (x + 255) / 256 * 256; }
+
+}  // namespace
+
+size_t prune_workspace_bytes(int K, int N, int G) {
+  const size_t nt = (size_t)(N + G - 1) / G;
+  return align_up((size_t)N * 16) + 3 * align_up((size_t)N * 4) +          // column score, keep, pos, list
+         align_up(nt * K * 16) + 3 * align_up(nt * K * 4);                  // row score, keep, pos, list
+}
+
+hipError_t prune_device(const uint16_t* B, int K, int N, int ldb, int G, bool tvw, int n_cols_pruned,
+                        int rows_per_tile, uint8_t* mask, uint8_t* tile_mask, void* workspace,
+                        hipStream_t stream) {
+  const int n_kept = N - n_cols_pruned;
+  const int nt = (n_kept + G - 1) / G;
+  char* w = (char*)workspace;
+  const size_t ntmax = (size_t)(N + G - 1) / G;
+  u128* col_score = (u128*)w;            w += align_up((size_t)N * 16);
+  int32_t* col_keep = (int32_t*)w;       w += align_up((size_t)N * 4);
+  int32_t* col_pos = (int32_t*)w;        w += align_up((size_t)N * 4);
+  int32_t* kept_cols = (int32_t*)w;      w += align_up((size_t)N * 4);
+  u128* row_score = (u128*)w;            w += align_up(ntmax * K * 16);
+  int32_t* row_keep = (int32_t*)w;       w += align_up(ntmax * K * 4);
+  int32_t* row_pos = (int32_t*)w;        w += align_up(ntmax * K * 4);
+  int32_t* row_list = (int32_t*)w;
+  const int T = 256;
+  hipLaunchKernelGGL(column_scores, dim3((N + T - 1) / T), dim3(T), 0, stream, B, K, N, ldb, col_score);
+  hipLaunchKernelGGL(keep_all_but_lowest, dim3((N + T - 1) / T, 1), dim3(T), 0, stream, col_score, N,
+                     n_cols_pruned, col_keep);
+  hipLaunchKernelGGL(compact, dim3(1), dim3(1024), 0, stream, col_keep, N, col_pos, kept_cols);
+  if (nt > 0) {
+    hipLaunchKernelGGL(tile_row_scores, dim3((K + T - 1) / T, nt), dim3(T), 0, stream, B, K, ldb, G, n_kept,
+                       kept_cols, row_score);
+    hipLaunchKernelGGL(keep_all_but_lowest, dim3((K + T - 1) / T, nt), dim3(T), 0, stream, row_score, K,
+                       K - rows_per_tile, row_keep);
+  }
+  const size_t total = (size_t)K * N;
+  const unsigned eb = (unsigned)((total + T - 1) / T);
+  if (tvw) {      // tile mask (if asked for) and an all-zero element mask for the 2:4 step to fill
+    hipLaunchKernelGGL(emit_tile_mask, dim3(eb), dim3(T), 0, stream, K, N, G, col_pos, row_keep, tile_mask, mask);
+  } else {        // TW: the element mask is the tile mask
+    hipLaunchKernelGGL(emit_tile_mask, dim3(eb), dim3(T), 0, stream, K, N, G, col_pos, row_keep, mask,
+                       (uint8_t*)nullptr);
+    if (tile_mask)
+      hipLaunchKernelGGL(emit_tile_mask, dim3(eb), dim3(T), 0, stream, K, N, G, col_pos, row_keep, tile_mask,
+                         (uint8_t*)nullptr);
+  }
+  if (tvw && nt > 0 && rows_per_tile > 0) {
+    hipLaunchKernelGGL(compact, dim3(nt), dim3(1024), 0, stream, row_keep, K, row_pos, row_list);
+    const int groups = (rows_per_tile + 3) / 4;
+    hipLaunchKernelGGL(two_of_four, dim3((G + 63) / 64, groups, nt), dim3(64), 0, stream, B, K, N, ldb, G, n_kept,
+                       rows_per_tile, kept_cols, row_list, mask);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace twg
