@@ -40,10 +40,20 @@ int pick_tile_m(int M, int n_tiles, int G, int max_k) {
   return G == 32 ? 128 : 64;
 }
 
-// TVW: 128-row tiles.  The 256-row instance (8 waves) measured within 3 % of it on
-// every configured shape (slower on most), so it is only used when asked for.
-int pick_tile_m_tvw(int G) {
-  return (G == 128 && opt_tile_m.load() == 256) ? 256 : 128;
+// TVW tiles are 128 rows high, two workgroups per CU (76 KB of LDS each).  64-row tiles
+// (three per CU) win where 128-row tiles would leave CUs idle or end in a thin last
+// round: at most one workgroup per CU, or a remainder of at most half a round of 512.
+// Measured on the configured shapes: 3-13 % on the BERT-base ones, while large grids and
+// long K loops (the weight tile is re-read per workgroup) keep 128.  The 256-row instance
+// (8 waves) is within 3 % of the 128-row one everywhere and only used when asked for.
+int pick_tile_m_tvw(int G, int M, int n_tiles) {
+  const int forced = opt_tile_m.load();
+  if (G != 128) return 128;
+  if (forced == 64 || forced == 128 || forced == 256) return forced;
+  const long wgs128 = (long)((M + 127) / 128) * n_tiles;
+  if (wgs128 <= 256) return 64;
+  const long tail = wgs128 % 512;
+  return (wgs128 <= 1536 && tail != 0 && tail <= 256) ? 64 : 128;
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -227,7 +237,7 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
     return e == hipSuccess ? TW_OK : TW_ERR_HIP;
   }
   if (h->pattern == TW_PATTERN_TVW) {
-    const int tvw_tm = pick_tile_m_tvw(h->G);
+    const int tvw_tm = pick_tile_m_tvw(h->G, M, h->n_tiles > 0 ? h->n_tiles : 1);
     hipError_t e = twg::launch_tvw_km(h->G, tvw_tm, opt_depth.load(), g, (hipStream_t)stream);
     if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
     return e == hipSuccess ? TW_OK : TW_ERR_HIP;

@@ -333,6 +333,8 @@ hipError_t launch_tvw_km(int G, int tm, int depth, GemmArgs g, hipStream_t strea
   if (G == 128 && tm == 128 && depth == 3) return launch<128, 128, 2, 3>(g, stream);
   if (G == 128 && tm == 128 && depth == 4) return launch<128, 128, 2, 4>(g, stream);
   if (G == 128 && tm == 256) return launch<256, 128, 2, 3, 8>(g, stream);   // 8 waves, 64 x 64 per wave
+  if (G == 128 && tm == 64 && depth == 3) return launch<64, 128, 2, 3>(g, stream);   // 64 x 32 per wave
+  if (G == 128 && tm == 64 && depth == 4) return launch<64, 128, 2, 4>(g, stream);
   if (G == 64 && tm == 128 && depth == 3) return launch<128, 64, 1, 3>(g, stream);
   if (G == 64 && tm == 128 && depth == 4) return launch<128, 64, 1, 4>(g, stream);
   return hipErrorInvalidValue;

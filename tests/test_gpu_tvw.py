@@ -66,16 +66,17 @@ def test_all_ones_counts_kept_elements():
     assert np.array_equal(C, np.broadcast_to(mask.sum(0).astype(np.float64), (M, N)))
 
 
+@pytest.mark.parametrize("tile_m", [256, 64])
 @pytest.mark.parametrize("M", [8, 300, 520])
-def test_256_row_tiles_eight_waves(M):
-    """The 256 x 128 instance (8 waves): identity A pins the layout bit for bit,
-    random A goes against the oracle; M below, across and beyond one tile."""
+def test_other_tile_heights(M, tile_m):
+    """The 256 x 128 (8 waves) and 64 x 128 instances: identity A pins the layout bit for
+    bit, random A goes against the oracle; M below, across and beyond one tile."""
     rng = np.random.default_rng(40 + M)
     K, N, G = 330, 300, 128
     mask, tm = random_tvw_mask(rng, K, N, G, full=(M != 300))
     B = wl.make_B(40, K, N, 1.0)
-    tw.tw_set_option("tile_m", 256)
-    print(f"case tvw 256-row tiles M={M}", flush=True)
+    tw.tw_set_option("tile_m", tile_m)
+    print(f"case tvw {tile_m}-row tiles M={M}", flush=True)
     A = wl.make_A(M, M, K)
     C, raw = _run(A, B, mask, tm, G, fill=3.0, ldc=(M + 7) // 8 * 8 + 8)
     assert_C_close(C, og.gemm_oracle(A, B, mask), og.abs_bound(A, B, mask))
@@ -86,7 +87,7 @@ def test_256_row_tiles_eight_waves(M):
     assert np.array_equal(raw[:, :K].T.view(np.uint16), want.view(np.uint16))
     tw.tw_set_option("tile_m", 128)
     _, raw128 = _run(A, B, mask, tm, G)
-    tw.tw_set_option("tile_m", 256)
+    tw.tw_set_option("tile_m", tile_m)
     _, raw256 = _run(A, B, mask, tm, G)
     assert np.array_equal(raw128[:, :M].view(np.uint16), raw256[:, :M].view(np.uint16))
 
