@@ -45,7 +45,7 @@ PLAN = [(0, 4), (1, 1), (2, 1)]          # (shape index in the config, copies pe
 # what the same counters read for a plain 256 MiB device copy.  A measurement that
 # cannot be taken from inside this script: None where no such run has been made.
 MEASURED_TRAFFIC_BYTES = {("tw", False): None, ("tvw", False): None,
-                          ("tw", True): 32.47e6, ("tvw", True): 29.48e6}   # key: (pattern, Q/K/V grouped)
+                          ("tw", True): 32.47e6, ("tvw", True): 29.45e6}   # key: (pattern, Q/K/V grouped)
 
 
 def algorithmic_bytes(M, K_union, N, pattern, sum_kw, sum_k):
