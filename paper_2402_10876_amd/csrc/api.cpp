@@ -226,6 +226,7 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
   g.zero_cols = h->img.d_zero_cols; g.n_zero = (int)h->img.zero_cols.size();
   g.meta = h->img.d_meta;
   g.ew_ptr = h->img.d_ew_ptr; g.ew_pairs = h->img.d_ew_pairs;
+  g.ew_last = h->img.ew_pairs.empty() ? 0 : (int)h->img.ew_pairs.size() - 1;
   g.n_tiles = h->n_tiles; g.K = h->K; g.N = h->N; g.xcd_map = opt_xcd_map.load();
 #ifdef TWG_TRACE
   static int trace_launch = 0;

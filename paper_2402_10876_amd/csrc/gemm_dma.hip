@@ -90,32 +90,57 @@ __device__ __forceinline__ void wait_vm() {
 // TW part).  Here it is added to the fp32 sums of the thread that stores the 8 values
 // C^T[col][m .. m+8): for every restored (k, v) of the column, s += v * A^T[k][m .. m+8).
 // Pairs travel as k << 16 | fp16 bits; the list is padded in registers with
-// (row 0, +0), which adds nothing.  A rows are lda >= round-up-8(M) halves long, so the
+// (row 0, +0), which adds nothing.  Every load is unconditional (index clamped to the
+// list, value selected afterwards): a load under a branch would be waited for on its own.  A rows are lda >= round-up-8(M) halves long, so the
 // 16-byte read at m < M stays inside the row; lanes at or past M are not stored.
-__device__ __forceinline__ void ew_accumulate(const GemmArgs& g, int lo, int hi, const _Float16* A_m,
-                                              float (&s)[8]) {
-  constexpr int U = 8;     // elements per round trip; the next U pairs are fetched while these U rows arrive
-  uint32_t nx[U];
+template <int P>      // P columns at a time: P times the loads in flight per round trip
+__device__ __forceinline__ void ew_accumulate(const GemmArgs& g, const int (&lo)[P], const int (&hi)[P],
+                                              const _Float16* A_m, float (&s)[P][8]) {
+  constexpr int U = 8 / P;     // elements per column and round trip; the next ones are fetched meanwhile
+  int e[P];
+  uint32_t nx[P][U];
+  bool more = false;
 #pragma unroll
-  for (int u = 0; u < U; ++u) nx[u] = lo + u < hi ? g.ew_pairs[lo + u] : 0u;
-  for (int e = lo; e < hi; e += U) {
-    uint32_t pr[U];
-    half8 a[U];
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      pr[u] = nx[u];
-      a[u] = *(const half8*)(A_m + (size_t)(pr[u] >> 16) * g.lda);
-    }
-#pragma unroll
-    for (int u = 0; u < U; ++u) nx[u] = e + U + u < hi ? g.ew_pairs[e + U + u] : 0u;
+  for (int p = 0; p < P; ++p) {
+    e[p] = lo[p];
+    more |= lo[p] < hi[p];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      union { uint16_t b; _Float16 h; } cv;
-      cv.b = (uint16_t)(pr[u] & 0xffffu);
-      const float v = (float)cv.h;
-#pragma unroll
-      for (int q = 0; q < 8; ++q) s[q] = __builtin_fmaf(v, (float)a[u][q], s[q]);
+      const uint32_t w = g.ew_pairs[min(lo[p] + u, g.ew_last)];
+      nx[p][u] = lo[p] + u < hi[p] ? w : 0u;
     }
+  }
+  while (more) {
+    uint32_t pr[P][U];
+    half8 a[P][U];
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        pr[p][u] = nx[p][u];
+        a[p][u] = *(const half8*)(A_m + (size_t)(pr[p][u] >> 16) * g.lda);
+      }
+    more = false;
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+      e[p] += U;
+      more |= e[p] < hi[p];
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        const uint32_t w = g.ew_pairs[min(e[p] + u, g.ew_last)];
+        nx[p][u] = e[p] + u < hi[p] ? w : 0u;
+      }
+    }
+#pragma unroll
+    for (int p = 0; p < P; ++p)
+#pragma unroll
+      for (int u = 0; u < U; ++u) {
+        union { uint16_t b; _Float16 h; } cv;
+        cv.b = (uint16_t)(pr[p][u] & 0xffffu);
+        const float v = (float)cv.h;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) s[p][q] = __builtin_fmaf(v, (float)a[p][u][q], s[p][q]);
+      }
   }
 }
 
@@ -131,16 +156,24 @@ __device__ __forceinline__ void store_row_chunk(const GemmArgs& g, _Float16* dst
 __device__ __forceinline__ void ew_fill_column(const GemmArgs& g, int which) {
   const int col = g.zero_cols[which];
   const int lo = g.ew_ptr[col], hi = g.ew_ptr[col + 1];
+  if (lo == hi) {                        // the usual case (uniform over the workgroup)
+    zero_fill_column(g, which);
+    return;
+  }
   _Float16* row = g.C + (size_t)col * g.ldc;
   for (int m = threadIdx.x * 8; m < g.M; m += (int)blockDim.x * 8) {
-    float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    ew_accumulate(g, lo, hi, g.A + m, s);
-    store_row_chunk(g, row + m, m, s);
+    float s[1][8] = {{0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f}};
+    const int lo1[1] = {lo}, hi1[1] = {hi};
+    ew_accumulate<1>(g, lo1, hi1, g.A + m, s);
+    store_row_chunk(g, row + m, m, s[0]);
   }
 }
 
 template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KSPLIT = 1, bool EW = false>
-__global__ __launch_bounds__(NWAVES * 64) void tw_gemm_km_dma_kernel(GemmArgs g) {
+// (the TEW epilogue must not cost the 128 x 128 instance its third wave per SIMD: the second
+// launch-bound asks the compiler to keep the register count within that occupancy)
+__global__ __launch_bounds__(NWAVES * 64, (EW && TM <= 128 && TN <= 128 && NWAVES == 4) ? 3 : 1)
+void tw_gemm_km_dma_kernel(GemmArgs g) {
   constexpr int NT = NWAVES * 64;          // threads of the workgroup
   constexpr int WPG = NWAVES / KSPLIT;     // waves per group
   constexpr int KSS = KS * KSPLIT;         // condensed rows per pipeline stage
@@ -162,7 +195,7 @@ __global__ __launch_bounds__(NWAVES * 64) void tw_gemm_km_dma_kernel(GemmArgs g)
   // tile is staged in fp32 so that their products join the sum before the one rounding
   constexpr int CS = EW ? (TM + 4) * 4 : (TM + 4) * 2;
   static_assert(!(EW && DENSE), "");
-  constexpr int PIPE_BYTES = D * STAGE, EPI_BYTES = TN * CS;
+  constexpr int PIPE_BYTES = D * STAGE, EPI_BYTES = (EW ? TN / 2 : TN) * CS;   // EW stages half a tile at a time
   constexpr int RED_BYTES = KSPLIT > 1 ? TM * TN * 4 : 0;      // partial accumulators of group 1
   static_assert(RED_BYTES <= PIPE_BYTES, "the reduction reuses the pipeline buffers");
   constexpr int LDS_BYTES = PIPE_BYTES > EPI_BYTES ? PIPE_BYTES : EPI_BYTES;
@@ -204,16 +237,6 @@ __global__ __launch_bounds__(NWAVES * 64) void tw_gemm_km_dma_kernel(GemmArgs g)
     if constexpr (DENSE) { cols[i] = t * TN + n; if (cols[i] >= g.N) cols[i] = -1; }
     else cols[i] = g.col_idx[t * TN + n];
   }
-  // restored elements of those columns (TEW): [ew_lo, ew_hi) in the pair list
-  int ew_lo[EW ? NPASS : 1], ew_hi[EW ? NPASS : 1];
-  if constexpr (EW) {
-#pragma unroll
-    for (int i = 0; i < NPASS; ++i) {
-      ew_lo[i] = cols[i] >= 0 ? g.ew_ptr[cols[i]] : 0;
-      ew_hi[i] = cols[i] >= 0 ? g.ew_ptr[cols[i] + 1] : 0;
-    }
-  }
-
   // ---- geometry of the asynchronous copies --------------------------------
   // Copy instruction j of this wave fills LDS bytes [(wave*NI + j) KiB, +1 KiB)
   // of the stage; lane l owns the 16 bytes at l*16, i.e. tile row
@@ -419,47 +442,76 @@ __global__ __launch_bounds__(NWAVES * 64) void tw_gemm_km_dma_kernel(GemmArgs g)
     __syncthreads();
   }
   if constexpr (EW) {
-    // fp32 staging, then every thread finishes its (column, 8 x m) pieces: restored
-    // elements added, one rounding, streaming store
-    if (grp == 0) {
-#pragma unroll
-      for (int i = 0; i < MB; ++i)
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-          const int n = wn * WN + j * 32 + (lane & 31);
-#pragma unroll
-          for (int rq = 0; rq < 4; ++rq) {
-            const int mm = wm * WM + i * 32 + 8 * rq + 4 * (lane >> 5);
-            floatx4 v;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) v[r] = acc[i][j][rq * 4 + r];
-            *(floatx4*)(lds + n * CS + mm * 4) = v;
-          }
-        }
-    }
-    __syncthreads();
+    // Restored elements of this thread's columns: [ew_lo, ew_hi) in the pair list.  Loaded here,
+    // not at kernel start, where the dependent loads would hold up the first copies.
+    int ew_lo[NPASS], ew_hi[NPASS];
 #pragma unroll
     for (int i = 0; i < NPASS; ++i) {
-      if (dst_off[i] < 0) continue;
-      const int n = r0 + i * ROWS_PER_PASS;
-      const floatx4 lo4 = *(const floatx4*)(lds + n * CS + c * 32);
-      const floatx4 hi4 = *(const floatx4*)(lds + n * CS + c * 32 + 16);
-      float sum[8] = {lo4[0], lo4[1], lo4[2], lo4[3], hi4[0], hi4[1], hi4[2], hi4[3]};
-      ew_accumulate(g, ew_lo[i], ew_hi[i], g.A + m, sum);
-      store_row_chunk(g, g.C + dst_off[i], m, sum);
+      const int col = cols[i] < 0 ? 0 : cols[i];          // unconditional loads, selected afterwards
+      const int p0 = g.ew_ptr[col], p1 = g.ew_ptr[col + 1];
+      const bool live = dst_off[i] >= 0;
+      ew_lo[i] = live ? p0 : 0;
+      ew_hi[i] = live ? p1 : 0;
+    }
+    // fp32 staging, half of the tile's columns at a time (the staging area then fits the
+    // pipeline buffers and does not cost occupancy); every thread finishes its
+    // (column, 8 x m) pieces: restored elements added, one rounding, streaming store
+    static_assert(NPASS % 2 == 0 && (TN / 2) % 32 == 0, "");
+    constexpr int P = (NPASS / 2) % 2 == 0 ? 2 : 1;      // columns finished together
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      if (h) __syncthreads();
+      if (grp == 0) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+          for (int j = 0; j < NB; ++j) {
+            const int nblk = wn * WN + j * 32;                 // wave-uniform
+            if (nblk / (TN / 2) != h) continue;
+            const int n = nblk - h * (TN / 2) + (lane & 31);
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+              const int mm = wm * WM + i * 32 + 8 * rq + 4 * (lane >> 5);
+              floatx4 v;
+#pragma unroll
+              for (int r = 0; r < 4; ++r) v[r] = acc[i][j][rq * 4 + r];
+              *(floatx4*)(lds + n * CS + mm * 4) = v;
+            }
+          }
+      }
+      __syncthreads();
+#pragma unroll
+      for (int i = h * (NPASS / 2); i < (h + 1) * (NPASS / 2); i += P) {
+        float sum[P][8];
+        int lo2[P], hi2[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+          const int n = r0 + (i + p) * ROWS_PER_PASS - h * (TN / 2);
+          const floatx4 lo4 = *(const floatx4*)(lds + n * CS + c * 32);
+          const floatx4 hi4 = *(const floatx4*)(lds + n * CS + c * 32 + 16);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) { sum[p][q] = lo4[q]; sum[p][4 + q] = hi4[q]; }
+          lo2[p] = ew_lo[i + p];
+          hi2[p] = ew_hi[i + p];
+        }
+        ew_accumulate<P>(g, lo2, hi2, g.A + (m < g.M ? m : 0), sum);
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+          if (dst_off[i + p] >= 0) store_row_chunk(g, g.C + dst_off[i + p], m, sum[p]);
+      }
     }
   } else {
     if (grp == 0) {
-  #pragma unroll
+#pragma unroll
       for (int i = 0; i < MB; ++i)
-  #pragma unroll
+#pragma unroll
         for (int j = 0; j < NB; ++j) {
           const int n = wn * WN + j * 32 + (lane & 31);
-  #pragma unroll
+#pragma unroll
           for (int rq = 0; rq < 4; ++rq) {
             const int mm = wm * WM + i * 32 + 8 * rq + 4 * (lane >> 5);
             half4 v;
-  #pragma unroll
+#pragma unroll
             for (int r = 0; r < 4; ++r) v[r] = (_Float16)acc[i][j][rq * 4 + r];
             *(half4*)(lds + n * CS + mm * 2) = v;
           }
@@ -472,13 +524,13 @@ __global__ __launch_bounds__(NWAVES * 64) void tw_gemm_km_dma_kernel(GemmArgs g)
     // from lingering dirty in L2 until the end-of-kernel write-back
     union Chunk { uint2 h[2]; u32x4 v; };   // staging rows are 8-byte aligned only
     Chunk ck[NPASS];
-  #pragma unroll
+#pragma unroll
     for (int i = 0; i < NPASS; ++i) {
       const int n = r0 + i * ROWS_PER_PASS;
       ck[i].h[0] = *(const uint2*)(lds + n * CS + c * 16);
       ck[i].h[1] = *(const uint2*)(lds + n * CS + c * 16 + 8);
     }
-  #pragma unroll
+#pragma unroll
     for (int i = 0; i < NPASS; ++i) {
       if (dst_off[i] < 0) continue;
       _Float16* dst = g.C + dst_off[i];

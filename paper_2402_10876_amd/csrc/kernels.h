@@ -20,7 +20,8 @@ struct GemmArgs {
   const int32_t* zero_cols;      // pruned columns of C, written as +0
   const uint32_t* meta;          // TVW: 2:4 position words
   const int32_t* ew_ptr;         // TEW: N+1 offsets into ew_pairs by original column of C
-  const uint32_t* ew_pairs;      // TEW: restored elements, K row << 16 | fp16 bits
+  const uint32_t* ew_pairs;      // TEW: restored elements, K row << 16 | fp16 bits (at least one readable word)
+  int ew_last;                   // TEW: index of the last pair (0 when there is none)
   int n_zero;
   int n_tiles, n_mtiles;
   int K, N;                      // dense only
