@@ -51,3 +51,36 @@ def gemm_bruteforce(A16: np.ndarray, B16: np.ndarray, mask: np.ndarray) -> np.nd
         for i in range(M):
             C[i, n] = math.fsum(a[i][k] * b[k][n] for k in kept)
     return C
+
+
+# ---------------------------------------------------------------------------
+# 8-bit integer variant.  The paper treats quantisation as orthogonal to its
+# sparsity (Section II-B; Section VI-B "Int8 Quantization" runs the tensor cores
+# in Int8): the product is the same definition over integers, and it is exact.
+# ---------------------------------------------------------------------------
+def gemm_i8_oracle(A8: np.ndarray, B8: np.ndarray, mask: np.ndarray) -> np.ndarray:
+    """C = A . (B (.) mask) for int8 A (M x K) and B (K x N), exact, int64."""
+    if A8.dtype != np.int8 or B8.dtype != np.int8 or B8.shape != mask.shape:
+        raise ValueError("int8 A and B, mask of B's shape")
+    return A8.astype(np.int64) @ (B8.astype(np.int64) * (mask != 0))
+
+
+def gemm_i8_bruteforce(A8: np.ndarray, B8: np.ndarray, mask: np.ndarray) -> np.ndarray:
+    """The same with Python integers, element by element, over the kept elements only."""
+    M, K = A8.shape
+    N = B8.shape[1]
+    a, b = A8.tolist(), B8.tolist()
+    C = np.zeros((M, N), dtype=np.int64)
+    for n in range(N):
+        kept = [k for k in range(K) if mask[k, n]]
+        for i in range(M):
+            C[i, n] = sum(a[i][k] * b[k][n] for k in kept)
+    return C
+
+
+def requantize_i8(acc: np.ndarray, scale: float) -> np.ndarray:
+    """int32 sums -> int8: the sum converted to fp32 (round to nearest even), times the fp32
+    scale (one fp32 rounding), rounded to the nearest integer (halves to even), clamped to
+    [-128, 127].  Every step has one IEEE-defined result, so this is bit-exact to follow."""
+    x = acc.astype(np.int32).astype(np.float32) * np.float32(scale)
+    return np.clip(np.rint(x), -128, 127).astype(np.int8)

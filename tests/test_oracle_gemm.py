@@ -118,3 +118,45 @@ def test_planted_mistakes_are_caught():
     wrong_nomask = A.astype(np.float64) @ B.astype(np.float64)
     for w in (wrong_T, wrong_mask_T, wrong_nomask):
         assert np.abs(w - ref).max() > 1e-3
+
+
+# ---- int8 variant -------------------------------------------------------------------------------
+def test_i8_oracle_equals_bruteforce_and_dense():
+    rng = np.random.default_rng(0)
+    A = rng.integers(-128, 128, (5, 9), dtype=np.int8)
+    B = rng.integers(-128, 128, (9, 7), dtype=np.int8)
+    mask = (rng.random((9, 7)) < 0.6).astype(np.uint8)
+    C = og.gemm_i8_oracle(A, B, mask)
+    assert C.dtype == np.int64 and np.array_equal(C, og.gemm_i8_bruteforce(A, B, mask))
+    ones = np.ones_like(mask)
+    assert np.array_equal(og.gemm_i8_oracle(A, B, ones), A.astype(np.int64) @ B.astype(np.int64))
+    # extreme values do not wrap: (-128) * (-128) * 9
+    A[:] = -128; B[:] = -128
+    assert (og.gemm_i8_oracle(A, B, ones) == 9 * 16384).all()
+    # pruned columns are zero, pruned rows do not matter, disjoint masks add up
+    m1 = mask.copy(); m1[:, 2] = 0
+    assert not og.gemm_i8_oracle(A, B, m1)[:, 2].any()
+    m2 = (1 - mask).astype(np.uint8)
+    assert np.array_equal(og.gemm_i8_oracle(A, B, mask) + og.gemm_i8_oracle(A, B, m2), og.gemm_i8_oracle(A, B, ones))
+
+
+def test_i8_planted_mistakes_fail():
+    rng = np.random.default_rng(1)
+    A = rng.integers(-128, 128, (6, 6), dtype=np.int8)
+    B = rng.integers(-128, 128, (6, 6), dtype=np.int8)
+    mask = (rng.random((6, 6)) < 0.5).astype(np.uint8)
+    C = og.gemm_i8_oracle(A, B, mask)
+    assert not np.array_equal(C, og.gemm_i8_oracle(A.T.copy(), B, mask))
+    assert not np.array_equal(C, og.gemm_i8_oracle(A, B, mask.T.copy()))
+    assert not np.array_equal(C, A.astype(np.int64) @ B.astype(np.int64))
+    assert not np.array_equal(C, (A.view(np.uint8).astype(np.int64)) @ (B.astype(np.int64) * mask))   # sign dropped
+
+
+def test_requantize_rule():
+    acc = np.array([0, 1, 2, 3, -1, -3, 5, 7, 1000, -1000, 2 ** 24 + 1, 254, 255, -256, -257], np.int64)
+    q = og.requantize_i8(acc, 0.5)
+    #            0  .5->0  1  1.5->2  -.5->-0  -1.5->-2  2.5->2  3.5->4  clamp  clamp  clamp  127  127.5->128->127  -128  -128.5->-128
+    assert q.tolist() == [0, 0, 1, 2, 0, -2, 2, 4, 127, -128, 127, 127, 127, -128, -128]
+    # int32 -> fp32 is itself rounded (to even): 2^24 + 1 becomes 2^24
+    assert og.requantize_i8(np.array([2 ** 24 + 1]), 2.0 ** -18).tolist() == [64]
+    assert og.requantize_i8(np.array([3]), np.float32(1 / 3)).tolist() == [1]
