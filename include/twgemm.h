@@ -57,6 +57,9 @@ typedef enum {
 
 typedef enum { TW_PATTERN_TW = 0, TW_PATTERN_TVW = 1, TW_PATTERN_TEW = 2 } tw_pattern;
 
+/* Element type of a packed weight (and of the A it multiplies). */
+typedef enum { TW_DTYPE_F16 = 0, TW_DTYPE_I8 = 1 } tw_dtype;
+
 /*
  * Memory layout of A and C.  Section V ("Memory Accesses Coalesce") stores the
  * tiles transposed so that skipping a K-column of A / an N-column of C becomes
@@ -109,6 +112,8 @@ typedef struct {
   const int32_t* ew_col_ptr;   /* NULL unless TEW */
   const int32_t* ew_row;
   const uint16_t* ew_val;
+  int32_t dtype;               /* TW_DTYPE_I8: every entry of `values` is an int8 value,
+                                  sign-extended to 16 bits; offsets count elements */
 } tw_packed_view;
 
 /*
@@ -207,6 +212,41 @@ tw_status tw_gemm(const void* A_dev, int M, int lda, int layout, tw_handle_t h,
 tw_status tw_dense_gemm(const void* A_dev, const void* B_dev, void* C_dev,
                         int M, int K, int N, int lda, int ldb, int ldc,
                         int layout, void* stream);
+
+/*
+ * Int8 (Section VI-B "Int8 Quantization": the pattern is independent of the
+ * element type, the matrix cores run the same condensed product on int8
+ * operands with int32 sums).  TW pattern, TW_LAYOUT_KM only.
+ *
+ * tw_pack_i8_host / tw_pack_i8 - as tw_pack_host / tw_pack for a K x N row-major
+ *   int8 weight (ldb = N) and a TW mask.  Same errors.  The handle works with
+ *   tw_upload, tw_concat (members of one dtype), tw_export (see `dtype`),
+ *   tw_unpack (values sign-extended to 16 bits), tw_flop_counts and tw_free;
+ *   tw_gemm refuses it (TW_ERR_ARG), as tw_gemm_i8 refuses an fp16 handle.
+ * tw_gemm_i8 - C = A . (B (.) mask), exact in int32 (|sum| <= K * 2^14 < 2^31 for
+ *   K <= 131071; larger K: TW_ERR_UNSUPPORTED).
+ *   A_dev   device int8, K x M (element (i,k) at A[k*lda + i]), 16-byte aligned,
+ *           lda >= M, multiple of 16, K * lda < 2^32
+ *   C_dev   device, N x M (element (i,n) at C[n*ldc + i]), 16-byte aligned, ldc >= M,
+ *           multiple of 16, in elements of:
+ *             c_dtype = 0: int32 sums;
+ *             c_dtype = 1: int8 = clamp(round-half-even(fp32(sum) * scale), -128, 127),
+ *                          the product taken in fp32 with one rounding
+ *           pruned columns are written as 0.
+ *   Asynchronous on `stream`, allocates nothing.  Errors: TW_ERR_ARG, TW_ERR_STATE,
+ *   TW_ERR_UNSUPPORTED (G = 32, K or A too large), TW_ERR_HIP.
+ * tw_dense_gemm_i8 - the dense int8 baseline on the same matrix cores and layouts:
+ *   B_dev K x N row-major int8, ldb >= N, multiple of 16, 16-byte aligned;
+ *   K % 64 != 0 gives TW_ERR_UNSUPPORTED.
+ */
+tw_status tw_pack_i8_host(const int8_t* B_host, const uint8_t* mask_host, int K, int N, int G,
+                          tw_handle_t* out);
+tw_status tw_pack_i8(const int8_t* B_host, const uint8_t* mask_host, int K, int N, int G,
+                     tw_handle_t* out);
+tw_status tw_gemm_i8(const void* A_dev, int M, int lda, tw_handle_t h, void* C_dev, int ldc,
+                     int c_dtype, float scale, void* stream);
+tw_status tw_dense_gemm_i8(const void* A_dev, const void* B_dev, void* C_dev, int M, int K, int N,
+                           int lda, int ldb, int ldc, int c_dtype, float scale, void* stream);
 
 /* tw_export - fill *out with the logical view (host pointers owned by h). */
 tw_status tw_export(tw_handle_t h, tw_packed_view* out);

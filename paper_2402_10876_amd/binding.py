@@ -11,11 +11,13 @@ import numpy as np
 
 PATTERN_TW, PATTERN_TVW, PATTERN_TEW = 0, 1, 2
 LAYOUT_KM, LAYOUT_MK = 0, 1
+DTYPE_F16, DTYPE_I8 = 0, 1
 
 EXPORTED_SYMBOLS = [
     "tw_pack_host", "tw_upload", "tw_pack", "tw_pack_dev", "tw_prune_dev",
     "tw_prune_workspace_bytes", "tw_concat", "tw_gemm", "tw_dense_gemm", "tw_export",
     "tw_unpack", "tw_free", "tw_status_str", "tw_set_option", "tw_flop_counts",
+    "tw_pack_i8_host", "tw_pack_i8", "tw_gemm_i8", "tw_dense_gemm_i8",
 ]
 
 _lib = None
@@ -37,7 +39,7 @@ class _View(C.Structure):
                 ("meta", C.POINTER(C.c_uint8)), ("valid", C.POINTER(C.c_uint8)),
                 ("tile_col_off", C.POINTER(C.c_int32)), ("ew_nnz", C.c_int64),
                 ("ew_col_ptr", C.POINTER(C.c_int32)), ("ew_row", C.POINTER(C.c_int32)),
-                ("ew_val", C.POINTER(C.c_uint16))]
+                ("ew_val", C.POINTER(C.c_uint16)), ("dtype", C.c_int32)]
 
 
 def lib_path() -> str:
@@ -67,6 +69,10 @@ def lib():
         L.tw_prune_dev.argtypes = [vp, i, i, i, i, i, i, i, vp, vp, vp, C.c_size_t, vp]
         L.tw_pack_dev.argtypes = [vp, i, vp, vp, i, i, i, i, vp, C.POINTER(vp)]
         L.tw_gemm.argtypes = [vp, i, i, i, vp, vp, i, vp]
+        L.tw_pack_i8_host.argtypes = [vp, vp, i, i, i, C.POINTER(vp)]
+        L.tw_pack_i8.argtypes = L.tw_pack_i8_host.argtypes
+        L.tw_gemm_i8.argtypes = [vp, i, i, vp, vp, i, i, C.c_float, vp]
+        L.tw_dense_gemm_i8.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, C.c_float, vp]
         L.tw_dense_gemm.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, vp]
         L.tw_export.argtypes = [vp, C.POINTER(_View)]
         L.tw_unpack.argtypes = [vp, vp, vp]
@@ -122,7 +128,9 @@ class PackedWeight:
         ctok = arr(v.cto_k, sk, np.int32)
         voff = arr(v.val_off, nt + 1, np.int64)
         vals = arr(v.values, int(voff[-1]) if voff.size else 0, np.uint16)
-        out = dict(K=v.K, N=v.N, G=v.G, pattern=v.pattern, n_kept=nk, n_tiles=nt,
+        if v.dtype == DTYPE_I8:          # int8 values travel sign-extended to 16 bits
+            vals = vals.view(np.int16).astype(np.int8)
+        out = dict(K=v.K, N=v.N, G=v.G, pattern=v.pattern, dtype=v.dtype, n_kept=nk, n_tiles=nt,
                    col_idx=arr(v.col_idx, nk, np.int32), cto_n=arr(v.cto_n, nk, np.int32),
                    row_idx=[rows[tko[t]:tko[t + 1]] for t in range(nt)],
                    cto_k=[ctok[tko[t]:tko[t + 1]] for t in range(nt)])
@@ -152,6 +160,8 @@ class PackedWeight:
         Bm = np.empty((v.K, v.N), np.uint16)
         mask = np.empty((v.K, v.N), np.uint8)
         _check(lib().tw_unpack(self.handle, _host_ptr(Bm), _host_ptr(mask)), "tw_unpack")
+        if v.dtype == DTYPE_I8:
+            Bm = Bm.view(np.int16).astype(np.int8)
         return Bm, mask
 
     def flop_counts(self):
@@ -199,6 +209,27 @@ def tw_pack(B16, mask, G, pattern, tile_mask=None) -> PackedWeight:
     return _pack("tw_pack", B16, mask, G, pattern, tile_mask)
 
 
+def _pack_i8(fn_name, B8, mask, G):
+    B8 = np.ascontiguousarray(B8)
+    if B8.dtype != np.int8:
+        raise TypeError("B must be int8")
+    mask = np.ascontiguousarray(mask, dtype=np.uint8)
+    if mask.shape != B8.shape or B8.ndim != 2:
+        raise ValueError("B and mask must be K x N")
+    K, N = B8.shape
+    h = C.c_void_p()
+    _check(getattr(lib(), fn_name)(_host_ptr(B8), _host_ptr(mask), K, N, int(G), C.byref(h)), fn_name)
+    return PackedWeight(h)
+
+
+def tw_pack_i8_host(B8, mask, G) -> PackedWeight:
+    return _pack_i8("tw_pack_i8_host", B8, mask, G)
+
+
+def tw_pack_i8(B8, mask, G) -> PackedWeight:
+    return _pack_i8("tw_pack_i8", B8, mask, G)
+
+
 def tw_prune_workspace_bytes(K: int, N: int, G: int) -> int:
     n = C.c_size_t()
     _check(lib().tw_prune_workspace_bytes(K, N, G, C.byref(n)), "tw_prune_workspace_bytes")
@@ -239,6 +270,18 @@ def tw_dense_gemm(A_ptr: int, B_ptr: int, C_ptr: int, M: int, K: int, N: int, ld
                   ldb: int, ldc: int, layout: int, stream: int = 0):
     _check(lib().tw_dense_gemm(A_ptr, B_ptr, C_ptr, M, K, N, lda, ldb, ldc, layout, stream),
            "tw_dense_gemm")
+
+
+def tw_gemm_i8(A_ptr: int, M: int, lda: int, packed: PackedWeight, C_ptr: int, ldc: int,
+               c_dtype: int = 0, scale: float = 1.0, stream: int = 0):
+    """int8 A (K x M) times a packed int8 weight; C (N x M) int32 (c_dtype 0) or requantised int8 (1)."""
+    _check(lib().tw_gemm_i8(A_ptr, M, lda, packed.handle, C_ptr, ldc, c_dtype, scale, stream), "tw_gemm_i8")
+
+
+def tw_dense_gemm_i8(A_ptr: int, B_ptr: int, C_ptr: int, M: int, K: int, N: int, lda: int, ldb: int,
+                     ldc: int, c_dtype: int = 0, scale: float = 1.0, stream: int = 0):
+    _check(lib().tw_dense_gemm_i8(A_ptr, B_ptr, C_ptr, M, K, N, lda, ldb, ldc, c_dtype, scale, stream),
+           "tw_dense_gemm_i8")
 
 
 def tw_set_option(name: str, value: int):

@@ -5,6 +5,7 @@
 #include <atomic>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "kernels.h"
 #include "packed.h"
@@ -111,7 +112,8 @@ tw_status tw_upload(tw_handle_t h) {
   Part parts[10] = {
       {d.col_idx.data(), d.col_idx.size() * 4, 0},   {d.tile_kp_off.data(), d.tile_kp_off.size() * 4, 0},
       {d.row_idx.data(), d.row_idx.size() * 4, 0},   {d.zero_cols.data(), d.zero_cols.size() * 4, 0},
-      {d.tile_order.data(), d.tile_order.size() * 4, 0}, {d.vals.data(), d.vals.size() * 2, 0},
+      {d.tile_order.data(), d.tile_order.size() * 4, 0},
+      h->dtype == TW_DTYPE_I8 ? Part{d.vals8.data(), d.vals8.size(), 0} : Part{d.vals.data(), d.vals.size() * 2, 0},
       {d.meta.data(), d.meta.size() * 4, 0}, {d.tile_sched.data(), d.tile_sched.size() * 4, 0},
       {d.ew_ptr.data(), d.ew_ptr.size() * 4, 0}, {d.ew_pairs.data(), d.ew_pairs.size() * 4, 0}};
   size_t total = 0;
@@ -143,6 +145,36 @@ tw_status tw_upload(tw_handle_t h) {
 tw_status tw_pack(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_mask, int K, int N,
                   int G, int pattern, tw_handle_t* out) {
   tw_status st = tw_pack_host(B, mask, tile_mask, K, N, G, pattern, out);
+  if (st != TW_OK) return st;
+  st = tw_upload(*out);
+  if (st != TW_OK) { tw_free(*out); *out = nullptr; }
+  return st;
+}
+
+tw_status tw_pack_i8_host(const int8_t* B, const uint8_t* mask, int K, int N, int G, tw_handle_t* out) {
+  if (!out) return TW_ERR_ARG;
+  *out = nullptr;
+  if (!B || !mask || K < 1 || N < 1 || !valid_G(G)) return TW_ERR_ARG;
+  tw_handle_s* h = new (std::nothrow) tw_handle_s();
+  if (!h) return TW_ERR_ALLOC;
+  tw_status st;
+  try {
+    // the packer moves 16-bit patterns around without looking at them: int8 values
+    // ride through it sign-extended
+    std::vector<uint16_t> wide((size_t)K * N);
+    for (size_t i = 0; i < wide.size(); ++i) wide[i] = (uint16_t)(int16_t)B[i];
+    h->dtype = TW_DTYPE_I8;
+    st = twg::pack_host(wide.data(), mask, nullptr, K, N, G, TW_PATTERN_TW, h);
+  } catch (const std::bad_alloc&) {
+    st = TW_ERR_ALLOC;
+  }
+  if (st != TW_OK) { delete h; return st; }
+  *out = h;
+  return TW_OK;
+}
+
+tw_status tw_pack_i8(const int8_t* B, const uint8_t* mask, int K, int N, int G, tw_handle_t* out) {
+  tw_status st = tw_pack_i8_host(B, mask, K, N, G, out);
   if (st != TW_OK) return st;
   st = tw_upload(*out);
   if (st != TW_OK) { tw_free(*out); *out = nullptr; }
@@ -210,6 +242,7 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
   if (!A || !C || !h || M < 1) return TW_ERR_ARG;
   if (layout != TW_LAYOUT_KM && layout != TW_LAYOUT_MK) return TW_ERR_ARG;
   if (!aligned16(A) || !aligned16(C) || lda % 8 || ldc % 8) return TW_ERR_ARG;
+  if (h->dtype != TW_DTYPE_F16) return TW_ERR_ARG;
   if (!h->img.blob) return TW_ERR_STATE;
   if (layout == TW_LAYOUT_MK) {
     if (lda < h->K || ldc < h->N) return TW_ERR_ARG;
@@ -314,11 +347,60 @@ tw_status tw_dense_gemm(const void* A, const void* B, void* C, int M, int K, int
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
 
+// int8 M-tile: 256 rows while that still gives every CU two workgroups, else 128
+static int pick_tile_m_i8(int M, int n_tiles) {
+  const int forced = opt_tile_m.load();
+  if (forced == 128 || forced == 256) return forced;
+  return (long)((M + 255) / 256) * n_tiles >= 512 ? 256 : 128;
+}
+
+tw_status tw_gemm_i8(const void* A, int M, int lda, tw_handle_t h, void* C, int ldc, int c_dtype,
+                     float scale, void* stream) {
+  if (!A || !C || !h || M < 1 || (c_dtype != 0 && c_dtype != 1)) return TW_ERR_ARG;
+  if (!aligned16(A) || !aligned16(C) || lda % 16 || ldc % 16 || lda < M || ldc < M) return TW_ERR_ARG;
+  if (h->dtype != TW_DTYPE_I8) return TW_ERR_ARG;
+  if (!h->img.blob) return TW_ERR_STATE;
+  if (h->G == 32 || h->K > 131071) return TW_ERR_UNSUPPORTED;
+  if ((unsigned long long)h->K * (unsigned long long)lda >= (1ull << 32)) return TW_ERR_UNSUPPORTED;
+  twg::GemmI8Args g{};
+  g.A = (const int8_t*)A; g.C = C; g.M = M; g.lda = lda; g.ldc = ldc;
+  g.c_i8 = c_dtype; g.scale = scale;
+  g.vals = (const int8_t*)h->img.d_vals;
+  g.row_idx = h->img.d_row_idx; g.col_idx = h->img.d_col_idx; g.tile_sched = h->img.d_tile_sched;
+  g.zero_cols = h->img.d_zero_cols; g.n_zero = (int)h->img.zero_cols.size();
+  g.n_tiles = h->n_tiles; g.K = h->K; g.N = h->N; g.xcd_map = opt_xcd_map.load() ? 1 : 0;
+  const int tm = pick_tile_m_i8(M, h->n_tiles > 0 ? h->n_tiles : 1);
+  hipError_t e = twg::launch_tw_i8(h->G, tm, g, (hipStream_t)stream);
+  if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
+  return e == hipSuccess ? TW_OK : TW_ERR_HIP;
+}
+
+tw_status tw_dense_gemm_i8(const void* A, const void* B, void* C, int M, int K, int N, int lda, int ldb,
+                           int ldc, int c_dtype, float scale, void* stream) {
+  if (!A || !B || !C || M < 1 || K < 1 || N < 1 || (c_dtype != 0 && c_dtype != 1)) return TW_ERR_ARG;
+  if (!aligned16(A) || !aligned16(B) || !aligned16(C) || lda % 16 || ldb % 16 || ldc % 16) return TW_ERR_ARG;
+  if (ldb < N || lda < M || ldc < M) return TW_ERR_ARG;
+  if (K % 64 || K > 131071) return TW_ERR_UNSUPPORTED;
+  if ((unsigned long long)K * (unsigned long long)lda >= (1ull << 32) ||
+      (unsigned long long)K * (unsigned long long)ldb >= (1ull << 32))
+    return TW_ERR_UNSUPPORTED;
+  twg::GemmI8Args g{};
+  g.A = (const int8_t*)A; g.C = C; g.M = M; g.lda = lda; g.ldc = ldc;
+  g.c_i8 = c_dtype; g.scale = scale;
+  g.vals = (const int8_t*)B; g.ldb = ldb; g.K = K; g.N = N;
+  const int tn = 128;
+  g.n_tiles = (N + tn - 1) / tn;
+  g.xcd_map = opt_xcd_map.load() ? 1 : 0;
+  hipError_t e = twg::launch_dense_i8(tn, pick_tile_m_i8(M, g.n_tiles), g, (hipStream_t)stream);
+  if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
+  return e == hipSuccess ? TW_OK : TW_ERR_HIP;
+}
+
 tw_status tw_export(tw_handle_t h, tw_packed_view* out) {
   if (!h || !out) return TW_ERR_ARG;
   std::memset(out, 0, sizeof(*out));
   out->K = h->K; out->N = h->N; out->G = h->G; out->pattern = h->pattern;
-  out->n_kept = h->n_kept; out->n_tiles = h->n_tiles;
+  out->n_kept = h->n_kept; out->n_tiles = h->n_tiles; out->dtype = h->dtype;
   out->col_idx = h->col_idx.data(); out->cto_n = h->cto_n.data();
   out->tile_k_off = h->tile_k_off.data(); out->row_idx = h->row_idx.data();
   out->cto_k = h->cto_k.data(); out->val_off = h->val_off.data(); out->values = h->values.data();

@@ -95,7 +95,8 @@ __device__ __forceinline__ int xcd_remap(int bid, int n) {
 // these are XCD-local slots s, s+32, s+64, ..) are consecutive: they work on
 // the same weight tile at the same pace, and its rows are fetched from L2 once
 // per CU rather than once per workgroup.
-__device__ __forceinline__ void tile_of_workgroup(const GemmArgs& g, int bid, int n_gemm, int& mt, int& t) {
+template <class Args>
+__device__ __forceinline__ void tile_of_workgroup(const Args& g, int bid, int n_gemm, int& mt, int& t) {
   if (g.xcd_map == 2 && (g.n_mtiles & 7) == 0) {
     const int xcd = bid & 7, slot = bid >> 3;
     const int mts = g.n_mtiles >> 3, cnt = mts * g.n_tiles;

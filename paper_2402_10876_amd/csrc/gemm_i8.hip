@@ -1,0 +1,421 @@
+// Int8 TW kernel and dense int8 baseline for gfx950 (Section VI-B "Int8
+// Quantization": the TW pattern does not depend on the element type; the matrix
+// cores multiply int8 operands into int32 sums, which are exact).
+//
+// Same decomposition, layouts and pipeline as the fp16 asynchronous-copy kernel
+// (one workgroup per (M-tile, N-tile) pair, Listing 1; A is K x M and C is N x M,
+// Section V "Memory Accesses Coalesce"; global_load_lds_dwordx4 copies, three
+// stages in flight, one vmcnt wait and one s_barrier per stage), with bytes
+// instead of halves:
+//
+//   stage   : 64 condensed rows = two v_mfma_i32_32x32x32_i8 steps per block.
+//   LDS     : k-major tiles, TM (TN) bytes per row.  One transposing read
+//             (ds_read_b64_tr_b8) of a half-wave touches 8 consecutive rows x 32
+//             bytes; the XOR mask below sends those eight pieces to the eight
+//             32-byte slots of the 256-byte bank period.
+//   operand : lane l of the matrix instruction holds m (or n) = l % 32 and the 16
+//             bytes k = 16 (l / 32) .. +15 of the step: two transposing reads, 8 rows
+//             apart, whose source lane p of a 16-lane group reads 8 bytes at row
+//             k0 + p / 2, column x0 + 8 (p % 2).
+//   output  : int32 sums, or int8 = clamp(rne(fp32(sum) * scale)) (one fp32 product).
+#include <type_traits>
+
+#include "device_common.h"
+
+namespace twg {
+
+namespace {
+
+typedef int intx16 __attribute__((ext_vector_type(16)));
+typedef int int4v __attribute__((ext_vector_type(4)));
+
+template <int OFF>
+__device__ __forceinline__ int2v tr8_read(uint32_t addr) {
+  int2v v;
+  asm volatile("ds_read_b64_tr_b8 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+  return v;
+}
+
+struct Frag8 { int2v lo, hi; };
+
+__device__ __forceinline__ int4v as_int4(const Frag8& f) {
+  int4v r;
+  r[0] = f.lo[0]; r[1] = f.lo[1]; r[2] = f.hi[0]; r[3] = f.hi[1];
+  return r;
+}
+
+template <int N>
+__device__ __forceinline__ void wait_lds8(Frag8* f) {
+  // s_waitcnt tied to the fragments so that no use can be moved above it
+  if constexpr (N == 3)
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi),
+                 "+v"(f[2].lo), "+v"(f[2].hi));
+  else if constexpr (N == 4)
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi),
+                 "+v"(f[2].lo), "+v"(f[2].hi), "+v"(f[3].lo), "+v"(f[3].hi));
+  else if constexpr (N == 6)
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi),
+                 "+v"(f[2].lo), "+v"(f[2].hi), "+v"(f[3].lo), "+v"(f[3].hi), "+v"(f[4].lo),
+                 "+v"(f[4].hi), "+v"(f[5].lo), "+v"(f[5].hi));
+  else static_assert(N == 3, "unsupported fragment count");
+}
+
+// Wave-uniform 16-byte record through the scalar cache, complete on return.
+__device__ __forceinline__ int4v scalar_load4(const void* p) {
+  int4v r;
+  asm volatile("s_load_dwordx4 %0, %1, 0x0\n\ts_waitcnt lgkmcnt(0)" : "=s"(r) : "s"(p));
+  return r;
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vm() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// XOR mask on the byte offset inside a row of RB bytes (a multiple of 32: the 16-byte
+// chunks of the copies and the 8-byte pieces of the reads stay whole).
+template <int RB>
+__device__ __forceinline__ int swz8_mask(int row) {
+  if constexpr (RB == 256) return (row & 7) << 5;
+  else if constexpr (RB == 128) return ((row >> 1) & 3) << 5;   // two rows per bank period
+  else return ((row >> 2) & 1) << 5;                           // RB == 64: four rows per period
+}
+template <int RB>
+__device__ __forceinline__ int swz8(int row, int xbytes) {
+  return row * RB + (xbytes ^ swz8_mask<RB>(row));
+}
+
+__device__ __forceinline__ int requantize(int sum, float scale) {
+  float x = (float)sum * scale;            // int -> fp32 (nearest even), one fp32 product
+  x = __builtin_rintf(x);                  // halves to even
+  x = __builtin_fminf(__builtin_fmaxf(x, -128.f), 127.f);
+  return (int)x;
+}
+
+// Extra workgroups of a launch write 0 into one pruned column of C each.
+template <bool OUT8>
+__device__ __forceinline__ void zero_fill_column8(const GemmI8Args& g, int which) {
+  const int col = g.zero_cols[which];
+  constexpr int ES = OUT8 ? 1 : 4;
+  char* row = (char*)g.C + (size_t)col * g.ldc * ES;
+  const size_t bytes = (size_t)g.M * ES;
+  const u32x4 z = {0u, 0u, 0u, 0u};
+  for (size_t b = (size_t)threadIdx.x * 16; b < bytes; b += (size_t)blockDim.x * 16) {
+    if (b + 16 <= bytes) __builtin_nontemporal_store(z, (u32x4*)(row + b));
+    else for (size_t i = b; i < bytes; ++i) row[i] = 0;
+  }
+}
+
+constexpr int KS8 = 64;      // condensed rows per stage
+constexpr int D8 = 3;        // stages in flight
+
+}  // namespace
+
+template <int TM, int TN, int WAVES_M, bool DENSE, bool OUT8>
+__global__ __launch_bounds__(256) void tw_gemm_i8_kernel(GemmI8Args g) {
+  constexpr int NWAVES = 4, NT = 256, D = D8;
+  constexpr int WAVES_N = NWAVES / WAVES_M;
+  constexpr int WM = TM / WAVES_M, WN = TN / WAVES_N;
+  constexpr int MB = WM / 32, NB = WN / 32;
+  static_assert(MB >= 1 && NB >= 1, "wave tile must hold a 32x32 block");
+  constexpr int RBA = TM, RBB = TN;                    // LDS row bytes
+  constexpr int STAGE_A = KS8 * RBA, STAGE_B = KS8 * RBB, STAGE = STAGE_A + STAGE_B;
+  static_assert(STAGE_A % (1024 * NWAVES) == 0 && STAGE_B % (1024 * NWAVES) == 0,
+                "a stage is a whole number of 1 KiB copies per wave");
+  constexpr int NIA = STAGE_A / (1024 * NWAVES), NIB = STAGE_B / (1024 * NWAVES);
+  constexpr int RPIA = 1024 / RBA, RPIB = 1024 / RBB;  // tile rows per copy instruction
+  static_assert(RPIA == 4 || RPIA == 8, "row lists are fetched 4 or 8 entries at a time");
+  constexpr int NPS = NIA + NIB;
+  // epilogue: int32 tile staged as [n][m], half of the columns at a time
+  constexpr int CS = (TM + 4) * 4;
+  constexpr int HN = TN / 2;
+  static_assert(HN % 32 == 0, "");
+  constexpr int PIPE_BYTES = D * STAGE, EPI_BYTES = HN * CS;
+  constexpr int LDS_BYTES = PIPE_BYTES > EPI_BYTES ? PIPE_BYTES : EPI_BYTES;
+  __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int n_gemm = g.n_mtiles * g.n_tiles;
+  if ((int)blockIdx.x >= n_gemm) {
+    zero_fill_column8<OUT8>(g, blockIdx.x - n_gemm);
+    return;
+  }
+  int mt, t;                             // t: launch position of the tile, then the tile itself
+  tile_of_workgroup(g, blockIdx.x, n_gemm, mt, t);
+  const int m0 = mt * TM;
+
+  int kp0, ns;                           // ns: stages of 64 rows
+  if constexpr (DENSE) { kp0 = 0; ns = g.K / KS8; }    // host guarantees K % 64 == 0
+  else {
+    const int4v rec = scalar_load4(g.tile_sched + 4 * t);
+    t = rec[0]; kp0 = rec[1]; ns = rec[2] / KS8;
+  }
+  const int8_t* Bt = DENSE ? g.vals + (size_t)t * TN : g.vals + (size_t)kp0 * TN;
+  const uint32_t ldb = DENSE ? (uint32_t)g.ldb : (uint32_t)TN;
+
+  // ---- geometry of the asynchronous copies: instruction j of this wave fills LDS
+  // bytes [(wave*NI + j) KiB, +1 KiB) of the stage; lane l owns the 16 bytes at l*16,
+  // i.e. tile row (wave*NI + j)*RPI + l*16/RB at physical byte (l*16) % RB, which
+  // holds the logical bytes physical ^ swz8_mask(row).
+  const int lb = lane * 16;
+  const int a_rloc = lb / RBA, b_rloc = lb / RBB;
+  int a_el[NIA], b_el[NIB];
+#pragma unroll
+  for (int j = 0; j < NIA; ++j) {
+    const int row = (wave * NIA + j) * RPIA + a_rloc;
+    a_el[j] = (lb % RBA) ^ swz8_mask<RBA>(row);
+    if (m0 + a_el[j] >= g.M) a_el[j] = 0;   // past M: re-read chunk 0 (those lanes are never stored)
+  }
+#pragma unroll
+  for (int j = 0; j < NIB; ++j) {
+    const int row = (wave * NIB + j) * RPIB + b_rloc;
+    b_el[j] = (lb % RBB) ^ swz8_mask<RBB>(row);
+    if constexpr (DENSE) { if (t * TN + b_el[j] >= g.N) b_el[j] = 0; }
+  }
+  // wave-uniform base plus an unsigned 32-bit byte offset per lane (the host checks
+  // that A and B fit)
+  const char* Abase = (const char*)(g.A + m0);
+  const char* Bbase = (const char*)Bt;
+  const uint32_t lda = (uint32_t)g.lda;
+  uint32_t b_off[NIB];
+#pragma unroll
+  for (int j = 0; j < NIB; ++j)
+    b_off[j] = (uint32_t)((wave * NIB + j) * RPIB + b_rloc) * ldb + (uint32_t)b_el[j];
+
+  // Kept-row indices of a stage for copy instruction j: RPIA consecutive entries of the
+  // list at a wave-uniform address, through scalar loads written in assembly (a vector
+  // load would share the in-order counter of the asynchronous copies).  Each fetch is
+  // issued right after a stage barrier and waited for together with the first operand
+  // reads of that stage, one iteration before its rows are needed.
+  typedef int sidx_t __attribute__((ext_vector_type(RPIA)));
+  struct Rows { sidx_t r[NIA]; };
+  auto fetch_rows = [&](int s, Rows& dst) {
+    if constexpr (!DENSE) {
+#pragma unroll
+      for (int j = 0; j < NIA; ++j) {
+        const int* rp = g.row_idx + kp0 + s * KS8 + (wave * NIA + j) * RPIA;
+        if constexpr (RPIA == 4) asm volatile("s_load_dwordx4 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
+        else asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
+      }
+    }
+  };
+  auto tie_rows = [&](Rows& x) {      // after a wait: no use of x may be moved above this point
+    if constexpr (!DENSE) {
+      if constexpr (NIA == 2) asm volatile("" : "+s"(x.r[0]), "+s"(x.r[1]));
+      else asm volatile("" : "+s"(x.r[0]), "+s"(x.r[1]), "+s"(x.r[2]), "+s"(x.r[3]));
+    }
+  };
+  static_assert(NIA == 2 || NIA == 4, "");
+  auto issue = [&](int s, const Rows& rows) {     // copies of stage s; rows = its kept-row indices
+    char* dstA = lds + (s % D) * STAGE;
+    char* dstB = dstA + STAGE_A;
+    const uint32_t bs = (uint32_t)s * (uint32_t)KS8 * ldb;
+#pragma unroll
+    for (int j = 0; j < NIB; ++j)
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(Bbase + (bs + b_off[j])),
+                                       LDS_PTR(void, dstB + (wave * NIB + j) * 1024), 16, 0, 0);
+#pragma unroll
+    for (int j = 0; j < NIA; ++j) {
+      int row;
+      if constexpr (DENSE) row = s * KS8 + (wave * NIA + j) * RPIA + a_rloc;
+      else {
+        row = rows.r[j][0];
+#pragma unroll
+        for (int q = 1; q < RPIA; ++q) row = (a_rloc == q) ? rows.r[j][q] : row;
+      }
+      __builtin_amdgcn_global_load_lds(GLOBAL_PTR(Abase + ((uint32_t)row * lda + (uint32_t)a_el[j])),
+                                       LDS_PTR(void, dstA + (wave * NIA + j) * 1024), 16, 0, 0);
+    }
+  };
+
+  intx16 acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
+#pragma unroll
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+
+  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+  // per-lane LDS byte address of each operand block at stage buffer 0, k-step 0
+  const uint32_t lds0 = (uint32_t)(uintptr_t)LDS_PTR(char, lds);
+  const int p = lane & 15, q = lane >> 4;
+  const int frow = 16 * (q >> 1) + (p >> 1);
+  const int fcol = 16 * (q & 1) + 8 * (p & 1);
+  uint32_t fa[MB], fb[NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i) fa[i] = lds0 + swz8<RBA>(frow, wm * WM + i * 32 + fcol);
+#pragma unroll
+  for (int j = 0; j < NB; ++j) fb[j] = lds0 + STAGE_A + swz8<RBB>(frow, wn * WN + j * 32 + fcol);
+
+  constexpr int NF = MB + NB;
+  Frag8 f0[NF], f1[NF];      // operands of k-steps 0 and 1 of a stage
+  auto read_step = [&](uint32_t boff, auto KK_, Frag8* f) {
+    constexpr int KK = decltype(KK_)::value;
+    // rows +8 and +32 leave the swizzle mask of a lane's row unchanged
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+      f[i].lo = tr8_read<KK * RBA>(fa[i] + boff);
+      f[i].hi = tr8_read<(KK + 8) * RBA>(fa[i] + boff);
+    }
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      f[MB + j].lo = tr8_read<KK * RBB>(fb[j] + boff);
+      f[MB + j].hi = tr8_read<(KK + 8) * RBB>(fb[j] + boff);
+    }
+  };
+  auto mfma_step = [&](const Frag8* f) {
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(as_int4(f[i]), as_int4(f[MB + j]), acc[i][j], 0, 0, 0);
+  };
+  using K0 = std::integral_constant<int, 0>;
+  using K32 = std::integral_constant<int, 32>;
+
+  Rows rows_cur, rows_next;
+  if (ns > 0) {
+    // kept-row lists of the first D stages in one round trip, then D-1 stages of copies
+    Rows pro[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d) fetch_rows(d < ns ? d : ns - 1, pro[d]);
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+#pragma unroll
+    for (int d = 0; d < D; ++d) tie_rows(pro[d]);
+#pragma unroll
+    for (int d = 0; d < D - 1; ++d)
+      if (d < ns) issue(d, pro[d]);
+    rows_cur = pro[D - 1];
+  }
+  for (int s = 0; s < ns; ++s) {
+    // own copies of stage s have landed: at most the copies of the one newer stage remain
+    if (s + 1 < ns) wait_vm<NPS>();
+    else wait_vm<0>();
+    // everybody's copies of stage s have landed, everybody is done reading stage s-1
+    asm volatile("s_barrier" ::: "memory");
+    fetch_rows(s + D < ns ? s + D : ns - 1, rows_next);   // needed by the next iteration
+    const uint32_t boff = (uint32_t)((s % D) * STAGE);
+    read_step(boff, K0{}, f0);
+    if (s > 0) mfma_step(f1);            // second k-step of the previous stage
+    wait_lds8<NF>(f0);                   // full wait: the scalar loads above are in as well
+    tie_rows(rows_next);
+    // the copies of stage s+D-1 go into the buffer of stage s-1, which every wave has
+    // finished reading
+    if (s + D - 1 < ns) issue(s + D - 1, rows_cur);
+    read_step(boff, K32{}, f1);
+    mfma_step(f0);
+    rows_cur = rows_next;
+    wait_lds8<NF>(f1);
+  }
+  if (ns > 0) mfma_step(f1);
+
+  // ---- epilogue: stage as [n][m] int32, half of the tile's columns at a time; every
+  // thread then finishes (column, CH x m) pieces with one 16-byte streaming store each
+  constexpr int CH = OUT8 ? 16 : 4;            // m values per piece
+  constexpr int CA = TM / CH;                  // pieces per column
+  constexpr int RPP = NT / CA;                 // columns per pass
+  static_assert(HN % RPP == 0, "");
+  constexpr int NPASS = HN / RPP;
+  const int c = tid % CA, r0 = tid / CA;
+  const int m = m0 + c * CH;
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    // original column of C of every piece (CTO_n); loaded before the barrier, used after
+    int cols[NPASS];
+#pragma unroll
+    for (int i = 0; i < NPASS; ++i) {
+      const int n = h * HN + r0 + i * RPP;
+      if constexpr (DENSE) { cols[i] = t * TN + n; if (cols[i] >= g.N) cols[i] = -1; }
+      else cols[i] = g.col_idx[t * TN + n];
+    }
+    __syncthreads();                     // pipeline buffers / the previous half are free
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        const int nblk = wn * WN + j * 32;                 // wave-uniform
+        if (nblk / HN != h) continue;
+        const int n = nblk - h * HN + (lane & 31);
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          const int mm = wm * WM + i * 32 + 8 * rq + 4 * (lane >> 5);
+          int4v v;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) v[r] = acc[i][j][rq * 4 + r];
+          *(int4v*)(lds + n * CS + mm * 4) = v;
+        }
+      }
+    __syncthreads();
+    // all staged pieces into registers first (unconditional reads), then the stores
+    int4v pc[NPASS][CH / 4];
+#pragma unroll
+    for (int i = 0; i < NPASS; ++i) {
+      const char* src = lds + (r0 + i * RPP) * CS + c * CH * 4;
+#pragma unroll
+      for (int u = 0; u < CH / 4; ++u) pc[i][u] = *(const int4v*)(src + 16 * u);
+    }
+#pragma unroll
+    for (int i = 0; i < NPASS; ++i) {
+      if (cols[i] < 0 || m >= g.M) continue;
+      if constexpr (OUT8) {
+        int4v w;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          uint32_t pk = 0;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) pk |= ((uint32_t)requantize(pc[i][u][r], g.scale) & 0xffu) << (8 * r);
+          w[u] = (int)pk;
+        }
+        int8_t* dst = (int8_t*)g.C + (size_t)cols[i] * g.ldc + m;
+        if (m + 16 <= g.M) __builtin_nontemporal_store(w, (int4v*)dst);
+        else {
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            if (m + e < g.M) dst[e] = (int8_t)(w[e >> 2] >> (8 * (e & 3)));
+        }
+      } else {
+        int* dst = (int*)g.C + (size_t)cols[i] * g.ldc + m;
+        if (m + 4 <= g.M) __builtin_nontemporal_store(pc[i][0], (int4v*)dst);
+        else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (m + e < g.M) dst[e] = pc[i][0][e];
+        }
+      }
+    }
+  }
+}
+
+template <int TM, int TN, int WAVES_M, bool DENSE>
+static hipError_t launch8(const GemmI8Args& g, hipStream_t stream) {
+  const int grid = g.n_mtiles * g.n_tiles + g.n_zero;
+  if (grid <= 0) return hipSuccess;
+  if (g.c_i8)
+    hipLaunchKernelGGL((tw_gemm_i8_kernel<TM, TN, WAVES_M, DENSE, true>), dim3(grid), dim3(256), 0, stream, g);
+  else
+    hipLaunchKernelGGL((tw_gemm_i8_kernel<TM, TN, WAVES_M, DENSE, false>), dim3(grid), dim3(256), 0, stream, g);
+  return hipGetLastError();
+}
+
+template <bool DENSE>
+static hipError_t dispatch8(int G, int tm, GemmI8Args& g, hipStream_t stream) {
+  g.n_mtiles = (g.M + tm - 1) / tm;
+  if (G == 128 && tm == 128) return launch8<128, 128, 2, DENSE>(g, stream);
+  if (G == 128 && tm == 256) return launch8<256, 128, 2, DENSE>(g, stream);
+  if (G == 64 && tm == 128) return launch8<128, 64, 2, DENSE>(g, stream);
+  if (G == 64 && tm == 256) return launch8<256, 64, 4, DENSE>(g, stream);
+  return hipErrorInvalidValue;
+}
+
+hipError_t launch_tw_i8(int G, int tm, GemmI8Args g, hipStream_t stream) {
+  return dispatch8<false>(G, tm, g, stream);
+}
+
+hipError_t launch_dense_i8(int tn, int tm, GemmI8Args g, hipStream_t stream) {
+  g.n_zero = 0;
+  return dispatch8<true>(tn, tm, g, stream);
+}
+
+}  // namespace twg

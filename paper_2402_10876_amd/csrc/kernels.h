@@ -31,6 +31,29 @@ struct GemmArgs {
 #endif
 };
 
+// Int8 operands, int32 sums (gemm_i8.hip); layouts as the KM kernels above.
+struct GemmI8Args {
+  const int8_t* A;               // K x M bytes, element (i,k) at A[k*lda + i]
+  void* C;                       // N x M, int32 or (c_i8) requantised int8
+  int M, lda, ldc;
+  int c_i8;
+  float scale;
+  const int8_t* vals;            // TW: condensed image [sum Kp_t][G] bytes; dense: B, K x N row-major
+  int ldb;                       // dense only
+  const int32_t* row_idx;
+  const int32_t* col_idx;
+  const int32_t* tile_sched;
+  const int32_t* zero_cols;
+  int n_zero;
+  int n_tiles, n_mtiles;
+  int K, N;                      // dense only
+  int xcd_map;
+};
+// G / tn in {64, 128}, tm in {128, 256}; hipErrorInvalidValue when no instance exists.
+// The dense variant needs K % 64 == 0.
+hipError_t launch_tw_i8(int G, int tm, GemmI8Args g, hipStream_t stream);
+hipError_t launch_dense_i8(int tn, int tm, GemmI8Args g, hipStream_t stream);
+
 // G / tn: tile width (32, 64, 128); tm: M-tile (64, 128, 256).
 // hipErrorInvalidValue when no instance exists for (G, tm).
 hipError_t launch_tw_km(int G, int tm, GemmArgs g, hipStream_t stream);

@@ -226,14 +226,14 @@ tw_status unpack_host(const tw_handle_s* h, uint16_t* Bm, uint8_t* mask) {
 // the members before.
 tw_status concat_host(const tw_handle_s* const* parts, int n, tw_handle_s* h) try {
   const tw_handle_s* p0 = parts[0];
-  h->K = p0->K; h->G = p0->G; h->pattern = p0->pattern;
+  h->K = p0->K; h->G = p0->G; h->pattern = p0->pattern; h->dtype = p0->dtype;
   h->N = 0; h->n_kept = 0; h->n_tiles = 0; h->sum_kw = 0; h->sum_k = 0;
   h->tile_col_off.assign(1, 0); h->tile_k_off.assign(1, 0);
   h->val_off.assign(1, 0); h->meta_off.assign(1, 0);
   if (h->pattern == TW_PATTERN_TEW) h->ew_col_ptr.assign(1, 0);
   for (int i = 0; i < n; ++i) {
     const tw_handle_s* p = parts[i];
-    if (p->K != h->K || p->G != h->G || p->pattern != h->pattern) return TW_ERR_ARG;
+    if (p->K != h->K || p->G != h->G || p->pattern != h->pattern || p->dtype != h->dtype) return TW_ERR_ARG;
     if ((int64_t)h->N + p->N > INT32_MAX) return TW_ERR_ARG;
     for (int32_t c : p->col_idx) h->col_idx.push_back(c + h->N);
     for (int t = 0; t < p->n_tiles; ++t) {
@@ -288,7 +288,8 @@ void build_device_image(tw_handle_s* h) {
   DeviceImage& d = h->img;
   const int G = h->G, nt = h->n_tiles;
   const bool tvw = h->pattern == TW_PATTERN_TVW;
-  const int kstep = tvw ? KSTEP_TVW : KSTEP_TW;
+  const bool i8 = h->dtype == TW_DTYPE_I8;
+  const int kstep = i8 ? KSTEP_I8 : tvw ? KSTEP_TVW : KSTEP_TW;
   d.col_idx.assign((size_t)nt * G, -1);
   for (int t = 0; t < nt; ++t)
     std::copy(h->col_idx.begin() + h->tile_col_off[t], h->col_idx.begin() + h->tile_col_off[t + 1],
@@ -303,7 +304,7 @@ void build_device_image(tw_handle_s* h) {
   }
   // one stage of slack behind the last tile: the K-split kernel copies stages of
   // 64 rows and may run one 32-row stage past a tile's end (it never multiplies it)
-  d.row_idx.assign((size_t)d.tile_kp_off[nt] + KSTEP_TW, 0);
+  d.row_idx.assign((size_t)d.tile_kp_off[nt] + KSTEP_I8, 0);
   for (int t = 0; t < nt; ++t) {
     const int k0 = h->tile_k_off[t], kt = h->tile_k_off[t + 1] - k0;
     const int kp0 = d.tile_kp_off[t], kp = d.tile_kp_off[t + 1] - kp0;
@@ -335,6 +336,20 @@ void build_device_image(tw_handle_s* h) {
     d.tile_sched[4 * pos + 1] = d.tile_kp_off[t];
     d.tile_sched[4 * pos + 2] = d.tile_kp_off[t + 1] - d.tile_kp_off[t];
     d.tile_sched[4 * pos + 3] = h->tile_col_off[t + 1] - h->tile_col_off[t];
+  }
+  if (i8) {            // TW only: the condensed rows as bytes
+    d.vals.clear();
+    d.meta.clear();
+    d.vals8.assign(((size_t)d.tile_kp_off[nt] + KSTEP_I8) * G, 0);
+    for (int t = 0; t < nt; ++t) {
+      const int kt = h->tile_k_off[t + 1] - h->tile_k_off[t];
+      const int w = h->tile_col_off[t + 1] - h->tile_col_off[t];
+      const uint16_t* v = h->values.data() + h->val_off[t];
+      int8_t* o = d.vals8.data() + (size_t)d.tile_kp_off[t] * G;
+      for (int j = 0; j < kt; ++j)
+        for (int c = 0; c < w; ++c) o[(size_t)j * G + c] = (int8_t)(int16_t)v[(size_t)j * w + c];
+    }
+    return;
   }
   if (!tvw) {
     d.vals.assign(((size_t)d.tile_kp_off[nt] + KSTEP_TW) * G, 0);

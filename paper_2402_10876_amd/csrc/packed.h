@@ -15,6 +15,7 @@ namespace twg {
 // (two 2:4 sparse matrix-core instructions of 32 logical k each).
 constexpr int KSTEP_TW = 32;
 constexpr int KSTEP_TVW = 64;
+constexpr int KSTEP_I8 = 64;     // int8: one stage = two 32x32x32 matrix-core steps
 
 struct DeviceImage {
   // host staging (filled by the packer)
@@ -25,6 +26,7 @@ struct DeviceImage {
   std::vector<int32_t> tile_order;   // tiles by descending K_t (longest first)
   std::vector<int32_t> tile_sched;   // per launch position: {tile, kp offset, Kp_t, width}
   std::vector<uint16_t> vals;        // TW: [sum Kp_t][G]; TVW: swizzled compressed values
+  std::vector<int8_t> vals8;         // int8 TW: [sum Kp_t][G] bytes (vals is empty then)
   std::vector<uint32_t> meta;        // TVW: swizzled 2-bit position words
   std::vector<int32_t> ew_ptr;       // TEW: N+1 offsets into ew_pairs, by original column
   std::vector<uint32_t> ew_pairs;    // TEW: restored elements, row << 16 | fp16 bits
@@ -38,7 +40,7 @@ struct DeviceImage {
   const int32_t* d_zero_cols = nullptr;
   const int32_t* d_tile_order = nullptr;
   const int32_t* d_tile_sched = nullptr;
-  const uint16_t* d_vals = nullptr;
+  const uint16_t* d_vals = nullptr;  // int8: the byte image, same slot
   const uint32_t* d_meta = nullptr;
   const int32_t* d_ew_ptr = nullptr;
   const uint32_t* d_ew_pairs = nullptr;
@@ -48,6 +50,7 @@ struct DeviceImage {
 
 struct tw_handle_s {
   int32_t K = 0, N = 0, G = 0, pattern = 0;
+  int32_t dtype = TW_DTYPE_F16;      // int8 weights keep their bytes sign-extended in `values`
   int32_t n_kept = 0, n_tiles = 0;
   std::vector<int32_t> col_idx, cto_n, tile_col_off, tile_k_off, row_idx, cto_k;
   std::vector<int64_t> val_off, meta_off;

@@ -10,6 +10,8 @@ paper's 4096 x 4096 x 4096 sparsity sweep (Section VI-B; TVW at 50 % is plain
 tile rows of the matrix instead of one per tile: Section IV "global weight
 pruning", Section V "load imbalance") with the tiles launched longest first and
 in column order.  `--tew` adds the TEW pattern (TW plus delta restored elements).
+`--i8` times the int8 TW path (Section VI-B "Int8 Quantization") against the dense
+int8 baseline and the fp16 TW launch of the same mask.
 """
 from __future__ import annotations
 
@@ -36,6 +38,8 @@ def main():
     ap.add_argument("--imbalance", action="store_true")
     ap.add_argument("--tew", action="store_true",
                     help="TEW at 75 % with delta = 0.5, 1.5 and 5 % on the BERT shapes (Section VI, impact of delta)")
+    ap.add_argument("--i8", action="store_true",
+                    help="int8 TW at 75 % (int8 and int32 outputs) vs the dense int8 baseline")
     ap.add_argument("--reps", type=int, default=24)
     ap.add_argument("--sets", type=int, default=6)
     args = ap.parse_args()
@@ -120,6 +124,48 @@ def main():
                 tw.tw_set_option("tile_order", 1)
                 print(json.dumps(row), flush=True)
             del A, C
+
+    if args.i8:
+        shapes = [(2, si) for si in range(len(wl.SHAPES[2]))] + [(4, 0), (4, 1)]
+        if args.cube:
+            shapes.append((6, 0))
+        for cfg, si in shapes:
+            shp = wl.SHAPES[cfg][si]
+            M, K, N, G = shp.M, shp.K, shp.N, 128
+            nsets = max(2, min(args.sets, int(600e6 // (M * (K + 4 * N)))))
+            B8 = wl.rng_i8(wl.seed_for(cfg, si) + 1, (K, N))
+            for sp in (0.75, 0.875) if cfg != 6 else (0.5, 0.75, 0.875):
+                mask = wl.tw_mask(B8.astype(np.float16), G, density=1.0 - sp, col_frac=0.10)
+                packed = [tw.tw_pack_i8(B8, mask, G) for _ in range(nsets)]
+                p16 = [tw.tw_pack(B8.astype(np.float16), mask, G, tw.PATTERN_TW) for _ in range(nsets)]
+                A8 = [torch.randint(-127, 128, (K, M), dtype=torch.int8, device=dev) for _ in range(nsets)]
+                A16 = [a.to(torch.float16) for a in A8]
+                C32 = [torch.empty((N, M), dtype=torch.int32, device=dev) for _ in range(nsets)]
+                C8 = [torch.empty((N, M), dtype=torch.int8, device=dev) for _ in range(nsets)]
+                C16 = [torch.empty((N, M), dtype=torch.float16, device=dev) for _ in range(nsets)]
+                Bd = torch.from_numpy(B8).to(dev)
+                skw, sk, ku = packed[0].flop_counts()
+                t8 = timed(lambda r: tw.tw_gemm_i8(A8[r % nsets].data_ptr(), M, M, packed[r % nsets],
+                                                   C8[r % nsets].data_ptr(), M, 1, 1e-3, stream), args.reps)
+                t32 = timed(lambda r: tw.tw_gemm_i8(A8[r % nsets].data_ptr(), M, M, packed[r % nsets],
+                                                    C32[r % nsets].data_ptr(), M, 0, 1.0, stream), args.reps)
+                td8 = timed(lambda r: tw.tw_dense_gemm_i8(A8[r % nsets].data_ptr(), Bd.data_ptr(), C8[r % nsets].data_ptr(),
+                                                          M, K, N, M, N, M, 1, 1e-3, stream), args.reps)
+                t16 = timed(lambda r: tw.tw_gemm(A16[r % nsets].data_ptr(), M, M, tw.LAYOUT_KM, p16[r % nsets],
+                                                 C16[r % nsets].data_ptr(), M, stream), args.reps)
+                ab8 = M * ku + M * N + skw + 4 * sk         # int8 A rows, int8 C, condensed bytes, row lists
+                print(json.dumps(dict(
+                    shape=shp.name, M=M, K=K, N=N, G=G, pattern="tw_i8", sparsity=sp, K_union=ku,
+                    us_i8_out=round(t8 * 1e6, 2), us_i32_out=round(t32 * 1e6, 2), dense_i8_us=round(td8 * 1e6, 2),
+                    fp16_tw_us=round(t16 * 1e6, 2), speedup_vs_dense_i8=round(td8 / t8, 3),
+                    speedup_vs_fp16_tw=round(t16 / t8, 3),
+                    dense_eq_tops=round(2.0 * M * K * N / t8 / 1e12, 1),
+                    condensed_mfma_util=round(2.0 * M * skw / t8 / 5.0e15, 4),
+                    alg_MB=round(ab8 / 1e6, 2), alg_GBps=round(ab8 / t8 / 1e9, 1),
+                    roofline_frac=round(max(ab8 / HBM, 2.0 * M * skw / 5.0e15) / t8, 4))), flush=True)
+                for p in packed + p16:
+                    p.free()
+                del A8, A16, C32, C8, C16
 
     if args.tew:
         for cfg, si in ((2, 0), (2, 1), (2, 2), (4, 0), (4, 1)):

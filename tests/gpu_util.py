@@ -84,3 +84,53 @@ def run_dense_mk(tw, A16, B16):
                      tw.LAYOUT_MK, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
     return Cd.cpu().numpy()[:, :N].astype(np.float64)
+
+
+PAD8 = 0x55      # padding byte of int8 operands: any use of it shows up in the sums
+
+
+def to_dev_KM_i8(A8, lda=None):
+    """A (M x K int8) -> device tensor K x lda holding A^T."""
+    torch = _torch()
+    M, K = A8.shape
+    lda = lda or (M + 15) // 16 * 16
+    At = np.full((K, lda), PAD8, np.int8)
+    At[:, :M] = A8.T
+    return torch.from_numpy(At).cuda(), lda
+
+
+def new_C_i8(N, M, c_dtype, ldc=None, fill=-77):
+    torch = _torch()
+    ldc = ldc or (M + 15) // 16 * 16
+    dt = torch.int8 if c_dtype else torch.int32
+    return torch.full((N, ldc), fill, dtype=dt, device="cuda"), ldc
+
+
+def run_tw_i8(tw, packed, A8, N, *, c_dtype=0, scale=1.0, lda=None, ldc=None, fill=-77):
+    """Returns (C as M x N int64, raw N x ldc array)."""
+    torch = _torch()
+    M = A8.shape[0]
+    At, lda = to_dev_KM_i8(A8, lda)
+    Ct, ldc = new_C_i8(N, M, c_dtype, ldc, fill)
+    tw.tw_gemm_i8(At.data_ptr(), M, lda, packed, Ct.data_ptr(), ldc, c_dtype, scale,
+                  torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    raw = Ct.cpu().numpy()
+    return raw[:, :M].T.astype(np.int64), raw
+
+
+def run_dense_i8(tw, A8, B8, *, c_dtype=0, scale=1.0, lda=None, ldb=None, ldc=None, fill=-77):
+    torch = _torch()
+    M, K = A8.shape
+    N = B8.shape[1]
+    At, lda = to_dev_KM_i8(A8, lda)
+    ldb = ldb or (N + 15) // 16 * 16
+    Bp = np.full((K, ldb), PAD8, np.int8)
+    Bp[:, :N] = B8
+    Bd = torch.from_numpy(Bp).cuda()
+    Ct, ldc = new_C_i8(N, M, c_dtype, ldc, fill)
+    tw.tw_dense_gemm_i8(At.data_ptr(), Bd.data_ptr(), Ct.data_ptr(), M, K, N, lda, ldb, ldc, c_dtype, scale,
+                        torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    raw = Ct.cpu().numpy()
+    return raw[:, :M].T.astype(np.int64), raw

@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "twgemm.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = sorted(set(re.findall(r"\b(tw_[a-z_]+)\s*\(", header)))
+    declared = sorted(set(re.findall(r"\b(tw_[a-z0-9_]+)\s*\(", header)))
     assert declared == sorted(tw.EXPORTED_SYMBOLS)
     L = C.CDLL(tw.lib_path())
     for name in declared:

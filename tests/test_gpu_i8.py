@@ -1,0 +1,159 @@
+"""Int8 TW path against the integer oracle, through the C ABI (-m gpu): every sum is
+exact, so every comparison is bit for bit."""
+import numpy as np
+import pytest
+
+import paper_2402_10876_amd as tw
+from oracle import gemm as og
+from tests.helpers import random_tw_mask
+from tests import gpu_util as gu
+import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(autouse=True)
+def _reset_options():
+    tw.tw_set_option("tile_m", 0)
+    yield
+    tw.tw_set_option("tile_m", 0)
+
+
+def _case(seed, M, K, N, G, col_keep=0.8, row_keep=0.5):
+    rng = np.random.default_rng(seed)
+    mask = random_tw_mask(rng, K, N, G, col_keep=col_keep, row_keep=row_keep)
+    return wl.rng_i8(seed, (M, K)), wl.rng_i8(seed + 1, (K, N)), mask
+
+
+@pytest.mark.parametrize("tile_m", [128, 256])
+@pytest.mark.parametrize("G", [64, 128])
+def test_i8_ragged_shapes_int32(G, tile_m):
+    M, K, N = 333, 210, 300                       # all ragged, several tiles in M and N
+    A, B, mask = _case(G + tile_m, M, K, N, G)
+    print(f"i8 ragged G={G} tile_m={tile_m} M={M} K={K} N={N}", flush=True)
+    tw.tw_set_option("tile_m", tile_m)
+    p = tw.tw_pack_i8(B, mask, G)
+    C, raw = gu.run_tw_i8(tw, p, A, N)
+    p.free()
+    assert np.array_equal(C, og.gemm_i8_oracle(A, B, mask))
+    assert (raw[:, M:] == -77).all()              # padding of C untouched
+    assert (raw[~mask.any(0), :M] == 0).all()     # pruned columns are written as 0
+
+
+@pytest.mark.parametrize("G,tile_m", [(128, 128), (64, 256)])
+def test_i8_requantised_output(G, tile_m):
+    M, K, N = 190, 300, 200
+    A, B, mask = _case(7 + G, M, K, N, G)
+    scale = 1.0 / 151.0
+    print(f"i8 requantised G={G} tile_m={tile_m}", flush=True)
+    tw.tw_set_option("tile_m", tile_m)
+    p = tw.tw_pack_i8(B, mask, G)
+    C, raw = gu.run_tw_i8(tw, p, A, N, c_dtype=1, scale=scale)
+    p.free()
+    want = og.requantize_i8(og.gemm_i8_oracle(A, B, mask), scale)
+    assert (want == 127).any() and (want == -128).any() and (np.abs(want) < 100).any()   # clamps and interior both hit
+    assert np.array_equal(C, want.astype(np.int64))
+    assert (raw[:, M:] == -77).all()
+
+
+def test_i8_halves_round_to_even():
+    """scale = 0.5 on sums of known parity: x.5 must go to the even neighbour."""
+    K, N, G, M = 64, 64, 64, 40
+    A = np.zeros((M, K), np.int8)
+    A[:, 0] = np.arange(M) - 20                    # sum = (i - 20) * 1
+    B = np.zeros((K, N), np.int8)
+    B[0, :] = 1
+    mask = np.ones((K, N), np.uint8)
+    p = tw.tw_pack_i8(B, mask, G)
+    C, _ = gu.run_tw_i8(tw, p, A, N, c_dtype=1, scale=0.5)
+    p.free()
+    want = og.requantize_i8(og.gemm_i8_oracle(A, B, mask), 0.5)
+    assert np.array_equal(C, want.astype(np.int64))
+    assert C[21, 0] == 0 and C[23, 0] == 2 and C[17, 0] == -2     # 0.5 -> 0, 1.5 -> 2, -1.5 -> -2
+
+
+def test_i8_extreme_values_do_not_overflow():
+    K, N, G, M = 4096, 128, 128, 130
+    A = np.full((M, K), -128, np.int8)
+    B = np.full((K, N), -128, np.int8)
+    B[:, 1] = 127
+    mask = np.ones((K, N), np.uint8)
+    p = tw.tw_pack_i8(B, mask, G)
+    C, _ = gu.run_tw_i8(tw, p, A, N)
+    p.free()
+    assert (C[:, 0] == 4096 * 16384).all() and (C[:, 1] == -4096 * 128 * 127).all()
+    assert np.array_equal(C, og.gemm_i8_oracle(A, B, mask))
+
+
+def test_i8_identity_A_returns_the_masked_weight():
+    """A = I: C = B (.) mask; pins row and column index lists and the byte layout end to end."""
+    rng = np.random.default_rng(11)
+    K, N, G = 200, 330, 64
+    mask = random_tw_mask(rng, K, N, G)
+    B = wl.rng_i8(11, (K, N))
+    p = tw.tw_pack_i8(B, mask, G)
+    C, _ = gu.run_tw_i8(tw, p, np.eye(K, dtype=np.int8), N)
+    p.free()
+    assert np.array_equal(C, np.where(mask != 0, B, 0).astype(np.int64))
+
+
+def test_i8_degenerate_masks():
+    M, K, N, G = 70, 100, 150, 64
+    A, B = wl.rng_i8(1, (M, K)), wl.rng_i8(2, (K, N))
+    for name, mask in (("nothing kept", np.zeros((K, N), np.uint8)), ("everything kept", np.ones((K, N), np.uint8))):
+        print(f"i8 degenerate: {name}", flush=True)
+        p = tw.tw_pack_i8(B, mask, G)
+        C, _ = gu.run_tw_i8(tw, p, A, N)
+        p.free()
+        assert np.array_equal(C, og.gemm_i8_oracle(A, B, mask))
+    mask = np.zeros((K, N), np.uint8)              # one tile whose columns keep a single row
+    mask[37, 5:40] = 1
+    p = tw.tw_pack_i8(B, mask, G)
+    C, _ = gu.run_tw_i8(tw, p, A, N)
+    p.free()
+    assert np.array_equal(C, og.gemm_i8_oracle(A, B, mask))
+
+
+@pytest.mark.parametrize("c_dtype", [0, 1])
+def test_i8_dense_baseline(c_dtype):
+    M, K, N = 300, 192, 200
+    A, B = wl.rng_i8(5, (M, K)), wl.rng_i8(6, (K, N))
+    scale = 1.0 / 977.0
+    for tile_m in (128, 256):
+        print(f"i8 dense c_dtype={c_dtype} tile_m={tile_m}", flush=True)
+        tw.tw_set_option("tile_m", tile_m)
+        C, raw = gu.run_dense_i8(tw, A, B, c_dtype=c_dtype, scale=scale)
+        want = og.gemm_i8_oracle(A, B, np.ones((K, N), np.uint8))
+        if c_dtype:
+            want = og.requantize_i8(want, scale).astype(np.int64)
+        assert np.array_equal(C, want)
+        assert (raw[:, M:] == -77).all()
+
+
+def test_i8_concat_runs_as_one_launch():
+    rng = np.random.default_rng(21)
+    M, K, G = 150, 130, 128
+    A = wl.rng_i8(20, (M, K))
+    parts, Bs, masks = [], [], []
+    for i, N in enumerate((200, 128, 70)):
+        masks.append(random_tw_mask(rng, K, N, G)); Bs.append(wl.rng_i8(30 + i, (K, N)))
+        parts.append(tw.tw_pack_i8_host(Bs[-1], masks[-1], G))
+    cat = tw.tw_concat(parts)
+    C, _ = gu.run_tw_i8(tw, cat, A, 398)
+    cat.free()
+    assert np.array_equal(C, og.gemm_i8_oracle(A, np.concatenate(Bs, 1), np.concatenate(masks, 1)))
+
+
+def test_i8_full_size_bert_shape_on_sampled_rows():
+    """768 x 3072 at M = 4096 in the launch configuration the sweep times (automatic tile
+    choice), checked on sampled rows of C the oracle computes one by one."""
+    M, K, N, G = 4096, 768, 3072, 128
+    A, B = wl.rng_i8(40, (M, K)), wl.rng_i8(41, (K, N), sigma=30.0)
+    rng = np.random.default_rng(42)
+    mask = random_tw_mask(rng, K, N, G, col_keep=0.5, row_keep=0.5)
+    print("i8 full size 768x3072 M=4096", flush=True)
+    p = tw.tw_pack_i8(B, mask, G)
+    C, _ = gu.run_tw_i8(tw, p, A, N)
+    p.free()
+    rows = np.concatenate([[0, 127, 128, 255, 256, M - 1], rng.integers(0, M, 58)])
+    assert np.array_equal(C[rows], og.gemm_i8_oracle(A[rows], B, mask))

@@ -23,7 +23,7 @@ from dataclasses import dataclass, field
 import numpy as np
 
 __all__ = [
-    "rng_fp16", "make_A", "make_B", "Shape", "SHAPES", "CONFIGS",
+    "rng_fp16", "rng_i8", "make_A", "make_B", "Shape", "SHAPES", "CONFIGS",
     "tw_mask", "tvw_mask", "make_case", "Case", "seed_for",
 ]
 
@@ -36,6 +36,14 @@ def rng_fp16(seed: int, shape, sigma: float = 1.0) -> np.ndarray:
     g = np.random.Generator(np.random.PCG64(int(seed)))
     x = g.standard_normal(size=shape, dtype=np.float32) * np.float32(sigma)
     return x.astype(np.float16)
+
+
+def rng_i8(seed: int, shape, sigma: float = 40.0) -> np.ndarray:
+    """int8 array shaped like a symmetric 8-bit quantisation of normal data: N(0, sigma^2)
+    draws rounded to the nearest integer and clipped to [-127, 127]."""
+    g = np.random.Generator(np.random.PCG64(int(seed)))
+    x = g.standard_normal(size=shape, dtype=np.float32) * np.float32(sigma)
+    return np.clip(np.rint(x), -127, 127).astype(np.int8)
 
 
 def make_A(seed: int, M: int, K: int) -> np.ndarray:
