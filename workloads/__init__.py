@@ -24,7 +24,7 @@ import numpy as np
 
 __all__ = [
     "rng_fp16", "rng_i8", "make_A", "make_B", "Shape", "SHAPES", "CONFIGS",
-    "tw_mask", "tvw_mask", "make_case", "Case", "seed_for",
+    "tw_mask", "tvw_mask", "make_case", "Case", "seed_for", "ConvGeom", "CONV_LAYERS", "make_conv_input",
 ]
 
 
@@ -269,3 +269,55 @@ def make_case(config: int, shape_index: int = 0, *, pattern: str | None = None,
         raise ValueError(pattern)
     return Case(f"{shp.name}_{pattern}{int(round(sparsity * 10000)) / 100:g}_G{G}_{recipe}",
                 M, shp.K, shp.N, G, pattern, sparsity, seed, A, B, mask, tile_mask)
+
+
+# --------------------------------------------------------------------------
+# convolution inputs in the wide layout (config 5's layers before img2col)
+# --------------------------------------------------------------------------
+@dataclass
+class ConvGeom:
+    """C input channels, R x S filter, B images of H x W, stored per channel as B blocks of
+    L lines of P elements (padding included)."""
+    C: int
+    R: int
+    S: int
+    B: int
+    H: int
+    W: int
+    P: int
+    L: int
+
+    @property
+    def Mp(self) -> int:           # positions of the wide grid
+        return self.B * self.L * self.P
+
+    @property
+    def K(self) -> int:
+        return self.C * self.R * self.S
+
+    def ints(self) -> dict:        # keyword arguments of the oracle
+        return dict(R=self.R, S=self.S, B=self.B, H=self.H, W=self.W, P=self.P, L=self.L)
+
+
+def same_geom(C: int, R: int, S: int, B: int, H: int, W: int, pitch_multiple: int = 1) -> ConvGeom:
+    """Block size for a stride-1 'same' convolution: (R-1) extra lines, (S-1) extra columns,
+    the pitch rounded up to `pitch_multiple`."""
+    P = -(-(W + S - 1) // pitch_multiple) * pitch_multiple
+    return ConvGeom(C, R, S, B, H, W, P, H + R - 1)
+
+
+# config 5: VGG-16 3x3 convolutions, batch 8 (M = 8*56*56 and 8*14*14 valid positions)
+CONV_LAYERS = [("vgg16_conv3x3_256_56", same_geom(256, 3, 3, 8, 56, 56), 256),
+               ("vgg16_conv3x3_512_14", same_geom(512, 3, 3, 8, 14, 14), 512)]
+
+
+def make_conv_input(seed: int, g: ConvGeom, ldx: int | None = None) -> np.ndarray:
+    """fp16 C x ldx: N(0,1) pixels, zeros in the padding ((R-1)//2 lines above, (S-1)//2
+    columns left of every image, the rest below / right) and in the slack behind the grid."""
+    ldx = ldx or (g.Mp + 8 + 7) // 8 * 8
+    X = np.zeros((g.C, ldx), np.float16)
+    img = rng_fp16(seed, (g.C, g.B, g.H, g.W), 1.0)
+    blk = X[:, :g.Mp].reshape(g.C, g.B, g.L, g.P)
+    t, l = (g.R - 1) // 2, (g.S - 1) // 2
+    blk[:, :, t:t + g.H, l:l + g.W] = img
+    return X
