@@ -248,6 +248,34 @@ tw_status tw_gemm_i8(const void* A_dev, int M, int lda, tw_handle_t h, void* C_d
 tw_status tw_dense_gemm_i8(const void* A_dev, const void* B_dev, void* C_dev, int M, int K, int N,
                            int lda, int ldb, int ldc, int c_dtype, float scale, void* stream);
 
+/*
+ * Convolution without a materialised img2col matrix (Section VI-A turns a convolution into
+ * C = A x B by img2col; row m of A is the input window of output position m, row
+ * k = (c*R + r)*S + s of the K x N weight is filter tap (r, s) of input channel c).
+ * The input is stored "wide", channel-major, padding included:
+ *     X[c*ldx + b*L*P + yy*P + xx],  c < C, b < B (images), yy < L (lines of an image
+ *     block), xx < P (elements of a line),  L >= H+R-1,  P >= W+S-1.
+ * Output position m = b*L*P + y*P + x is an output pixel iff y < H and x < W; its window is
+ * X[c][m + r*P + s], so row k of A is the run of X that starts r*P + s elements into channel
+ * c, and the kernel gathers it from there.  C is N x ldc with all B*L*P positions of the wide
+ * grid: output pixels hold the convolution, the other positions +0 (where the zeros of a
+ * zero-padded layout sit depends on the caller's (R-1)/2, (S-1)/2 shift; this call does not
+ * care), pruned output channels +0.
+ *
+ * tw_conv_bind - fix the geometry for an uploaded fp16 TW or TVW handle with K = C*R*S
+ *   (the per-tile kept-row lists become element offsets on the device; allocates; binding
+ *   again replaces the previous geometry).  ldx >= roundup8(B*L*P) + (R-1)*P + S-1 so that
+ *   the windows of the last positions stay inside channel rows of ldx elements; C*ldx < 2^31.
+ *   Errors: TW_ERR_ARG, TW_ERR_STATE (not uploaded), TW_ERR_UNSUPPORTED (G = 32, TEW, int8),
+ *   TW_ERR_ALLOC, TW_ERR_HIP.
+ * tw_conv_gemm - the launch.  X_dev fp16, C rows of ldx elements, 16-byte aligned; C_dev fp16
+ *   N x ldc, ldc >= B*L*P, multiple of 8, 16-byte aligned.  Asynchronous on `stream`,
+ *   allocates nothing.  Errors: TW_ERR_ARG, TW_ERR_STATE (no geometry bound), TW_ERR_HIP.
+ */
+typedef struct { int32_t C, R, S, B, H, W, P, L; } tw_conv_geom;
+tw_status tw_conv_bind(tw_handle_t h, const tw_conv_geom* geom, int64_t ldx);
+tw_status tw_conv_gemm(const void* X_dev, tw_handle_t h, void* C_dev, int ldc, void* stream);
+
 /* tw_export - fill *out with the logical view (host pointers owned by h). */
 tw_status tw_export(tw_handle_t h, tw_packed_view* out);
 

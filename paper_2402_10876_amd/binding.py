@@ -17,7 +17,7 @@ EXPORTED_SYMBOLS = [
     "tw_pack_host", "tw_upload", "tw_pack", "tw_pack_dev", "tw_prune_dev",
     "tw_prune_workspace_bytes", "tw_concat", "tw_gemm", "tw_dense_gemm", "tw_export",
     "tw_unpack", "tw_free", "tw_status_str", "tw_set_option", "tw_flop_counts",
-    "tw_pack_i8_host", "tw_pack_i8", "tw_gemm_i8", "tw_dense_gemm_i8",
+    "tw_pack_i8_host", "tw_pack_i8", "tw_gemm_i8", "tw_dense_gemm_i8", "tw_conv_bind", "tw_conv_gemm",
 ]
 
 _lib = None
@@ -74,6 +74,8 @@ def lib():
         L.tw_gemm_i8.argtypes = [vp, i, i, vp, vp, i, i, C.c_float, vp]
         L.tw_dense_gemm_i8.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, C.c_float, vp]
         L.tw_dense_gemm.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, vp]
+        L.tw_conv_bind.argtypes = [vp, C.POINTER(_ConvGeom), C.c_int64]
+        L.tw_conv_gemm.argtypes = [vp, vp, vp, i, vp]
         L.tw_export.argtypes = [vp, C.POINTER(_View)]
         L.tw_unpack.argtypes = [vp, vp, vp]
         L.tw_free.argtypes = [vp]
@@ -93,6 +95,10 @@ def _check(st: int, what: str):
 
 def _host_ptr(a):
     return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+class _ConvGeom(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("C", "R", "S", "B", "H", "W", "P", "L")]
 
 
 class PackedWeight:
@@ -282,6 +288,16 @@ def tw_dense_gemm_i8(A_ptr: int, B_ptr: int, C_ptr: int, M: int, K: int, N: int,
                      ldc: int, c_dtype: int = 0, scale: float = 1.0, stream: int = 0):
     _check(lib().tw_dense_gemm_i8(A_ptr, B_ptr, C_ptr, M, K, N, lda, ldb, ldc, c_dtype, scale, stream),
            "tw_dense_gemm_i8")
+
+
+def tw_conv_bind(packed: PackedWeight, geom, ldx: int):
+    """geom: anything with integer attributes C, R, S, B, H, W, P, L (see tw_conv_geom)."""
+    g = _ConvGeom(*(int(getattr(geom, n)) for n in ("C", "R", "S", "B", "H", "W", "P", "L")))
+    _check(lib().tw_conv_bind(packed.handle, C.byref(g), int(ldx)), "tw_conv_bind")
+
+
+def tw_conv_gemm(X_ptr: int, packed: PackedWeight, C_ptr: int, ldc: int, stream: int = 0):
+    _check(lib().tw_conv_gemm(X_ptr, packed.handle, C_ptr, ldc, stream), "tw_conv_gemm")
 
 
 def tw_set_option(name: str, value: int):

@@ -25,16 +25,20 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 
 
 // M-tile heuristic: the largest tile that still gives every CU (256 of them)
 // about two workgroups; long K loops (matrix-core bound) accept fewer, larger
-// workgroups, small problems fall back to smaller tiles.
+// workgroups, small problems fall back to smaller tiles.  Short K loops with one
+// and a half workgroups per CU still take the larger tile (128 rows; 256 for G = 64):
+// they are bound by the L2 -> LDS traffic, which is (tm + G) / (tm G) per product
+// (measured on the 3 x 3 convolution 256 -> 256 at 56 x 56: 17.0 against 21.7 us).
 int pick_tile_m(int M, int n_tiles, int G, int max_k) {
   const int forced = opt_tile_m.load();
   if (forced == 64 || forced == 128 || forced == 256) {
     if (!(G == 32 && forced == 64)) return forced;
   }
-  const long need = max_k >= 768 ? 320 : 512;
   const int cand[3] = {256, 128, 64};
   for (int tm : cand) {
     if (G == 32 && tm == 64) break;
+    long need = max_k >= 768 ? 320 : 512;
+    if (need == 512 && (tm == 128 || (tm == 256 && G == 64))) need = 384;
     const long wgs = (long)((M + tm - 1) / tm) * n_tiles;
     if (wgs >= need) return tm;
   }
@@ -237,23 +241,18 @@ tw_status tw_concat(const tw_handle_t* parts, int n, int upload, tw_handle_t* ou
   return TW_OK;
 }
 
-tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void* C, int ldc,
-                  void* stream) {
-  if (!A || !C || !h || M < 1) return TW_ERR_ARG;
-  if (layout != TW_LAYOUT_KM && layout != TW_LAYOUT_MK) return TW_ERR_ARG;
-  if (!aligned16(A) || !aligned16(C) || lda % 8 || ldc % 8) return TW_ERR_ARG;
-  if (h->dtype != TW_DTYPE_F16) return TW_ERR_ARG;
-  if (!h->img.blob) return TW_ERR_STATE;
-  if (layout == TW_LAYOUT_MK) {
-    if (lda < h->K || ldc < h->N) return TW_ERR_ARG;
-    if (h->pattern != TW_PATTERN_TW) return TW_ERR_UNSUPPORTED;   // TVW and TEW exist for K x M only
-  } else if (lda < M || ldc < M) {
-    return TW_ERR_ARG;
-  }
+// The launch behind tw_gemm and tw_conv_gemm.  conv: A is the wide input, the row list holds
+// window offsets (lda = 1) and M counts the wide grid.
+static tw_status gemm_launch(const void* A, int M, int lda, int layout, tw_handle_t h, void* C, int ldc,
+                             void* stream, bool conv) {
   twg::GemmArgs g{};
   g.A = (const _Float16*)A; g.C = (_Float16*)C; g.M = M; g.lda = lda; g.ldc = ldc;
   g.vals = (const _Float16*)h->img.d_vals;
   g.row_idx = h->img.d_row_idx; g.tile_kp_off = h->img.d_tile_kp_off;
+  if (conv) {
+    g.row_idx = h->d_conv_off;
+    g.conv_P = h->conv.P; g.conv_L = h->conv.L; g.conv_H = h->conv.H; g.conv_W = h->conv.W;
+  }
   g.col_idx = h->img.d_col_idx; g.tile_order = h->img.d_tile_order;
   g.tile_sched = h->img.d_tile_sched;
   g.zero_cols = h->img.d_zero_cols; g.n_zero = (int)h->img.zero_cols.size();
@@ -277,15 +276,17 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
     return e == hipSuccess ? TW_OK : TW_ERR_HIP;
   }
   int tm = pick_tile_m(M, h->n_tiles > 0 ? h->n_tiles : 1, h->G, h->max_kp);
-  if (h->pattern == TW_PATTERN_TEW && h->G == 64 && tm == 64) tm = 128;   // no 64 x 64 instance there
+  // no 64 x 64 instance of the asynchronous kernel (tried: one matrix instruction per wave and
+  // k-step is too little work per barrier; plain TW falls back to the register-staged kernel)
+  if ((h->pattern == TW_PATTERN_TEW || conv) && h->G == 64 && tm == 64) tm = 128;
   hipError_t e = hipErrorInvalidValue;
   // TEW: the same kernels with the restored elements added in the epilogue (3 stages only)
   const bool tew = h->pattern == TW_PATTERN_TEW;
   auto launch_dma = tew ? twg::launch_tew_km_dma : twg::launch_tw_km_dma;
   const int depth = tew ? 3 : opt_depth.load();
   // the asynchronous kernel addresses A with 32-bit byte offsets
-  const bool a_fits32 = (unsigned long long)h->K * (unsigned long long)lda * 2ull < (1ull << 32);
-  if ((opt_kernel.load() != 1 || tew) && h->G != 32 && a_fits32) {
+  const bool a_fits32 = conv || (unsigned long long)h->K * (unsigned long long)lda * 2ull < (1ull << 32);
+  if ((opt_kernel.load() != 1 || tew || conv) && h->G != 32 && a_fits32) {
     // long K with too few tiles to fill the chip: split K inside the workgroup
     // 256-row tiles run with 8 waves (64 x 64 per wave): half the registers per wave, two
     // workgroups per CU
@@ -294,14 +295,75 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
     const int ks = opt_ksplit.load();
     if (ks == 2 || (ks == 0 && use_ksplit(M, h->n_tiles, h->max_kp, &tmk))) variant = twg::DMA_KSPLIT2;
     if (variant == twg::DMA_KSPLIT2 && ks == 2) tmk = tm == 256 ? 128 : tm;
+    if (variant == twg::DMA_KSPLIT2 && h->G == 64 && conv) tmk = 128;   // the one K-split instance for G = 64
     e = launch_dma(h->G, variant == twg::DMA_KSPLIT2 ? tmk : tm, depth, variant, g, (hipStream_t)stream);
     if (e == hipErrorInvalidValue && variant != twg::DMA_WAVES4)
       e = launch_dma(h->G, tm, depth, twg::DMA_WAVES4, g, (hipStream_t)stream);
   }
-  if (e == hipErrorInvalidValue && opt_kernel.load() != 2 && !tew)
+  if (e == hipErrorInvalidValue && opt_kernel.load() != 2 && !tew && !conv)
     e = twg::launch_tw_km(h->G, tm, g, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;
+}
+
+tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void* C, int ldc,
+                  void* stream) {
+  if (!A || !C || !h || M < 1) return TW_ERR_ARG;
+  if (layout != TW_LAYOUT_KM && layout != TW_LAYOUT_MK) return TW_ERR_ARG;
+  if (!aligned16(A) || !aligned16(C) || lda % 8 || ldc % 8) return TW_ERR_ARG;
+  if (h->dtype != TW_DTYPE_F16) return TW_ERR_ARG;
+  if (!h->img.blob) return TW_ERR_STATE;
+  if (layout == TW_LAYOUT_MK) {
+    if (lda < h->K || ldc < h->N) return TW_ERR_ARG;
+    if (h->pattern != TW_PATTERN_TW) return TW_ERR_UNSUPPORTED;   // TVW and TEW exist for K x M only
+  } else if (lda < M || ldc < M) {
+    return TW_ERR_ARG;
+  }
+  return gemm_launch(A, M, lda, layout, h, C, ldc, stream, false);
+}
+
+tw_status tw_conv_bind(tw_handle_t h, const tw_conv_geom* cg, int64_t ldx) {
+  if (!h || !cg) return TW_ERR_ARG;
+  if (cg->C < 1 || cg->R < 1 || cg->S < 1 || cg->B < 1 || cg->H < 1 || cg->W < 1) return TW_ERR_ARG;
+  if (cg->P < cg->W + cg->S - 1 || cg->L < cg->H + cg->R - 1) return TW_ERR_ARG;
+  if ((int64_t)cg->C * cg->R * cg->S != h->K) return TW_ERR_ARG;
+  const int64_t Mp = (int64_t)cg->B * cg->L * cg->P;
+  if (Mp > INT32_MAX - 8) return TW_ERR_ARG;
+  const int64_t reach = (Mp + 7) / 8 * 8 + (int64_t)(cg->R - 1) * cg->P + cg->S - 1;
+  if (ldx < reach || ldx % 8 || (int64_t)cg->C * ldx >= (1ll << 31)) return TW_ERR_ARG;
+  if (h->dtype != TW_DTYPE_F16 || h->pattern == TW_PATTERN_TEW || h->G == 32) return TW_ERR_UNSUPPORTED;
+  if (!h->img.blob) return TW_ERR_STATE;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return TW_ERR_HIP;
+  if (dev != h->img.device) return TW_ERR_STATE;
+  std::vector<int32_t> off;
+  try {
+    off.resize(h->img.row_idx.size());
+  } catch (const std::bad_alloc&) {
+    return TW_ERR_ALLOC;
+  }
+  const int RS = cg->R * cg->S;
+  for (size_t i = 0; i < off.size(); ++i) {
+    const int k = h->img.row_idx[i], c = k / RS, r = (k % RS) / cg->S, s = k % cg->S;
+    off[i] = (int32_t)((int64_t)c * ldx + (int64_t)r * cg->P + s);
+  }
+  int32_t* d = nullptr;
+  if (hipMalloc((void**)&d, off.size() * 4 + 4) != hipSuccess) { (void)hipGetLastError(); return TW_ERR_ALLOC; }
+  if (hipMemcpy(d, off.data(), off.size() * 4, hipMemcpyHostToDevice) != hipSuccess) {
+    (void)hipFree(d);
+    return TW_ERR_HIP;
+  }
+  if (h->d_conv_off) (void)hipFree(h->d_conv_off);
+  h->d_conv_off = d; h->conv = *cg; h->conv_ldx = ldx;
+  return TW_OK;
+}
+
+tw_status tw_conv_gemm(const void* X, tw_handle_t h, void* C, int ldc, void* stream) {
+  if (!X || !C || !h) return TW_ERR_ARG;
+  if (!h->d_conv_off) return TW_ERR_STATE;
+  const int Mp = h->conv.B * h->conv.L * h->conv.P;
+  if (!aligned16(X) || !aligned16(C) || ldc % 8 || ldc < Mp) return TW_ERR_ARG;
+  return gemm_launch(X, Mp, 1, TW_LAYOUT_KM, h, C, ldc, stream, true);
 }
 
 tw_status tw_dense_gemm(const void* A, const void* B, void* C, int M, int K, int N, int lda,
@@ -424,6 +486,7 @@ tw_status tw_free(tw_handle_t h) {
   if (!h) return TW_OK;
   tw_status st = TW_OK;
   if (h->img.blob && hipFree(h->img.blob) != hipSuccess) st = TW_ERR_HIP;
+  if (h->d_conv_off && hipFree(h->d_conv_off) != hipSuccess) st = TW_ERR_HIP;
   delete h;
   return st;
 }

@@ -112,6 +112,24 @@ __device__ __forceinline__ void tile_of_workgroup(const Args& g, int bid, int n_
   t = lid - mt * g.n_tiles;
 }
 
+// Implicit img2col: which of the 8 wide-grid positions m .. m+7 are output pixels (x < W and
+// y < H); all-ones halves for those, zero for the padding lanes.  One division per thread.
+__device__ __forceinline__ u32x4 conv_valid_mask(const GemmArgs& g, int m) {
+  const uint32_t P = (uint32_t)g.conv_P, L = (uint32_t)g.conv_L;
+  const uint32_t line = (uint32_t)m / P;
+  uint32_t x = (uint32_t)m - line * P, y = line % L;
+  uint32_t h[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    h[e] = (x < (uint32_t)g.conv_W && y < (uint32_t)g.conv_H) ? 0xffffu : 0u;
+    if (++x == P) { x = 0; if (++y == L) y = 0; }
+  }
+  u32x4 v;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) v[j] = h[2 * j] | (h[2 * j + 1] << 16);
+  return v;
+}
+
 // Extra workgroups of a launch write +0 into one pruned column of C each.
 __device__ __forceinline__ void zero_fill_column(const GemmArgs& g, int which) {
   const int col = g.zero_cols[which];

@@ -530,15 +530,20 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
       ck[i].h[0] = *(const uint2*)(lds + n * CS + c * 16);
       ck[i].h[1] = *(const uint2*)(lds + n * CS + c * 16 + 8);
     }
+    // implicit img2col: the padding lanes of the wide grid are written as +0 (uniform branch)
+    u32x4 vm = {~0u, ~0u, ~0u, ~0u};
+    if (g.conv_P) vm = conv_valid_mask(g, m);
 #pragma unroll
     for (int i = 0; i < NPASS; ++i) {
       if (dst_off[i] < 0) continue;
       _Float16* dst = g.C + dst_off[i];
-      if (m + 8 <= g.M) __builtin_nontemporal_store(ck[i].v, (u32x4*)dst);
+      if (m + 8 <= g.M) __builtin_nontemporal_store(ck[i].v & vm, (u32x4*)dst);
       else {
         const int n = r0 + i * ROWS_PER_PASS;
-        const _Float16* e = (const _Float16*)(lds + n * CS + c * 16);
-        for (int qq = 0; m + qq < g.M; ++qq) dst[qq] = e[qq];
+        const uint16_t* e = (const uint16_t*)(lds + n * CS + c * 16);
+#pragma unroll
+        for (int qq = 0; qq < 8; ++qq)
+          if (m + qq < g.M) ((uint16_t*)dst)[qq] = e[qq] & (uint16_t)(vm[qq >> 1] >> (16 * (qq & 1)));
       }
     }
   }
@@ -550,6 +555,7 @@ template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KS
 static hipError_t launch(const GemmArgs& g, hipStream_t stream) {
   const int grid = g.n_mtiles * g.n_tiles + g.n_zero;
   if (grid <= 0) return hipSuccess;
+  (void)hipGetLastError();   // an error left behind by an earlier call of this thread is not this launch's
   hipLaunchKernelGGL((tw_gemm_km_dma_kernel<TM, TN, WAVES_M, D, DENSE, NWAVES, KSPLIT, EW>), dim3(grid),
                      dim3(NWAVES * 64), 0, stream, g);
   return hipGetLastError();

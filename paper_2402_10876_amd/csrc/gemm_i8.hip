@@ -392,6 +392,7 @@ template <int TM, int TN, int WAVES_M, bool DENSE>
 static hipError_t launch8(const GemmI8Args& g, hipStream_t stream) {
   const int grid = g.n_mtiles * g.n_tiles + g.n_zero;
   if (grid <= 0) return hipSuccess;
+  (void)hipGetLastError();   // an error left behind by an earlier call of this thread is not this launch's
   if (g.c_i8)
     hipLaunchKernelGGL((tw_gemm_i8_kernel<TM, TN, WAVES_M, DENSE, true>), dim3(grid), dim3(256), 0, stream, g);
   else

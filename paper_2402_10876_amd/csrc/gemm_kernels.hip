@@ -305,6 +305,7 @@ template <int TM, int TN, int WAVES_M, bool DENSE, bool MK>
 static hipError_t launch(const GemmArgs& g, hipStream_t stream) {
   const int grid = g.n_mtiles * g.n_tiles + g.n_zero;
   if (grid <= 0) return hipSuccess;
+  (void)hipGetLastError();   // an error left behind by an earlier call of this thread is not this launch's
   hipLaunchKernelGGL((tw_gemm_km_kernel<TM, TN, WAVES_M, DENSE, MK>), dim3(grid), dim3(NTHREADS),
                      0, stream, g);
   return hipGetLastError();

@@ -26,6 +26,10 @@ struct GemmArgs {
   int n_tiles, n_mtiles;
   int K, N;                      // dense only
   int xcd_map;
+  // Implicit img2col (0 = off): the "rows" of A are window shifts into a wide input (row list =
+  // element offsets, lda = 1) and M counts the positions of the wide grid, P per line, L lines
+  // per image block; positions with x >= W or y >= H are written as +0.
+  int conv_P, conv_L, conv_H, conv_W;
 #ifdef TWG_TRACE
   int trace_slot;                // developer build: which of two trace buffers this launch writes
 #endif

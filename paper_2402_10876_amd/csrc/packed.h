@@ -62,6 +62,11 @@ struct tw_handle_s {
   int32_t k_union = 0;  // K rows kept by at least one tile
   int32_t max_kp = 0;  // largest padded K_t
   twg::DeviceImage img;
+  // implicit img2col binding (tw_conv_bind): geometry and the device list of window offsets
+  // parallel to img.row_idx
+  tw_conv_geom conv{};
+  int64_t conv_ldx = 0;
+  int32_t* d_conv_off = nullptr;
 };
 
 namespace twg {

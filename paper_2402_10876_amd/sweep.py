@@ -10,6 +10,8 @@ paper's 4096 x 4096 x 4096 sparsity sweep (Section VI-B; TVW at 50 % is plain
 tile rows of the matrix instead of one per tile: Section IV "global weight
 pruning", Section V "load imbalance") with the tiles launched longest first and
 in column order.  `--tew` adds the TEW pattern (TW plus delta restored elements).
+`--conv` times config 5's convolutions with the img2col matrix never materialised
+(`tw_conv_gemm` on the wide input) against the same handle on the materialised matrix.
 `--i8` times the int8 TW path (Section VI-B "Int8 Quantization") against the dense
 int8 baseline and the fp16 TW launch of the same mask.
 """
@@ -38,6 +40,8 @@ def main():
     ap.add_argument("--imbalance", action="store_true")
     ap.add_argument("--tew", action="store_true",
                     help="TEW at 75 % with delta = 0.5, 1.5 and 5 % on the BERT shapes (Section VI, impact of delta)")
+    ap.add_argument("--conv", action="store_true",
+                    help="implicit img2col (tw_conv_gemm) vs the materialised matrix on the VGG layers")
     ap.add_argument("--i8", action="store_true",
                     help="int8 TW at 75 % (int8 and int32 outputs) vs the dense int8 baseline")
     ap.add_argument("--reps", type=int, default=24)
@@ -124,6 +128,43 @@ def main():
                 tw.tw_set_option("tile_order", 1)
                 print(json.dumps(row), flush=True)
             del A, C
+
+    if args.conv:
+        for si, (name, g, N) in enumerate(wl.CONV_LAYERS):
+            M, K, Mp, ldx = g.B * g.H * g.W, g.K, g.Mp, wl.conv_ldx(g)
+            ns_conv = max(2, min(24, int(600e6 // (2 * (g.C * ldx + N * Mp)))))
+            ns_mat = max(2, min(args.sets, int(600e6 // (2 * M * (K + N)))))
+            X = [torch.randn((g.C, ldx), dtype=torch.float16, device=dev) for _ in range(ns_conv)]
+            Cw = [torch.empty((N, Mp), dtype=torch.float16, device=dev) for _ in range(ns_conv)]
+            A = [torch.randn((K, M), dtype=torch.float16, device=dev) for _ in range(ns_mat)]
+            Cm = [torch.empty((N, M), dtype=torch.float16, device=dev) for _ in range(ns_mat)]
+            for pattern, sp, G in (("tw", 0.75, 128), ("tw", 0.75, 64), ("tvw", 0.875, 128), ("tw", 0.0, 128)):
+                c = wl.make_case(5, si, pattern=pattern, sparsity=sp, G=G, col_frac=0.0 if sp == 0.0 else None,
+                                 with_A=False)
+                pat = tw.PATTERN_TW if pattern == "tw" else tw.PATTERN_TVW
+                packed = [tw.tw_pack(c.B, c.mask, G, pat, tile_mask=c.tile_mask if pattern != "tw" else None)
+                          for _ in range(ns_conv)]
+                for p in packed:
+                    tw.tw_conv_bind(p, g, ldx)
+                skw, sk, ku = packed[0].flop_counts()
+                t_conv = timed(lambda r: tw.tw_conv_gemm(X[r % ns_conv].data_ptr(), packed[r % ns_conv],
+                                                         Cw[r % ns_conv].data_ptr(), Mp, stream), args.reps)
+                t_mat = timed(lambda r: tw.tw_gemm(A[r % ns_mat].data_ptr(), M, M, tw.LAYOUT_KM, packed[r % ns_mat],
+                                                   Cm[r % ns_mat].data_ptr(), M, stream), args.reps)
+                wbytes = 2 * skw if pattern == "tw" else skw + skw // 8
+                ab = 2 * g.C * Mp + 2 * N * Mp + wbytes + 4 * sk       # the input once, C over the wide grid, weight
+                print(json.dumps(dict(
+                    shape=name, positions=M, wide_grid=Mp, K=K, N=N, G=G, pattern=pattern, sparsity=sp,
+                    us_implicit=round(t_conv * 1e6, 2), us_materialised=round(t_mat * 1e6, 2),
+                    speedup_vs_materialised=round(t_mat / t_conv, 3),
+                    dense_eq_tflops=round(2.0 * M * K * N / t_conv / 1e12, 1),
+                    input_MB=round(2 * g.C * Mp / 1e6, 2), materialised_A_MB=round(2 * M * ku / 1e6, 2),
+                    alg_MB=round(ab / 1e6, 2), alg_GBps=round(ab / t_conv / 1e9, 1),
+                    roofline_frac=round(max(ab / HBM, (1.0 if pattern == "tvw" else 2.0) * Mp * skw / MFMA) / t_conv, 4))),
+                    flush=True)
+                for p in packed:
+                    p.free()
+            del X, Cw, A, Cm
 
     if args.i8:
         shapes = [(2, si) for si in range(len(wl.SHAPES[2]))] + [(4, 0), (4, 1)]

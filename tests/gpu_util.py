@@ -134,3 +134,17 @@ def run_dense_i8(tw, A8, B8, *, c_dtype=0, scale=1.0, lda=None, ldb=None, ldc=No
     torch.cuda.synchronize()
     raw = Ct.cpu().numpy()
     return raw[:, :M].T.astype(np.int64), raw
+
+
+def run_conv(tw, packed, X16, geom, N, *, ldc=None, fill=float("nan")):
+    """Implicit-img2col launch: X16 is C x ldx (wide layout).  Returns (C over the wide grid as
+    Mp x N float64, raw N x ldc fp16 array)."""
+    torch = _torch()
+    Mp = geom.Mp
+    Xd = torch.from_numpy(np.ascontiguousarray(X16)).cuda()
+    tw.tw_conv_bind(packed, geom, X16.shape[1])
+    Ct, ldc = new_C(N, Mp, ldc, fill)
+    tw.tw_conv_gemm(Xd.data_ptr(), packed, Ct.data_ptr(), ldc, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    raw = Ct.cpu().numpy()
+    return raw[:, :Mp].T.astype(np.float64), raw

@@ -24,7 +24,7 @@ import numpy as np
 
 __all__ = [
     "rng_fp16", "rng_i8", "make_A", "make_B", "Shape", "SHAPES", "CONFIGS",
-    "tw_mask", "tvw_mask", "make_case", "Case", "seed_for", "ConvGeom", "CONV_LAYERS", "make_conv_input",
+    "tw_mask", "tvw_mask", "make_case", "Case", "seed_for", "ConvGeom", "same_geom", "conv_ldx", "CONV_LAYERS", "make_conv_input",
 ]
 
 
@@ -311,10 +311,16 @@ CONV_LAYERS = [("vgg16_conv3x3_256_56", same_geom(256, 3, 3, 8, 56, 56), 256),
                ("vgg16_conv3x3_512_14", same_geom(512, 3, 3, 8, 14, 14), 512)]
 
 
+def conv_ldx(g: ConvGeom) -> int:
+    """Shortest channel row (multiple of 8) in which the windows of every wide-grid position,
+    padding lanes included, stay inside the row."""
+    return ((g.Mp + 7) // 8 * 8 + (g.R - 1) * g.P + g.S - 1 + 7) // 8 * 8
+
+
 def make_conv_input(seed: int, g: ConvGeom, ldx: int | None = None) -> np.ndarray:
     """fp16 C x ldx: N(0,1) pixels, zeros in the padding ((R-1)//2 lines above, (S-1)//2
     columns left of every image, the rest below / right) and in the slack behind the grid."""
-    ldx = ldx or (g.Mp + 8 + 7) // 8 * 8
+    ldx = ldx or conv_ldx(g)
     X = np.zeros((g.C, ldx), np.float16)
     img = rng_fp16(seed, (g.C, g.B, g.H, g.W), 1.0)
     blk = X[:, :g.Mp].reshape(g.C, g.B, g.L, g.P)
