@@ -216,10 +216,11 @@ tw_status tw_dense_gemm(const void* A_dev, const void* B_dev, void* C_dev,
 /*
  * Int8 (Section VI-B "Int8 Quantization": the pattern is independent of the
  * element type, the matrix cores run the same condensed product on int8
- * operands with int32 sums).  TW pattern, TW_LAYOUT_KM only.
+ * operands with int32 sums).  TW and TVW patterns, TW_LAYOUT_KM only.
  *
  * tw_pack_i8_host / tw_pack_i8 - as tw_pack_host / tw_pack for a K x N row-major
- *   int8 weight (ldb = N) and a TW mask.  Same errors.  The handle works with
+ *   int8 weight (ldb = N); pattern TW or TVW (TEW: TW_ERR_UNSUPPORTED), tile_mask as
+ *   there.  Same errors.  The handle works with
  *   tw_upload, tw_concat (members of one dtype), tw_export (see `dtype`),
  *   tw_unpack (values sign-extended to 16 bits), tw_flop_counts and tw_free;
  *   tw_gemm refuses it (TW_ERR_ARG), as tw_gemm_i8 refuses an fp16 handle.
@@ -239,10 +240,11 @@ tw_status tw_dense_gemm(const void* A_dev, const void* B_dev, void* C_dev,
  *   B_dev K x N row-major int8, ldb >= N, multiple of 16, 16-byte aligned;
  *   K % 64 != 0 gives TW_ERR_UNSUPPORTED.
  */
-tw_status tw_pack_i8_host(const int8_t* B_host, const uint8_t* mask_host, int K, int N, int G,
+tw_status tw_pack_i8_host(const int8_t* B_host, const uint8_t* mask_host,
+                          const uint8_t* tile_mask_host, int K, int N, int G, int pattern,
                           tw_handle_t* out);
-tw_status tw_pack_i8(const int8_t* B_host, const uint8_t* mask_host, int K, int N, int G,
-                     tw_handle_t* out);
+tw_status tw_pack_i8(const int8_t* B_host, const uint8_t* mask_host, const uint8_t* tile_mask_host,
+                     int K, int N, int G, int pattern, tw_handle_t* out);
 tw_status tw_gemm_i8(const void* A_dev, int M, int lda, tw_handle_t h, void* C_dev, int ldc,
                      int c_dtype, float scale, void* stream);
 tw_status tw_dense_gemm_i8(const void* A_dev, const void* B_dev, void* C_dev, int M, int K, int N,

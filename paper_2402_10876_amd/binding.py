@@ -69,7 +69,7 @@ def lib():
         L.tw_prune_dev.argtypes = [vp, i, i, i, i, i, i, i, vp, vp, vp, C.c_size_t, vp]
         L.tw_pack_dev.argtypes = [vp, i, vp, vp, i, i, i, i, vp, C.POINTER(vp)]
         L.tw_gemm.argtypes = [vp, i, i, i, vp, vp, i, vp]
-        L.tw_pack_i8_host.argtypes = [vp, vp, i, i, i, C.POINTER(vp)]
+        L.tw_pack_i8_host.argtypes = [vp, vp, vp, i, i, i, i, C.POINTER(vp)]
         L.tw_pack_i8.argtypes = L.tw_pack_i8_host.argtypes
         L.tw_gemm_i8.argtypes = [vp, i, i, vp, vp, i, i, C.c_float, vp]
         L.tw_dense_gemm_i8.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, C.c_float, vp]
@@ -215,25 +215,30 @@ def tw_pack(B16, mask, G, pattern, tile_mask=None) -> PackedWeight:
     return _pack("tw_pack", B16, mask, G, pattern, tile_mask)
 
 
-def _pack_i8(fn_name, B8, mask, G):
+def _pack_i8(fn_name, B8, mask, G, pattern, tile_mask):
     B8 = np.ascontiguousarray(B8)
     if B8.dtype != np.int8:
         raise TypeError("B must be int8")
     mask = np.ascontiguousarray(mask, dtype=np.uint8)
     if mask.shape != B8.shape or B8.ndim != 2:
         raise ValueError("B and mask must be K x N")
+    if tile_mask is not None:
+        tile_mask = np.ascontiguousarray(tile_mask, dtype=np.uint8)
+        if tile_mask.shape != B8.shape:
+            raise ValueError("tile_mask must be K x N")
     K, N = B8.shape
     h = C.c_void_p()
-    _check(getattr(lib(), fn_name)(_host_ptr(B8), _host_ptr(mask), K, N, int(G), C.byref(h)), fn_name)
+    _check(getattr(lib(), fn_name)(_host_ptr(B8), _host_ptr(mask), _host_ptr(tile_mask), K, N, int(G),
+                                   int(pattern), C.byref(h)), fn_name)
     return PackedWeight(h)
 
 
-def tw_pack_i8_host(B8, mask, G) -> PackedWeight:
-    return _pack_i8("tw_pack_i8_host", B8, mask, G)
+def tw_pack_i8_host(B8, mask, G, pattern=PATTERN_TW, tile_mask=None) -> PackedWeight:
+    return _pack_i8("tw_pack_i8_host", B8, mask, G, pattern, tile_mask)
 
 
-def tw_pack_i8(B8, mask, G) -> PackedWeight:
-    return _pack_i8("tw_pack_i8", B8, mask, G)
+def tw_pack_i8(B8, mask, G, pattern=PATTERN_TW, tile_mask=None) -> PackedWeight:
+    return _pack_i8("tw_pack_i8", B8, mask, G, pattern, tile_mask)
 
 
 def tw_prune_workspace_bytes(K: int, N: int, G: int) -> int:

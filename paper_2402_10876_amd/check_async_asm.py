@@ -26,7 +26,7 @@ from concurrent.futures import ThreadPoolExecutor
 PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-KERNEL_SOURCES = ["gemm_kernels.hip", "gemm_dma.hip", "gemm_tvw.hip", "gemm_i8.hip"]
+KERNEL_SOURCES = ["gemm_kernels.hip", "gemm_dma.hip", "gemm_tvw.hip", "gemm_i8.hip", "gemm_tvw_i8.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "--cuda-device-only", "-S", "-Wno-unused-command-line-argument"]
 

@@ -155,10 +155,13 @@ tw_status tw_pack(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_ma
   return st;
 }
 
-tw_status tw_pack_i8_host(const int8_t* B, const uint8_t* mask, int K, int N, int G, tw_handle_t* out) {
+tw_status tw_pack_i8_host(const int8_t* B, const uint8_t* mask, const uint8_t* tile_mask, int K, int N,
+                          int G, int pattern, tw_handle_t* out) {
   if (!out) return TW_ERR_ARG;
   *out = nullptr;
   if (!B || !mask || K < 1 || N < 1 || !valid_G(G)) return TW_ERR_ARG;
+  if (pattern == TW_PATTERN_TEW) return TW_ERR_UNSUPPORTED;
+  if (pattern != TW_PATTERN_TW && pattern != TW_PATTERN_TVW) return TW_ERR_ARG;
   tw_handle_s* h = new (std::nothrow) tw_handle_s();
   if (!h) return TW_ERR_ALLOC;
   tw_status st;
@@ -168,7 +171,7 @@ tw_status tw_pack_i8_host(const int8_t* B, const uint8_t* mask, int K, int N, in
     std::vector<uint16_t> wide((size_t)K * N);
     for (size_t i = 0; i < wide.size(); ++i) wide[i] = (uint16_t)(int16_t)B[i];
     h->dtype = TW_DTYPE_I8;
-    st = twg::pack_host(wide.data(), mask, nullptr, K, N, G, TW_PATTERN_TW, h);
+    st = twg::pack_host(wide.data(), mask, tile_mask, K, N, G, pattern, h);
   } catch (const std::bad_alloc&) {
     st = TW_ERR_ALLOC;
   }
@@ -177,8 +180,9 @@ tw_status tw_pack_i8_host(const int8_t* B, const uint8_t* mask, int K, int N, in
   return TW_OK;
 }
 
-tw_status tw_pack_i8(const int8_t* B, const uint8_t* mask, int K, int N, int G, tw_handle_t* out) {
-  tw_status st = tw_pack_i8_host(B, mask, K, N, G, out);
+tw_status tw_pack_i8(const int8_t* B, const uint8_t* mask, const uint8_t* tile_mask, int K, int N, int G,
+                     int pattern, tw_handle_t* out) {
+  tw_status st = tw_pack_i8_host(B, mask, tile_mask, K, N, G, pattern, out);
   if (st != TW_OK) return st;
   st = tw_upload(*out);
   if (st != TW_OK) { tw_free(*out); *out = nullptr; }
@@ -431,8 +435,17 @@ tw_status tw_gemm_i8(const void* A, int M, int lda, tw_handle_t h, void* C, int 
   g.row_idx = h->img.d_row_idx; g.col_idx = h->img.d_col_idx; g.tile_sched = h->img.d_tile_sched;
   g.zero_cols = h->img.d_zero_cols; g.n_zero = (int)h->img.zero_cols.size();
   g.n_tiles = h->n_tiles; g.K = h->K; g.N = h->N; g.xcd_map = opt_xcd_map.load() ? 1 : 0;
-  const int tm = pick_tile_m_i8(M, h->n_tiles > 0 ? h->n_tiles : 1);
-  hipError_t e = twg::launch_tw_i8(h->G, tm, g, (hipStream_t)stream);
+  g.meta = h->img.d_meta;
+  hipError_t e;
+  if (h->pattern == TW_PATTERN_TVW) {
+    // 64-row tiles where 128-row tiles would not give every CU a workgroup
+    const int forced = opt_tile_m.load();
+    const long wgs128 = (long)((M + 127) / 128) * (h->n_tiles > 0 ? h->n_tiles : 1);
+    const int tm = h->G != 128 ? 128 : (forced == 64 || forced == 128) ? forced : (wgs128 <= 256 ? 64 : 128);
+    e = twg::launch_tvw_i8(h->G, tm, g, (hipStream_t)stream);
+  } else {
+    e = twg::launch_tw_i8(h->G, pick_tile_m_i8(M, h->n_tiles > 0 ? h->n_tiles : 1), g, (hipStream_t)stream);
+  }
   if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;
 }

@@ -21,12 +21,12 @@
 #include <type_traits>
 
 #include "device_common.h"
+#include "i8_common.h"
 
 namespace twg {
 
 namespace {
 
-typedef int intx16 __attribute__((ext_vector_type(16)));
 typedef int int4v __attribute__((ext_vector_type(4)));
 
 template <int OFF>
@@ -83,27 +83,6 @@ __device__ __forceinline__ int swz8_mask(int row) {
 template <int RB>
 __device__ __forceinline__ int swz8(int row, int xbytes) {
   return row * RB + (xbytes ^ swz8_mask<RB>(row));
-}
-
-__device__ __forceinline__ int requantize(int sum, float scale) {
-  float x = (float)sum * scale;            // int -> fp32 (nearest even), one fp32 product
-  x = __builtin_rintf(x);                  // halves to even
-  x = __builtin_fminf(__builtin_fmaxf(x, -128.f), 127.f);
-  return (int)x;
-}
-
-// Extra workgroups of a launch write 0 into one pruned column of C each.
-template <bool OUT8>
-__device__ __forceinline__ void zero_fill_column8(const GemmI8Args& g, int which) {
-  const int col = g.zero_cols[which];
-  constexpr int ES = OUT8 ? 1 : 4;
-  char* row = (char*)g.C + (size_t)col * g.ldc * ES;
-  const size_t bytes = (size_t)g.M * ES;
-  const u32x4 z = {0u, 0u, 0u, 0u};
-  for (size_t b = (size_t)threadIdx.x * 16; b < bytes; b += (size_t)blockDim.x * 16) {
-    if (b + 16 <= bytes) __builtin_nontemporal_store(z, (u32x4*)(row + b));
-    else for (size_t i = b; i < bytes; ++i) row[i] = 0;
-  }
 }
 
 constexpr int KS8 = 64;      // condensed rows per stage

@@ -48,6 +48,7 @@ struct GemmI8Args {
   const int32_t* col_idx;
   const int32_t* tile_sched;
   const int32_t* zero_cols;
+  const uint32_t* meta;          // TVW: 2:4 position words
   int n_zero;
   int n_tiles, n_mtiles;
   int K, N;                      // dense only
@@ -57,6 +58,8 @@ struct GemmI8Args {
 // The dense variant needs K % 64 == 0.
 hipError_t launch_tw_i8(int G, int tm, GemmI8Args g, hipStream_t stream);
 hipError_t launch_dense_i8(int tn, int tm, GemmI8Args g, hipStream_t stream);
+// int8 TVW on the sparse matrix instruction (gemm_tvw_i8.hip): G = 128 with tm in {64, 128}, G = 64 with tm = 128.
+hipError_t launch_tvw_i8(int G, int tm, GemmI8Args g, hipStream_t stream);
 
 // G / tn: tile width (32, 64, 128); tm: M-tile (64, 128, 256).
 // hipErrorInvalidValue when no instance exists for (G, tm).

@@ -289,7 +289,7 @@ void build_device_image(tw_handle_s* h) {
   const int G = h->G, nt = h->n_tiles;
   const bool tvw = h->pattern == TW_PATTERN_TVW;
   const bool i8 = h->dtype == TW_DTYPE_I8;
-  const int kstep = i8 ? KSTEP_I8 : tvw ? KSTEP_TVW : KSTEP_TW;
+  const int kstep = i8 ? (tvw ? KSTEP_I8_TVW : KSTEP_I8) : tvw ? KSTEP_TVW : KSTEP_TW;
   d.col_idx.assign((size_t)nt * G, -1);
   for (int t = 0; t < nt; ++t)
     std::copy(h->col_idx.begin() + h->tile_col_off[t], h->col_idx.begin() + h->tile_col_off[t + 1],
@@ -304,7 +304,7 @@ void build_device_image(tw_handle_s* h) {
   }
   // one stage of slack behind the last tile: the K-split kernel copies stages of
   // 64 rows and may run one 32-row stage past a tile's end (it never multiplies it)
-  d.row_idx.assign((size_t)d.tile_kp_off[nt] + KSTEP_I8, 0);
+  d.row_idx.assign((size_t)d.tile_kp_off[nt] + KSTEP_I8_TVW, 0);
   for (int t = 0; t < nt; ++t) {
     const int k0 = h->tile_k_off[t], kt = h->tile_k_off[t + 1] - k0;
     const int kp0 = d.tile_kp_off[t], kp = d.tile_kp_off[t + 1] - kp0;
@@ -337,7 +337,48 @@ void build_device_image(tw_handle_s* h) {
     d.tile_sched[4 * pos + 2] = d.tile_kp_off[t + 1] - d.tile_kp_off[t];
     d.tile_sched[4 * pos + 3] = h->tile_col_off[t + 1] - h->tile_col_off[t];
   }
-  if (i8) {            // TW only: the condensed rows as bytes
+  if (i8 && tvw) {
+    // int8 TVW, register order of v_smfmac_i32_32x32x64_i8's sparse operand: for K-stage s
+    // (128 condensed rows), half u (64 rows = 16 groups of 4), column block nb and lane l:
+    // column w = 32 nb + l%32; the lane's 16 bytes are stored values 0 and 1 of the groups
+    // 8 (l/32) .. +7 of the half (byte 2j+i = value i of group j), its position word has the
+    // meta nibble of group j at bits [4j+3 : 4j].  A lane's bytes are contiguous (one 16-byte
+    // load), a wave's 64 lanes are contiguous (1 KiB); one word per (s, u, nb, lane).
+    const int nbt = G / 32;
+    d.vals.clear();
+    d.vals8.assign((size_t)d.tile_kp_off[nt] / 2 * G, 0);
+    d.meta.assign((size_t)d.tile_kp_off[nt] / 64 * nbt * 64, 0);
+    for (int t = 0; t < nt; ++t) {
+      const int kt = h->tile_k_off[t + 1] - h->tile_k_off[t];
+      const int ng = (kt + 3) / 4;
+      const int w = h->tile_col_off[t + 1] - h->tile_col_off[t];
+      const int kp0 = d.tile_kp_off[t], kp = d.tile_kp_off[t + 1] - kp0;
+      const uint16_t* v = h->values.data() + h->val_off[t];
+      const uint8_t* me = h->meta.data() + h->meta_off[t];
+      int8_t* ov = d.vals8.data() + (size_t)kp0 / 2 * G;
+      uint32_t* om = d.meta.data() + (size_t)kp0 / 64 * nbt * 64;
+      for (int su = 0; su < kp / 64; ++su)          // su = 2 s + u
+        for (int nb = 0; nb < nbt; ++nb)
+          for (int l = 0; l < 64; ++l) {
+            const int c = 32 * nb + l % 32;
+            int8_t* dst = ov + (((size_t)su * nbt + nb) * 64 + l) * 16;
+            uint32_t word = 0;
+            for (int j = 0; j < 8; ++j) {
+              const int g = 16 * su + 8 * (l / 32) + j;   // logical group of 4 condensed rows
+              uint32_t nib = 0x4;                         // positions (0,1), zero values
+              if (g < ng && c < w) {
+                nib = me[(size_t)g * w + c];
+                dst[2 * j + 0] = (int8_t)(int16_t)v[((size_t)g * 2 + 0) * w + c];
+                dst[2 * j + 1] = (int8_t)(int16_t)v[((size_t)g * 2 + 1) * w + c];
+              }
+              word |= nib << (4 * j);
+            }
+            om[((size_t)su * nbt + nb) * 64 + l] = word;
+          }
+    }
+    return;
+  }
+  if (i8) {            // TW: the condensed rows as bytes
     d.vals.clear();
     d.meta.clear();
     d.vals8.assign(((size_t)d.tile_kp_off[nt] + KSTEP_I8) * G, 0);

@@ -15,7 +15,8 @@ namespace twg {
 // (two 2:4 sparse matrix-core instructions of 32 logical k each).
 constexpr int KSTEP_TW = 32;
 constexpr int KSTEP_TVW = 64;
-constexpr int KSTEP_I8 = 64;     // int8: one stage = two 32x32x32 matrix-core steps
+constexpr int KSTEP_I8 = 64;     // int8 TW: one stage = two 32x32x32 matrix-core steps
+constexpr int KSTEP_I8_TVW = 128; // int8 TVW: one stage = two 32x32x64 sparse steps
 
 struct DeviceImage {
   // host staging (filled by the packer)
@@ -26,7 +27,7 @@ struct DeviceImage {
   std::vector<int32_t> tile_order;   // tiles by descending K_t (longest first)
   std::vector<int32_t> tile_sched;   // per launch position: {tile, kp offset, Kp_t, width}
   std::vector<uint16_t> vals;        // TW: [sum Kp_t][G]; TVW: swizzled compressed values
-  std::vector<int8_t> vals8;         // int8 TW: [sum Kp_t][G] bytes (vals is empty then)
+  std::vector<int8_t> vals8;         // int8: TW [sum Kp_t][G] bytes, TVW swizzled compressed bytes (vals is empty then)
   std::vector<uint32_t> meta;        // TVW: swizzled 2-bit position words
   std::vector<int32_t> ew_ptr;       // TEW: N+1 offsets into ew_pairs, by original column
   std::vector<uint32_t> ew_pairs;    // TEW: restored elements, row << 16 | fp16 bits

@@ -6,7 +6,7 @@ import pytest
 
 import paper_2402_10876_amd as tw
 from oracle import pack as opk
-from tests.helpers import random_tw_mask
+from tests.helpers import random_tw_mask, random_tvw_mask
 import workloads as wl
 
 
@@ -36,12 +36,39 @@ def test_i8_export_structure_and_values(seed):
     p.free()
 
 
+@pytest.mark.parametrize("seed,full", [(0, True), (1, False), (2, True)])
+def test_i8_tvw_export_equals_oracle_pack(seed, full):
+    """The packer moves 16-bit patterns without looking at them: the TVW form of an int8 weight is
+    the oracle's TVW form of the same integers held in fp16 (exact), value for value."""
+    rng = np.random.default_rng(200 + seed)
+    K, N = int(rng.integers(4, 150)), int(rng.integers(1, 300))
+    G = int(rng.choice([64, 128]))
+    mask, tmask = random_tvw_mask(rng, K, N, G, full=full)
+    B = wl.rng_i8(seed, (K, N))
+    p = tw.tw_pack_i8_host(B, mask, G, tw.PATTERN_TVW, tile_mask=tmask)
+    e = p.export()
+    r = opk.ref_pack(B.astype(np.float16), mask, G, opk.PATTERN_TVW, tile_mask=tmask)
+    assert e["dtype"] == tw.DTYPE_I8 and e["pattern"] == tw.PATTERN_TVW
+    assert np.array_equal(e["col_idx"], r["col_idx"])
+    for t in range(r["n_tiles"]):
+        assert np.array_equal(e["row_idx"][t], r["row_idx"][t])
+        assert np.array_equal(e["meta"][t], r["meta"][t]) and np.array_equal(e["valid"][t], r["valid"][t])
+        assert np.array_equal(e["values"][t].astype(np.float16).view(np.uint16), r["values"][t])
+    Bm, m2 = p.unpack()
+    assert np.array_equal(m2, mask) and np.array_equal(Bm, np.where(mask != 0, B, 0))
+    p.free()
+
+
 def test_i8_rejects_a_non_tw_mask():
     mask = np.ones((8, 64), np.uint8)
     mask[3, 5] = 0
     with pytest.raises(tw.TwError) as ei:
         tw.tw_pack_i8_host(np.ones((8, 64), np.int8), mask, 64)
     assert ei.value.status == 2
+    with pytest.raises(tw.TwError) as ei:
+        tw.tw_pack_i8_host(np.ones((8, 64), np.int8), np.ones((8, 64), np.uint8), 64, tw.PATTERN_TEW,
+                           tile_mask=np.ones((8, 64), np.uint8))
+    assert ei.value.status == 3
 
 
 def test_i8_concat_and_dtype_mismatch():

@@ -5,7 +5,7 @@ import pytest
 
 import paper_2402_10876_amd as tw
 from oracle import gemm as og
-from tests.helpers import random_tw_mask
+from tests.helpers import random_tw_mask, random_tvw_mask
 from tests import gpu_util as gu
 import workloads as wl
 
@@ -157,3 +157,56 @@ def test_i8_full_size_bert_shape_on_sampled_rows():
     p.free()
     rows = np.concatenate([[0, 127, 128, 255, 256, M - 1], rng.integers(0, M, 58)])
     assert np.array_equal(C[rows], og.gemm_i8_oracle(A[rows], B, mask))
+
+
+# ---- TVW on the sparse int8 matrix instruction -------------------------------------------
+
+@pytest.mark.parametrize("G,tile_m", [(128, 64), (128, 128), (64, 128)])
+@pytest.mark.parametrize("full", [True, False])
+def test_i8_tvw_ragged_shapes(G, tile_m, full):
+    M, K, N = 333, 420, 300                       # K_t of about 210: two stages with a ragged tail
+    rng = np.random.default_rng(G + tile_m + full)
+    mask, tmask = random_tvw_mask(rng, K, N, G, col_keep=0.85, row_keep=0.5, full=full)
+    A, B = wl.rng_i8(50, (M, K)), wl.rng_i8(51, (K, N))
+    print(f"i8 tvw G={G} tile_m={tile_m} full={full}", flush=True)
+    tw.tw_set_option("tile_m", tile_m)
+    p = tw.tw_pack_i8(B, mask, G, tw.PATTERN_TVW, tile_mask=tmask)
+    C, raw = gu.run_tw_i8(tw, p, A, N)
+    p.free()
+    assert np.array_equal(C, og.gemm_i8_oracle(A, B, mask))
+    assert (raw[:, M:] == -77).all()
+    assert (raw[~tmask.any(0), :M] == 0).all()
+
+
+def test_i8_tvw_every_position_pair_and_identity_A():
+    """A = I and a mask that walks all six position pairs through every group and column:
+    C must be B (.) mask exactly (pins the position words and the byte order of the sparse operand)."""
+    K, N, G = 256, 128, 128
+    pairs = [(0, 1), (0, 2), (0, 3), (1, 2), (1, 3), (2, 3)]
+    mask = np.zeros((K, N), np.uint8)
+    for g4 in range(K // 4):
+        for n in range(N):
+            a, b = pairs[(g4 * 5 + n) % 6]
+            mask[4 * g4 + a, n] = mask[4 * g4 + b, n] = 1
+    B = wl.rng_i8(60, (K, N))
+    B[B == 0] = 3
+    p = tw.tw_pack_i8(B, mask, G, tw.PATTERN_TVW, tile_mask=np.ones((K, N), np.uint8))
+    C, _ = gu.run_tw_i8(tw, p, np.eye(K, dtype=np.int8), N)
+    p.free()
+    assert np.array_equal(C, np.where(mask != 0, B, 0).astype(np.int64))
+
+
+def test_i8_tvw_requantised_and_full_size_samples():
+    M, K, N, G = 4096, 768, 3072, 128
+    A, B = wl.rng_i8(70, (M, K)), wl.rng_i8(71, (K, N), sigma=30.0)
+    rng = np.random.default_rng(72)
+    mask, tmask = random_tvw_mask(rng, K, N, G, col_keep=0.9, row_keep=0.3)
+    scale = 1.0 / 97.0
+    print("i8 tvw full size 768x3072 M=4096, int8 output", flush=True)
+    p = tw.tw_pack_i8(B, mask, G, tw.PATTERN_TVW, tile_mask=tmask)
+    C, _ = gu.run_tw_i8(tw, p, A, N, c_dtype=1, scale=scale)
+    p.free()
+    rows = np.concatenate([[0, 63, 64, 127, 128, M - 1], rng.integers(0, M, 58)])
+    want = og.requantize_i8(og.gemm_i8_oracle(A[rows], B, mask), scale)
+    assert (np.abs(want) < 100).any() and (np.abs(want) == 127).any()
+    assert np.array_equal(C[rows], want.astype(np.int64))
