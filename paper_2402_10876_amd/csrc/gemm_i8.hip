@@ -91,7 +91,9 @@ constexpr int D8 = 3;        // stages in flight
 }  // namespace
 
 template <int TM, int TN, int WAVES_M, bool DENSE, bool OUT8>
-__global__ __launch_bounds__(256) void tw_gemm_i8_kernel(GemmI8Args g) {
+// (the 256 x 128 instance holds 128 accumulators per lane; its epilogue must not push the
+// register count past two waves per SIMD, which the 72 KiB of LDS allow)
+__global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i8_kernel(GemmI8Args g) {
   constexpr int NWAVES = 4, NT = 256, D = D8;
   constexpr int WAVES_N = NWAVES / WAVES_M;
   constexpr int WM = TM / WAVES_M, WN = TN / WAVES_N;
@@ -290,9 +292,59 @@ __global__ __launch_bounds__(256) void tw_gemm_i8_kernel(GemmI8Args g) {
   }
   if (ns > 0) mfma_step(f1);
 
-  // ---- epilogue: stage as [n][m] int32, half of the tile's columns at a time; every
-  // thread then finishes (column, CH x m) pieces with one 16-byte streaming store each
-  constexpr int CH = OUT8 ? 16 : 4;            // m values per piece
+  if constexpr (OUT8) {
+    // ---- epilogue, int8 output: requantise in registers, stage the whole tile as bytes
+    // [n][m] (rows of TM + 16 bytes), then one 16-byte streaming store of 16 m per thread
+    constexpr int CS8 = TM + 16;
+    static_assert(TN * CS8 <= LDS_BYTES, "");
+    constexpr int CA = TM / 16;                  // pieces per column
+    constexpr int RPP = NT / CA;                 // columns per pass
+    static_assert(TN % RPP == 0, "");
+    constexpr int NPASS = TN / RPP;
+    const int c = tid % CA, r0 = tid / CA;
+    const int m = m0 + c * 16;
+    int cols[NPASS];                             // original column of C of every piece (CTO_n)
+#pragma unroll
+    for (int i = 0; i < NPASS; ++i) {
+      const int n = r0 + i * RPP;
+      if constexpr (DENSE) { cols[i] = t * TN + n; if (cols[i] >= g.N) cols[i] = -1; }
+      else cols[i] = g.col_idx[t * TN + n];
+    }
+    __syncthreads();                             // the pipeline buffers are free
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        const int n = wn * WN + j * 32 + (lane & 31);
+#pragma unroll
+        for (int rq = 0; rq < 4; ++rq) {
+          const int mm = wm * WM + i * 32 + 8 * rq + 4 * (lane >> 5);
+          uint32_t pk = 0;
+#pragma unroll
+          for (int r = 0; r < 4; ++r)
+            pk |= ((uint32_t)requantize(acc[i][j][rq * 4 + r], g.scale) & 0xffu) << (8 * r);
+          *(uint32_t*)(lds + n * CS8 + mm) = pk;
+        }
+      }
+    __syncthreads();
+    int4v pc[NPASS];
+#pragma unroll
+    for (int i = 0; i < NPASS; ++i) pc[i] = *(const int4v*)(lds + (r0 + i * RPP) * CS8 + c * 16);
+#pragma unroll
+    for (int i = 0; i < NPASS; ++i) {
+      if (cols[i] < 0 || m >= g.M) continue;
+      int8_t* dst = (int8_t*)g.C + (size_t)cols[i] * g.ldc + m;
+      if (m + 16 <= g.M) __builtin_nontemporal_store(pc[i], (int4v*)dst);
+      else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+          if (m + e < g.M) dst[e] = (int8_t)(pc[i][e >> 2] >> (8 * (e & 3)));
+      }
+    }
+  } else {
+  // ---- epilogue, int32 output: stage as [n][m], half of the tile's columns at a time;
+  // every thread then finishes (column, 4 x m) pieces with one 16-byte streaming store each
+  constexpr int CH = 4;                        // m values per piece
   constexpr int CA = TM / CH;                  // pieces per column
   constexpr int RPP = NT / CA;                 // columns per pass
   static_assert(HN % RPP == 0, "");
@@ -328,42 +380,21 @@ __global__ __launch_bounds__(256) void tw_gemm_i8_kernel(GemmI8Args g) {
       }
     __syncthreads();
     // all staged pieces into registers first (unconditional reads), then the stores
-    int4v pc[NPASS][CH / 4];
+    int4v pc[NPASS];
 #pragma unroll
-    for (int i = 0; i < NPASS; ++i) {
-      const char* src = lds + (r0 + i * RPP) * CS + c * CH * 4;
-#pragma unroll
-      for (int u = 0; u < CH / 4; ++u) pc[i][u] = *(const int4v*)(src + 16 * u);
-    }
+    for (int i = 0; i < NPASS; ++i) pc[i] = *(const int4v*)(lds + (r0 + i * RPP) * CS + c * 16);
 #pragma unroll
     for (int i = 0; i < NPASS; ++i) {
       if (cols[i] < 0 || m >= g.M) continue;
-      if constexpr (OUT8) {
-        int4v w;
+      int* dst = (int*)g.C + (size_t)cols[i] * g.ldc + m;
+      if (m + 4 <= g.M) __builtin_nontemporal_store(pc[i], (int4v*)dst);
+      else {
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          uint32_t pk = 0;
-#pragma unroll
-          for (int r = 0; r < 4; ++r) pk |= ((uint32_t)requantize(pc[i][u][r], g.scale) & 0xffu) << (8 * r);
-          w[u] = (int)pk;
-        }
-        int8_t* dst = (int8_t*)g.C + (size_t)cols[i] * g.ldc + m;
-        if (m + 16 <= g.M) __builtin_nontemporal_store(w, (int4v*)dst);
-        else {
-#pragma unroll
-          for (int e = 0; e < 16; ++e)
-            if (m + e < g.M) dst[e] = (int8_t)(w[e >> 2] >> (8 * (e & 3)));
-        }
-      } else {
-        int* dst = (int*)g.C + (size_t)cols[i] * g.ldc + m;
-        if (m + 4 <= g.M) __builtin_nontemporal_store(pc[i][0], (int4v*)dst);
-        else {
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (m + e < g.M) dst[e] = pc[i][0][e];
-        }
+        for (int e = 0; e < 4; ++e)
+          if (m + e < g.M) dst[e] = pc[i][e];
       }
     }
+  }
   }
 }
 

@@ -175,10 +175,17 @@ def main():
             M, K, N, G = shp.M, shp.K, shp.N, 128
             nsets = max(2, min(args.sets, int(600e6 // (M * (K + 4 * N)))))
             B8 = wl.rng_i8(wl.seed_for(cfg, si) + 1, (K, N))
-            for sp in (0.75, 0.875) if cfg != 6 else (0.5, 0.75, 0.875):
-                mask = wl.tw_mask(B8.astype(np.float16), G, density=1.0 - sp, col_frac=0.10)
-                packed = [tw.tw_pack_i8(B8, mask, G) for _ in range(nsets)]
-                p16 = [tw.tw_pack(B8.astype(np.float16), mask, G, tw.PATTERN_TW) for _ in range(nsets)]
+            cases = [("tw", sp) for sp in ((0.75, 0.875) if cfg != 6 else (0.5, 0.75, 0.875))] + [("tvw", 0.875)]
+            for pattern, sp in cases:
+                B16 = B8.astype(np.float16)
+                if pattern == "tw":
+                    mask = tmask = wl.tw_mask(B16, G, density=1.0 - sp, col_frac=0.10)
+                else:
+                    mask, tmask = wl.tvw_mask(B16, G, sparsity=sp, col_frac=0.10)
+                pat = tw.PATTERN_TW if pattern == "tw" else tw.PATTERN_TVW
+                tmk = tmask if pattern == "tvw" else None
+                packed = [tw.tw_pack_i8(B8, mask, G, pat, tile_mask=tmk) for _ in range(nsets)]
+                p16 = [tw.tw_pack(B16, mask, G, pat, tile_mask=tmk) for _ in range(nsets)]
                 A8 = [torch.randint(-127, 128, (K, M), dtype=torch.int8, device=dev) for _ in range(nsets)]
                 A16 = [a.to(torch.float16) for a in A8]
                 C32 = [torch.empty((N, M), dtype=torch.int32, device=dev) for _ in range(nsets)]
@@ -194,16 +201,18 @@ def main():
                                                           M, K, N, M, N, M, 1, 1e-3, stream), args.reps)
                 t16 = timed(lambda r: tw.tw_gemm(A16[r % nsets].data_ptr(), M, M, tw.LAYOUT_KM, p16[r % nsets],
                                                  C16[r % nsets].data_ptr(), M, stream), args.reps)
-                ab8 = M * ku + M * N + skw + 4 * sk         # int8 A rows, int8 C, condensed bytes, row lists
+                # int8 A rows, int8 C, condensed bytes (TVW: the kept half + 2 bits per stored value), row lists
+                ab8 = M * ku + M * N + (skw if pattern == "tw" else skw // 2 + skw // 8) + 4 * sk
+                issued = (2.0 if pattern == "tw" else 1.0) * M * skw        # TVW: skw counts the rows before 2:4
                 print(json.dumps(dict(
-                    shape=shp.name, M=M, K=K, N=N, G=G, pattern="tw_i8", sparsity=sp, K_union=ku,
+                    shape=shp.name, M=M, K=K, N=N, G=G, pattern=pattern + "_i8", sparsity=sp, K_union=ku,
                     us_i8_out=round(t8 * 1e6, 2), us_i32_out=round(t32 * 1e6, 2), dense_i8_us=round(td8 * 1e6, 2),
-                    fp16_tw_us=round(t16 * 1e6, 2), speedup_vs_dense_i8=round(td8 / t8, 3),
-                    speedup_vs_fp16_tw=round(t16 / t8, 3),
+                    fp16_us=round(t16 * 1e6, 2), speedup_vs_dense_i8=round(td8 / t8, 3),
+                    speedup_vs_fp16=round(t16 / t8, 3),
                     dense_eq_tops=round(2.0 * M * K * N / t8 / 1e12, 1),
-                    condensed_mfma_util=round(2.0 * M * skw / t8 / 5.0e15, 4),
+                    condensed_mfma_util=round(issued / t8 / 5.0e15, 4),
                     alg_MB=round(ab8 / 1e6, 2), alg_GBps=round(ab8 / t8 / 1e9, 1),
-                    roofline_frac=round(max(ab8 / HBM, 2.0 * M * skw / 5.0e15) / t8, 4))), flush=True)
+                    roofline_frac=round(max(ab8 / HBM, issued / 5.0e15) / t8, 4))), flush=True)
                 for p in packed + p16:
                     p.free()
                 del A8, A16, C32, C8, C16
