@@ -274,9 +274,12 @@ __global__ __launch_bounds__(256) void tvw_gemm_i8_kernel(GemmI8Args g) {
   if (ns > 0) smfmac_step(f1);
 
   // ---- epilogue: acc[i][j][r] is C^T(n, m) with m = lane % 32 and
-  // n = 8*(r/4) + 4*(lane/32) + r%4 inside the 32 x 32 block; staged as [n][m] int32, then
-  // every thread finishes (column, CH x m) pieces with one 16-byte streaming store each
+  // n = 8*(r/4) + 4*(lane/32) + r%4 inside the 32 x 32 block; staged as [n][m] (int32, or
+  // int8 requantised in registers), then every thread finishes (column, CH x m) pieces with
+  // one 16-byte streaming store each
   constexpr int CH = OUT8 ? 16 : 4;
+  constexpr int ES = OUT8 ? 1 : 4;                        // bytes per staged element
+  constexpr int CSE = OUT8 ? TM + 16 : CS;                // staged row bytes
   constexpr int CA = TM / CH;
   constexpr int RPP = NT / CA;
   static_assert(TN % RPP == 0, "");
@@ -295,41 +298,26 @@ __global__ __launch_bounds__(256) void tvw_gemm_i8_kernel(GemmI8Args g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int n = wn * WN + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        *(int*)(lds + n * CS + mm * 4) = acc[i][j][r];
+        if constexpr (OUT8) *(int8_t*)(lds + n * CSE + mm) = (int8_t)requantize(acc[i][j][r], g.scale);
+        else *(int*)(lds + n * CSE + mm * 4) = acc[i][j][r];
       }
     }
   __syncthreads();
+  int4v pc[NPASS];
+#pragma unroll
+  for (int i = 0; i < NPASS; ++i) pc[i] = *(const int4v*)(lds + (r0 + i * RPP) * CSE + c * CH * ES);
 #pragma unroll
   for (int i = 0; i < NPASS; ++i) {
-    const char* src = lds + (r0 + i * RPP) * CS + c * CH * 4;
-    int4v pc[CH / 4];
-#pragma unroll
-    for (int u = 0; u < CH / 4; ++u) pc[u] = *(const int4v*)(src + 16 * u);
     if (cols[i] < 0 || m >= g.M) continue;
-    if constexpr (OUT8) {
-      int4v w;
+    char* dst = (char*)g.C + ((size_t)cols[i] * g.ldc + m) * ES;
+    if (m + CH <= g.M) __builtin_nontemporal_store(pc[i], (int4v*)dst);
+    else {
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        uint32_t pk = 0;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) pk |= ((uint32_t)requantize(pc[u][r], g.scale) & 0xffu) << (8 * r);
-        w[u] = (int)pk;
-      }
-      int8_t* dst = (int8_t*)g.C + (size_t)cols[i] * g.ldc + m;
-      if (m + 16 <= g.M) __builtin_nontemporal_store(w, (int4v*)dst);
-      else {
-#pragma unroll
-        for (int e = 0; e < 16; ++e)
-          if (m + e < g.M) dst[e] = (int8_t)(w[e >> 2] >> (8 * (e & 3)));
-      }
-    } else {
-      int* dst = (int*)g.C + (size_t)cols[i] * g.ldc + m;
-      if (m + 4 <= g.M) __builtin_nontemporal_store(pc[0], (int4v*)dst);
-      else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          if (m + e < g.M) dst[e] = pc[0][e];
-      }
+      for (int e = 0; e < CH; ++e)
+        if (m + e < g.M) {
+          if constexpr (OUT8) dst[e] = (char)(pc[i][e >> 2] >> (8 * (e & 3)));
+          else ((int*)dst)[e] = pc[i][e];
+        }
     }
   }
 }
