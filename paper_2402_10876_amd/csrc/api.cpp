@@ -413,10 +413,12 @@ tw_status tw_dense_gemm(const void* A, const void* B, void* C, int M, int K, int
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
 
-// int8 M-tile: 256 rows while that still gives every CU two workgroups, else 128
-static int pick_tile_m_i8(int M, int n_tiles) {
+// int8 M-tile: 256 rows while that still gives every CU two workgroups, else 128.  The 64-row
+// instance (G = 128) is only used on request: it measured no better than 128 rows on the small
+// BERT-base launches and worse on the dense baseline.
+static int pick_tile_m_i8(int M, int n_tiles, int G) {
   const int forced = opt_tile_m.load();
-  if (forced == 128 || forced == 256) return forced;
+  if (forced == 128 || forced == 256 || (forced == 64 && G == 128)) return forced;
   return (long)((M + 255) / 256) * n_tiles >= 512 ? 256 : 128;
 }
 
@@ -444,7 +446,7 @@ tw_status tw_gemm_i8(const void* A, int M, int lda, tw_handle_t h, void* C, int 
     const int tm = h->G != 128 ? 128 : (forced == 64 || forced == 128) ? forced : (wgs128 <= 256 ? 64 : 128);
     e = twg::launch_tvw_i8(h->G, tm, g, (hipStream_t)stream);
   } else {
-    e = twg::launch_tw_i8(h->G, pick_tile_m_i8(M, h->n_tiles > 0 ? h->n_tiles : 1), g, (hipStream_t)stream);
+    e = twg::launch_tw_i8(h->G, pick_tile_m_i8(M, h->n_tiles > 0 ? h->n_tiles : 1, h->G), g, (hipStream_t)stream);
   }
   if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;
@@ -466,7 +468,7 @@ tw_status tw_dense_gemm_i8(const void* A, const void* B, void* C, int M, int K, 
   const int tn = 128;
   g.n_tiles = (N + tn - 1) / tn;
   g.xcd_map = opt_xcd_map.load() ? 1 : 0;
-  hipError_t e = twg::launch_dense_i8(tn, pick_tile_m_i8(M, g.n_tiles), g, (hipStream_t)stream);
+  hipError_t e = twg::launch_dense_i8(tn, pick_tile_m_i8(M, g.n_tiles, tn), g, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;
 }

@@ -105,7 +105,7 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
                 "a stage is a whole number of 1 KiB copies per wave");
   constexpr int NIA = STAGE_A / (1024 * NWAVES), NIB = STAGE_B / (1024 * NWAVES);
   constexpr int RPIA = 1024 / RBA, RPIB = 1024 / RBB;  // tile rows per copy instruction
-  static_assert(RPIA == 4 || RPIA == 8, "row lists are fetched 4 or 8 entries at a time");
+  static_assert(RPIA == 4 || RPIA == 8 || RPIA == 16, "row lists are fetched 4, 8 or 16 entries at a time");
   constexpr int NPS = NIA + NIB;
   // epilogue: int32 tile staged as [n][m], half of the columns at a time
   constexpr int CS = (TM + 4) * 4;
@@ -177,17 +177,19 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
       for (int j = 0; j < NIA; ++j) {
         const int* rp = g.row_idx + kp0 + s * KS8 + (wave * NIA + j) * RPIA;
         if constexpr (RPIA == 4) asm volatile("s_load_dwordx4 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
-        else asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
+        else if constexpr (RPIA == 8) asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
+        else asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
       }
     }
   };
   auto tie_rows = [&](Rows& x) {      // after a wait: no use of x may be moved above this point
     if constexpr (!DENSE) {
-      if constexpr (NIA == 2) asm volatile("" : "+s"(x.r[0]), "+s"(x.r[1]));
+      if constexpr (NIA == 1) asm volatile("" : "+s"(x.r[0]));
+      else if constexpr (NIA == 2) asm volatile("" : "+s"(x.r[0]), "+s"(x.r[1]));
       else asm volatile("" : "+s"(x.r[0]), "+s"(x.r[1]), "+s"(x.r[2]), "+s"(x.r[3]));
     }
   };
-  static_assert(NIA == 2 || NIA == 4, "");
+  static_assert(NIA == 1 || NIA == 2 || NIA == 4, "");
   auto issue = [&](int s, const Rows& rows) {     // copies of stage s; rows = its kept-row indices
     char* dstA = lds + (s % D) * STAGE;
     char* dstB = dstA + STAGE_A;
@@ -413,6 +415,7 @@ static hipError_t launch8(const GemmI8Args& g, hipStream_t stream) {
 template <bool DENSE>
 static hipError_t dispatch8(int G, int tm, GemmI8Args& g, hipStream_t stream) {
   g.n_mtiles = (g.M + tm - 1) / tm;
+  if (G == 128 && tm == 64) return launch8<64, 128, 1, DENSE>(g, stream);
   if (G == 128 && tm == 128) return launch8<128, 128, 2, DENSE>(g, stream);
   if (G == 128 && tm == 256) return launch8<256, 128, 2, DENSE>(g, stream);
   if (G == 64 && tm == 128) return launch8<128, 64, 2, DENSE>(g, stream);

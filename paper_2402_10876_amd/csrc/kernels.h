@@ -54,7 +54,7 @@ struct GemmI8Args {
   int K, N;                      // dense only
   int xcd_map;
 };
-// G / tn in {64, 128}, tm in {128, 256}; hipErrorInvalidValue when no instance exists.
+// G / tn in {64, 128}, tm in {128, 256} (and 64 for G = 128); hipErrorInvalidValue when no instance exists.
 // The dense variant needs K % 64 == 0.
 hipError_t launch_tw_i8(int G, int tm, GemmI8Args g, hipStream_t stream);
 hipError_t launch_dense_i8(int tn, int tm, GemmI8Args g, hipStream_t stream);

@@ -25,8 +25,7 @@ def _case(seed, M, K, N, G, col_keep=0.8, row_keep=0.5):
     return wl.rng_i8(seed, (M, K)), wl.rng_i8(seed + 1, (K, N)), mask
 
 
-@pytest.mark.parametrize("tile_m", [128, 256])
-@pytest.mark.parametrize("G", [64, 128])
+@pytest.mark.parametrize("G,tile_m", [(64, 128), (64, 256), (128, 64), (128, 128), (128, 256)])
 def test_i8_ragged_shapes_int32(G, tile_m):
     M, K, N = 333, 210, 300                       # all ragged, several tiles in M and N
     A, B, mask = _case(G + tile_m, M, K, N, G)
@@ -40,7 +39,7 @@ def test_i8_ragged_shapes_int32(G, tile_m):
     assert (raw[~mask.any(0), :M] == 0).all()     # pruned columns are written as 0
 
 
-@pytest.mark.parametrize("G,tile_m", [(128, 128), (64, 256)])
+@pytest.mark.parametrize("G,tile_m", [(128, 64), (128, 128), (64, 256)])
 def test_i8_requantised_output(G, tile_m):
     M, K, N = 190, 300, 200
     A, B, mask = _case(7 + G, M, K, N, G)
@@ -119,7 +118,7 @@ def test_i8_dense_baseline(c_dtype):
     M, K, N = 300, 192, 200
     A, B = wl.rng_i8(5, (M, K)), wl.rng_i8(6, (K, N))
     scale = 1.0 / 977.0
-    for tile_m in (128, 256):
+    for tile_m in (64, 128, 256):
         print(f"i8 dense c_dtype={c_dtype} tile_m={tile_m}", flush=True)
         tw.tw_set_option("tile_m", tile_m)
         C, raw = gu.run_dense_i8(tw, A, B, c_dtype=c_dtype, scale=scale)
