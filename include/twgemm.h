@@ -264,19 +264,25 @@ tw_status tw_dense_gemm_i8(const void* A_dev, const void* B_dev, void* C_dev, in
  * zero-padded layout sit depends on the caller's (R-1)/2, (S-1)/2 shift; this call does not
  * care), pruned output channels +0.
  *
- * tw_conv_bind - fix the geometry for an uploaded fp16 TW or TVW handle with K = C*R*S
- *   (the per-tile kept-row lists become element offsets on the device; allocates; binding
- *   again replaces the previous geometry).  ldx >= roundup8(B*L*P) + (R-1)*P + S-1 so that
- *   the windows of the last positions stay inside channel rows of ldx elements; C*ldx < 2^31.
- *   Errors: TW_ERR_ARG, TW_ERR_STATE (not uploaded), TW_ERR_UNSUPPORTED (G = 32, TEW, int8),
+ * tw_conv_bind - fix the geometry for an uploaded TW or TVW handle (fp16 or int8) with
+ *   K = C*R*S (the per-tile kept-row lists become element offsets on the device; allocates;
+ *   binding again replaces the previous geometry).  With c = 8 (fp16) or 16 (int8) elements
+ *   per 16-byte copy: ldx a multiple of c, ldx >= roundup_c(B*L*P) + (R-1)*P + S-1 so that the
+ *   windows of the last positions stay inside channel rows of ldx elements; C*ldx < 2^31.
+ *   Errors: TW_ERR_ARG, TW_ERR_STATE (not uploaded), TW_ERR_UNSUPPORTED (G = 32, TEW),
  *   TW_ERR_ALLOC, TW_ERR_HIP.
  * tw_conv_gemm - the launch.  X_dev fp16, C rows of ldx elements, 16-byte aligned; C_dev fp16
  *   N x ldc, ldc >= B*L*P, multiple of 8, 16-byte aligned.  Asynchronous on `stream`,
- *   allocates nothing.  Errors: TW_ERR_ARG, TW_ERR_STATE (no geometry bound), TW_ERR_HIP.
+ *   allocates nothing.  Errors: TW_ERR_ARG (also: an int8 handle), TW_ERR_STATE (no geometry
+ *   bound), TW_ERR_HIP.
+ * tw_conv_gemm_i8 - the same for an int8 handle: X_dev int8, C_dev int32 (c_dtype 0) or int8
+ *   requantised with `scale` (c_dtype 1) as in tw_gemm_i8, ldc >= B*L*P, multiple of 16.
  */
 typedef struct { int32_t C, R, S, B, H, W, P, L; } tw_conv_geom;
 tw_status tw_conv_bind(tw_handle_t h, const tw_conv_geom* geom, int64_t ldx);
 tw_status tw_conv_gemm(const void* X_dev, tw_handle_t h, void* C_dev, int ldc, void* stream);
+tw_status tw_conv_gemm_i8(const void* X_dev, tw_handle_t h, void* C_dev, int ldc, int c_dtype,
+                          float scale, void* stream);
 
 /* tw_export - fill *out with the logical view (host pointers owned by h). */
 tw_status tw_export(tw_handle_t h, tw_packed_view* out);

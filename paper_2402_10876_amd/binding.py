@@ -17,7 +17,7 @@ EXPORTED_SYMBOLS = [
     "tw_pack_host", "tw_upload", "tw_pack", "tw_pack_dev", "tw_prune_dev",
     "tw_prune_workspace_bytes", "tw_concat", "tw_gemm", "tw_dense_gemm", "tw_export",
     "tw_unpack", "tw_free", "tw_status_str", "tw_set_option", "tw_flop_counts",
-    "tw_pack_i8_host", "tw_pack_i8", "tw_gemm_i8", "tw_dense_gemm_i8", "tw_conv_bind", "tw_conv_gemm",
+    "tw_pack_i8_host", "tw_pack_i8", "tw_gemm_i8", "tw_dense_gemm_i8", "tw_conv_bind", "tw_conv_gemm", "tw_conv_gemm_i8",
 ]
 
 _lib = None
@@ -76,6 +76,7 @@ def lib():
         L.tw_dense_gemm.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, vp]
         L.tw_conv_bind.argtypes = [vp, C.POINTER(_ConvGeom), C.c_int64]
         L.tw_conv_gemm.argtypes = [vp, vp, vp, i, vp]
+        L.tw_conv_gemm_i8.argtypes = [vp, vp, vp, i, i, C.c_float, vp]
         L.tw_export.argtypes = [vp, C.POINTER(_View)]
         L.tw_unpack.argtypes = [vp, vp, vp]
         L.tw_free.argtypes = [vp]
@@ -303,6 +304,11 @@ def tw_conv_bind(packed: PackedWeight, geom, ldx: int):
 
 def tw_conv_gemm(X_ptr: int, packed: PackedWeight, C_ptr: int, ldc: int, stream: int = 0):
     _check(lib().tw_conv_gemm(X_ptr, packed.handle, C_ptr, ldc, stream), "tw_conv_gemm")
+
+
+def tw_conv_gemm_i8(X_ptr: int, packed: PackedWeight, C_ptr: int, ldc: int, c_dtype: int = 0, scale: float = 1.0,
+                    stream: int = 0):
+    _check(lib().tw_conv_gemm_i8(X_ptr, packed.handle, C_ptr, ldc, c_dtype, scale, stream), "tw_conv_gemm_i8")
 
 
 def tw_set_option(name: str, value: int):

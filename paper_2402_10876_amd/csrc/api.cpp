@@ -333,9 +333,10 @@ tw_status tw_conv_bind(tw_handle_t h, const tw_conv_geom* cg, int64_t ldx) {
   if ((int64_t)cg->C * cg->R * cg->S != h->K) return TW_ERR_ARG;
   const int64_t Mp = (int64_t)cg->B * cg->L * cg->P;
   if (Mp > INT32_MAX - 8) return TW_ERR_ARG;
-  const int64_t reach = (Mp + 7) / 8 * 8 + (int64_t)(cg->R - 1) * cg->P + cg->S - 1;
-  if (ldx < reach || ldx % 8 || (int64_t)cg->C * ldx >= (1ll << 31)) return TW_ERR_ARG;
-  if (h->dtype != TW_DTYPE_F16 || h->pattern == TW_PATTERN_TEW || h->G == 32) return TW_ERR_UNSUPPORTED;
+  const int chunk = h->dtype == TW_DTYPE_I8 ? 16 : 8;          // elements per 16-byte copy
+  const int64_t reach = (Mp + chunk - 1) / chunk * chunk + (int64_t)(cg->R - 1) * cg->P + cg->S - 1;
+  if (ldx < reach || ldx % chunk || (int64_t)cg->C * ldx >= (1ll << 31)) return TW_ERR_ARG;
+  if (h->pattern == TW_PATTERN_TEW || h->G == 32) return TW_ERR_UNSUPPORTED;
   if (!h->img.blob) return TW_ERR_STATE;
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) return TW_ERR_HIP;
@@ -364,6 +365,7 @@ tw_status tw_conv_bind(tw_handle_t h, const tw_conv_geom* cg, int64_t ldx) {
 
 tw_status tw_conv_gemm(const void* X, tw_handle_t h, void* C, int ldc, void* stream) {
   if (!X || !C || !h) return TW_ERR_ARG;
+  if (h->dtype != TW_DTYPE_F16) return TW_ERR_ARG;
   if (!h->d_conv_off) return TW_ERR_STATE;
   const int Mp = h->conv.B * h->conv.L * h->conv.P;
   if (!aligned16(X) || !aligned16(C) || ldc % 8 || ldc < Mp) return TW_ERR_ARG;
@@ -422,19 +424,18 @@ static int pick_tile_m_i8(int M, int n_tiles, int G) {
   return (long)((M + 255) / 256) * n_tiles >= 512 ? 256 : 128;
 }
 
-tw_status tw_gemm_i8(const void* A, int M, int lda, tw_handle_t h, void* C, int ldc, int c_dtype,
-                     float scale, void* stream) {
-  if (!A || !C || !h || M < 1 || (c_dtype != 0 && c_dtype != 1)) return TW_ERR_ARG;
-  if (!aligned16(A) || !aligned16(C) || lda % 16 || ldc % 16 || lda < M || ldc < M) return TW_ERR_ARG;
-  if (h->dtype != TW_DTYPE_I8) return TW_ERR_ARG;
-  if (!h->img.blob) return TW_ERR_STATE;
-  if (h->G == 32 || h->K > 131071) return TW_ERR_UNSUPPORTED;
-  if ((unsigned long long)h->K * (unsigned long long)lda >= (1ull << 32)) return TW_ERR_UNSUPPORTED;
+// The launch behind tw_gemm_i8 and tw_conv_gemm_i8 (conv: see gemm_launch).
+static tw_status gemm_i8_launch(const void* A, int M, int lda, tw_handle_t h, void* C, int ldc, int c_dtype,
+                                float scale, void* stream, bool conv) {
   twg::GemmI8Args g{};
   g.A = (const int8_t*)A; g.C = C; g.M = M; g.lda = lda; g.ldc = ldc;
   g.c_i8 = c_dtype; g.scale = scale;
   g.vals = (const int8_t*)h->img.d_vals;
   g.row_idx = h->img.d_row_idx; g.col_idx = h->img.d_col_idx; g.tile_sched = h->img.d_tile_sched;
+  if (conv) {
+    g.row_idx = h->d_conv_off;
+    g.conv_P = h->conv.P; g.conv_L = h->conv.L; g.conv_H = h->conv.H; g.conv_W = h->conv.W;
+  }
   g.zero_cols = h->img.d_zero_cols; g.n_zero = (int)h->img.zero_cols.size();
   g.n_tiles = h->n_tiles; g.K = h->K; g.N = h->N; g.xcd_map = opt_xcd_map.load() ? 1 : 0;
   g.meta = h->img.d_meta;
@@ -450,6 +451,28 @@ tw_status tw_gemm_i8(const void* A, int M, int lda, tw_handle_t h, void* C, int 
   }
   if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;
+}
+
+tw_status tw_gemm_i8(const void* A, int M, int lda, tw_handle_t h, void* C, int ldc, int c_dtype,
+                     float scale, void* stream) {
+  if (!A || !C || !h || M < 1 || (c_dtype != 0 && c_dtype != 1)) return TW_ERR_ARG;
+  if (!aligned16(A) || !aligned16(C) || lda % 16 || ldc % 16 || lda < M || ldc < M) return TW_ERR_ARG;
+  if (h->dtype != TW_DTYPE_I8) return TW_ERR_ARG;
+  if (!h->img.blob) return TW_ERR_STATE;
+  if (h->G == 32 || h->K > 131071) return TW_ERR_UNSUPPORTED;
+  if ((unsigned long long)h->K * (unsigned long long)lda >= (1ull << 32)) return TW_ERR_UNSUPPORTED;
+  return gemm_i8_launch(A, M, lda, h, C, ldc, c_dtype, scale, stream, false);
+}
+
+tw_status tw_conv_gemm_i8(const void* X, tw_handle_t h, void* C, int ldc, int c_dtype, float scale,
+                          void* stream) {
+  if (!X || !C || !h || (c_dtype != 0 && c_dtype != 1)) return TW_ERR_ARG;
+  if (h->dtype != TW_DTYPE_I8) return TW_ERR_ARG;
+  if (!h->d_conv_off) return TW_ERR_STATE;
+  const int Mp = h->conv.B * h->conv.L * h->conv.P;
+  if (!aligned16(X) || !aligned16(C) || ldc % 16 || ldc < Mp) return TW_ERR_ARG;
+  if (h->K > 131071) return TW_ERR_UNSUPPORTED;
+  return gemm_i8_launch(X, Mp, 1, h, C, ldc, c_dtype, scale, stream, true);
 }
 
 tw_status tw_dense_gemm_i8(const void* A, const void* B, void* C, int M, int K, int N, int lda, int ldb,

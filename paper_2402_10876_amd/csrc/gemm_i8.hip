@@ -332,6 +332,13 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
     int4v pc[NPASS];
 #pragma unroll
     for (int i = 0; i < NPASS; ++i) pc[i] = *(const int4v*)(lds + (r0 + i * RPP) * CS8 + c * 16);
+    if constexpr (!DENSE) {
+      if (g.conv_P) {                            // implicit img2col: padding lanes of the grid are 0
+        const int4v vm = (int4v)conv_valid_mask_i8<16>(g, m);
+#pragma unroll
+        for (int i = 0; i < NPASS; ++i) pc[i] &= vm;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < NPASS; ++i) {
       if (cols[i] < 0 || m >= g.M) continue;
@@ -385,6 +392,13 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
     int4v pc[NPASS];
 #pragma unroll
     for (int i = 0; i < NPASS; ++i) pc[i] = *(const int4v*)(lds + (r0 + i * RPP) * CS + c * 16);
+    if constexpr (!DENSE) {
+      if (g.conv_P) {
+        const int4v vm = (int4v)conv_valid_mask_i8<4>(g, m);
+#pragma unroll
+        for (int i = 0; i < NPASS; ++i) pc[i] &= vm;
+      }
+    }
 #pragma unroll
     for (int i = 0; i < NPASS; ++i) {
       if (cols[i] < 0 || m >= g.M) continue;

@@ -306,6 +306,11 @@ __global__ __launch_bounds__(256) void tvw_gemm_i8_kernel(GemmI8Args g) {
   int4v pc[NPASS];
 #pragma unroll
   for (int i = 0; i < NPASS; ++i) pc[i] = *(const int4v*)(lds + (r0 + i * RPP) * CSE + c * CH * ES);
+  if (g.conv_P) {                                // implicit img2col: padding lanes of the grid are 0
+    const int4v vm = (int4v)conv_valid_mask_i8<CH>(g, m);
+#pragma unroll
+    for (int i = 0; i < NPASS; ++i) pc[i] &= vm;
+  }
 #pragma unroll
   for (int i = 0; i < NPASS; ++i) {
     if (cols[i] < 0 || m >= g.M) continue;

@@ -15,6 +15,25 @@ __device__ __forceinline__ int requantize(int sum, float scale) {
   return (int)x;
 }
 
+// Implicit img2col: which of the CH wide-grid positions m .. m+CH-1 are output pixels (x < W and
+// y < H).  CH = 4: one all-ones dword per valid position (int32 output); CH = 16: one 0xff byte
+// per valid position (int8 output).  One division per thread.
+template <int CH>
+__device__ __forceinline__ u32x4 conv_valid_mask_i8(const GemmI8Args& g, int m) {
+  const uint32_t P = (uint32_t)g.conv_P, L = (uint32_t)g.conv_L;
+  const uint32_t line = (uint32_t)m / P;
+  uint32_t x = (uint32_t)m - line * P, y = line % L;
+  u32x4 v = {0u, 0u, 0u, 0u};
+#pragma unroll
+  for (int e = 0; e < CH; ++e) {
+    const bool ok = x < (uint32_t)g.conv_W && y < (uint32_t)g.conv_H;
+    if constexpr (CH == 4) v[e] = ok ? ~0u : 0u;
+    else v[e >> 2] |= ok ? (0xffu << (8 * (e & 3))) : 0u;
+    if (++x == P) { x = 0; if (++y == L) y = 0; }
+  }
+  return v;
+}
+
 // Extra workgroups of a launch write 0 into one pruned column of C each.
 template <bool OUT8>
 __device__ __forceinline__ void zero_fill_column8(const GemmI8Args& g, int which) {

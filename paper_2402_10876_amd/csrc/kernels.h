@@ -53,6 +53,7 @@ struct GemmI8Args {
   int n_tiles, n_mtiles;
   int K, N;                      // dense only
   int xcd_map;
+  int conv_P, conv_L, conv_H, conv_W;   // implicit img2col, as in GemmArgs (0 = off)
 };
 // G / tn in {64, 128}, tm in {128, 256} (and 64 for G = 128); hipErrorInvalidValue when no instance exists.
 // The dense variant needs K % 64 == 0.

@@ -148,3 +148,17 @@ def run_conv(tw, packed, X16, geom, N, *, ldc=None, fill=float("nan")):
     torch.cuda.synchronize()
     raw = Ct.cpu().numpy()
     return raw[:, :Mp].T.astype(np.float64), raw
+
+
+def run_conv_i8(tw, packed, X8, geom, N, *, c_dtype=0, scale=1.0, ldc=None, fill=-77):
+    """Implicit-img2col launch on int8: X8 is C x ldx (wide layout).  Returns (C over the wide grid
+    as Mp x N int64, raw N x ldc array)."""
+    torch = _torch()
+    Mp = geom.Mp
+    Xd = torch.from_numpy(np.ascontiguousarray(X8)).cuda()
+    tw.tw_conv_bind(packed, geom, X8.shape[1])
+    Ct, ldc = new_C_i8(N, Mp, c_dtype, ldc, fill)
+    tw.tw_conv_gemm_i8(Xd.data_ptr(), packed, Ct.data_ptr(), ldc, c_dtype, scale, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    raw = Ct.cpu().numpy()
+    return raw[:, :Mp].T.astype(np.int64), raw

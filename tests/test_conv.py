@@ -5,6 +5,7 @@ import pytest
 
 import paper_2402_10876_amd as tw
 from oracle import conv as oc
+from oracle import gemm as og
 from tests.helpers import assert_C_close, random_tw_mask, random_tvw_mask
 import workloads as wl
 
@@ -29,7 +30,10 @@ def test_bind_argument_errors_need_no_device():
     p32 = tw.tw_pack_host(np.ones((K, 32), np.float16), np.ones((K, 32), np.uint8), 32, tw.PATTERN_TW)
     assert _status(tw.tw_conv_bind, p32, g, ldx) == 3                       # G = 32
     p8 = tw.tw_pack_i8_host(np.ones((K, N), np.int8), np.ones((K, N), np.uint8), G)
-    assert _status(tw.tw_conv_bind, p8, g, ldx) == 3                        # int8
+    assert _status(tw.tw_conv_bind, p8, g, wl.conv_ldx(g, 16)) == 6         # int8 binds too, once uploaded
+    assert _status(tw.tw_conv_bind, p8, g, wl.conv_ldx(g, 16) + 8) == 1     # int8 rows: multiples of 16
+    assert _status(tw.tw_conv_gemm, 0x10000, p8, 0x20000, 64) == 1          # fp16 launch, int8 handle
+    assert _status(tw.tw_conv_gemm_i8, 0x10000, p, 0x20000, 64) == 1        # int8 launch, fp16 handle
     for q in (p, p32, p8):
         q.free()
 
@@ -121,3 +125,38 @@ def test_conv_vgg_layer_on_sampled_positions(G):
         assert (np.abs(Cw[m] - ref) <= 4e-3 * S + 1e-30).all()
     inval = ~oc.valid_positions(B=g.B, H=g.H, W=g.W, P=g.P, L=g.L)
     assert (raw[:, :g.Mp][:, inval].view(np.uint16) == 0).all()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("pattern", ["tw", "tvw"])
+@pytest.mark.parametrize("G,tile_m,c_dtype", [(128, 128, 0), (128, 64, 1), (64, 128, 1), (128, 256, 0)])
+def test_conv_int8_parity(pattern, G, tile_m, c_dtype):
+    """int8 input and weight: the img2col GEMM over integers, bit for bit, int32 or requantised."""
+    from tests import gpu_util as gu
+    g = wl.same_geom(24, 3, 3, 2, 13, 11)
+    N = 150
+    rng = np.random.default_rng(300 + G + tile_m + c_dtype)
+    X = wl.make_conv_input(20, g, int8=True)
+    Bw = wl.rng_i8(21, (g.K, N))
+    if pattern == "tw":
+        mask = tmask = random_tw_mask(rng, g.K, N, G, col_keep=0.85, row_keep=0.4)
+    else:
+        mask, tmask = random_tvw_mask(rng, g.K, N, G, col_keep=0.85, row_keep=0.5)
+    scale = 1.0 / 700.0
+    print(f"conv int8 {pattern} G={G} tile_m={tile_m} c_dtype={c_dtype}", flush=True)
+    tw.tw_set_option("tile_m", tile_m)
+    p = tw.tw_pack_i8(Bw, mask, G, tw.PATTERN_TVW if pattern == "tvw" else tw.PATTERN_TW,
+                      tile_mask=tmask if pattern == "tvw" else None)
+    try:
+        Cw, raw = gu.run_conv_i8(tw, p, X, g, N, c_dtype=c_dtype, scale=scale)
+    finally:
+        tw.tw_set_option("tile_m", 0)
+        p.free()
+    want = og.gemm_i8_oracle(oc.im2col_wide(X, **g.ints()), Bw, mask)
+    if c_dtype:
+        want = og.requantize_i8(want, scale).astype(np.int64)
+    assert np.abs(want).max() > 20
+    assert np.array_equal(Cw, want)
+    valid = oc.valid_positions(B=g.B, H=g.H, W=g.W, P=g.P, L=g.L)
+    assert (raw[:, :g.Mp][:, ~valid] == 0).all()
+    assert (raw[:, g.Mp:] == -77).all()

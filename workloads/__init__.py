@@ -311,18 +311,19 @@ CONV_LAYERS = [("vgg16_conv3x3_256_56", same_geom(256, 3, 3, 8, 56, 56), 256),
                ("vgg16_conv3x3_512_14", same_geom(512, 3, 3, 8, 14, 14), 512)]
 
 
-def conv_ldx(g: ConvGeom) -> int:
-    """Shortest channel row (multiple of 8) in which the windows of every wide-grid position,
-    padding lanes included, stay inside the row."""
-    return ((g.Mp + 7) // 8 * 8 + (g.R - 1) * g.P + g.S - 1 + 7) // 8 * 8
+def conv_ldx(g: ConvGeom, chunk: int = 8) -> int:
+    """Shortest channel row (multiple of `chunk` elements: 8 for fp16, 16 for int8) in which the
+    windows of every wide-grid position, padding lanes included, stay inside the row."""
+    up = lambda v: (v + chunk - 1) // chunk * chunk
+    return up(up(g.Mp) + (g.R - 1) * g.P + g.S - 1)
 
 
-def make_conv_input(seed: int, g: ConvGeom, ldx: int | None = None) -> np.ndarray:
-    """fp16 C x ldx: N(0,1) pixels, zeros in the padding ((R-1)//2 lines above, (S-1)//2
-    columns left of every image, the rest below / right) and in the slack behind the grid."""
-    ldx = ldx or conv_ldx(g)
-    X = np.zeros((g.C, ldx), np.float16)
-    img = rng_fp16(seed, (g.C, g.B, g.H, g.W), 1.0)
+def make_conv_input(seed: int, g: ConvGeom, ldx: int | None = None, int8: bool = False) -> np.ndarray:
+    """C x ldx, fp16 N(0,1) pixels (or int8, as rng_i8), zeros in the padding ((R-1)//2 lines above,
+    (S-1)//2 columns left of every image, the rest below / right) and in the slack behind the grid."""
+    ldx = ldx or conv_ldx(g, 16 if int8 else 8)
+    X = np.zeros((g.C, ldx), np.int8 if int8 else np.float16)
+    img = rng_i8(seed, (g.C, g.B, g.H, g.W)) if int8 else rng_fp16(seed, (g.C, g.B, g.H, g.W), 1.0)
     blk = X[:, :g.Mp].reshape(g.C, g.B, g.L, g.P)
     t, l = (g.R - 1) // 2, (g.S - 1) // 2
     blk[:, :, t:t + g.H, l:l + g.W] = img
