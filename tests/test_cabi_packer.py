@@ -25,6 +25,17 @@ def test_library_exports_every_declared_symbol():
         assert getattr(L, name) is not None
 
 
+def test_header_is_plain_c(tmp_path):
+    """include/twgemm.h is the boundary: it must compile as C99 on its own, warnings as errors."""
+    import subprocess
+    src = tmp_path / "t.c"
+    src.write_text('#include "twgemm.h"\nint main(void) { tw_conv_geom g = {1, 1, 1, 1, 1, 1, 1, 1}; tw_packed_view v;\n'
+                   '  (void)g; (void)v; return (int)TW_OK; }\n')
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-pedantic", "-I" + os.path.join(ROOT, "include"),
+                        "-fsyntax-only", str(src)], capture_output=True, text=True)
+    assert r.returncode == 0, r.stderr
+
+
 def _same(e, r):
     assert e["n_kept"] == r["n_kept"] and e["n_tiles"] == r["n_tiles"]
     assert np.array_equal(e["col_idx"], r["col_idx"])
