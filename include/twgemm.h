@@ -117,8 +117,8 @@ typedef struct {
 } tw_packed_view;
 
 /*
- * tw_pack_host - condense a pruned weight on the host (Section V: done
- * "offline before the model inference starts"; Algorithm 3's Condense).
+ * tw_pack_host - condense a pruned weight on the host (Section V: the weight is
+ * condensed once, ahead of inference, not per call; Algorithm 3's Condense).
  *   B_host     K x N row-major fp16 bit patterns (ldb = N)
  *   mask_host  K x N bytes, non-zero = kept
  *   tile_mask_host  TVW, may be NULL: the TW-level mask the 2:4 step was

@@ -2,7 +2,7 @@
 // (Algorithm 3: TW-C on whole columns, Condense, TW-R on the (1,G) row pieces of
 // every tile of kept columns; TVW: then 2 of every 4 consecutive kept rows per
 // column, Algorithm 2's VW with vectors of 4 and 50 %).  The importance score
-// is the sum of squares (Section IV calls magnitude the most intuitive score;
+// is the sum of squares (Section IV names weight magnitude as the simplest score;
 // the paper's Taylor score needs gradients).
 //
 // Scores are exact: an fp16 value is an integer multiple of 2^-24, its square
