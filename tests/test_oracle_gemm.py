@@ -160,3 +160,45 @@ def test_requantize_rule():
     # int32 -> fp32 is itself rounded (to even): 2^24 + 1 becomes 2^24
     assert og.requantize_i8(np.array([2 ** 24 + 1]), 2.0 ** -18).tolist() == [64]
     assert og.requantize_i8(np.array([3]), np.float32(1 / 3)).tolist() == [1]
+
+
+def _rne_to_fp32(x):
+    """Nearest binary32 value of a positive rational in the normal range, ties to even, in exact
+    arithmetic (Fractions): the IEEE 754 definition written out, no floating point used."""
+    from fractions import Fraction
+    assert x > 0
+    e = 0
+    while x >= 2:
+        x /= 2
+        e += 1
+    while x < 1:
+        x *= 2
+        e -= 1
+    assert -126 <= e <= 127
+    scaled = x * 2 ** 23                   # 24 significant bits: 2^23 <= scaled < 2^24
+    n, r = divmod(scaled.numerator, scaled.denominator)
+    if 2 * r > scaled.denominator or (2 * r == scaled.denominator and n % 2 == 1):
+        n += 1
+    return Fraction(n, 2 ** 23) * Fraction(2) ** e
+
+
+def test_requantize_against_exact_rational_arithmetic():
+    """Every step of the rule redone with Fractions on random sums and scales: int -> binary32
+    (nearest even), one binary32 product (nearest even), round half to even, clamp."""
+    from fractions import Fraction
+    rng = np.random.default_rng(17)
+    sums = np.concatenate([rng.integers(-2 ** 26, 2 ** 26, 300), rng.integers(-3000, 3000, 300),
+                           [2 ** 24 + 1, 2 ** 24 + 3, -(2 ** 25 + 2), 1, -1]]).astype(np.int64)
+    scales = np.concatenate([rng.uniform(1e-6, 1e-1, 600), [0.5, 0.25, 1.5, 2.5, 1e-3]]).astype(np.float32)
+    got = og.requantize_i8(sums, 1.0)                       # shapes differ: call element by element below
+    for s, sc in zip(sums.tolist(), scales.tolist()):
+        want = 0
+        if s != 0:
+            a = _rne_to_fp32(Fraction(abs(s)))               # |sum| as binary32
+            p = _rne_to_fp32(a * Fraction(sc))               # the product as binary32 (sc is a binary32 value)
+            n, r = divmod(p.numerator, p.denominator)        # round half to even
+            if 2 * r > p.denominator or (2 * r == p.denominator and n % 2 == 1):
+                n += 1
+            want = min(n, 128 if s < 0 else 127) * (-1 if s < 0 else 1)
+        assert int(og.requantize_i8(np.array([s]), np.float32(sc))[0]) == want, (s, sc)
+    assert got.shape == sums.shape
