@@ -209,3 +209,31 @@ def test_i8_tvw_requantised_and_full_size_samples():
     want = og.requantize_i8(og.gemm_i8_oracle(A[rows], B, mask), scale)
     assert (np.abs(want) < 100).any() and (np.abs(want) == 127).any()
     assert np.array_equal(C[rows], want.astype(np.int64))
+
+
+def test_i8_requantisation_of_sums_beyond_24_bits():
+    """Sums of 2^24 + 1 and 2^24 + 3 are not binary32 values: the conversion must round them to even
+    (2^24 and 2^24 + 4) before the one fp32 product, which a scale of 2.5 * 2^-24 turns into 2.5
+    (-> 2, half to even) and 2.5000006 (-> 3)."""
+    K, N, G, M = 1043, 64, 64, 20
+    a = np.zeros(K, np.int8)
+    cols = np.zeros((K, 3), np.int8)
+    a[:1040] = 127; cols[:1040, :] = 127                   # 1040 * 16129 = 16774160
+    a[1040] = 24; cols[1040, :] = 127                      # + 3048
+    a[1041] = 9; cols[1041, :] = 1                         # + 9          = 2^24 + 1
+    a[1042] = 2; cols[1042, 2] = 1                         # third column: + 2 = 2^24 + 3
+    cols[:, 1] = -cols[:, 1]                               # second column: -(2^24 + 1)
+    A = np.tile(a, (M, 1))
+    B = np.zeros((K, N), np.int8)
+    B[:, :3] = cols
+    mask = np.ones((K, N), np.uint8)
+    scale = float(np.float32(2.5 * 2.0 ** -24))
+    sums = og.gemm_i8_oracle(A, B, mask)
+    assert sums[0, :3].tolist() == [2 ** 24 + 1, -(2 ** 24 + 1), 2 ** 24 + 3]
+    p = tw.tw_pack_i8(B, mask, G)
+    C32, _ = gu.run_tw_i8(tw, p, A, N)
+    C8, _ = gu.run_tw_i8(tw, p, A, N, c_dtype=1, scale=scale)
+    p.free()
+    assert np.array_equal(C32, sums)
+    assert np.array_equal(C8, og.requantize_i8(sums, scale).astype(np.int64))
+    assert C8[0, :3].tolist() == [2, -2, 3]
