@@ -237,3 +237,24 @@ def test_i8_requantisation_of_sums_beyond_24_bits():
     assert np.array_equal(C32, sums)
     assert np.array_equal(C8, og.requantize_i8(sums, scale).astype(np.int64))
     assert C8[0, :3].tolist() == [2, -2, 3]
+
+
+def test_i8_refuses_what_the_32_bit_addressing_cannot_reach():
+    """K * lda >= 2^32 bytes of A: refused with a status before anything is launched (the pointers
+    are never dereferenced)."""
+    K, N, G = 70000, 64, 64
+    B = np.zeros((K, N), np.int8)
+    B[::1000, :] = 1
+    mask = np.zeros((K, N), np.uint8)
+    mask[::1000, :] = 1
+    p = tw.tw_pack_i8(B, mask, G)
+    fake = 0x7f0000000000
+    with pytest.raises(tw.TwError) as ei:
+        tw.tw_gemm_i8(fake, 65536, 65536, p, fake, 65536)
+    assert ei.value.status == 3
+    # the same weight with a short M is fine and exact
+    M = 48
+    A = wl.rng_i8(80, (M, K))
+    C, _ = gu.run_tw_i8(tw, p, A, N)
+    p.free()
+    assert np.array_equal(C, og.gemm_i8_oracle(A, B, mask))
