@@ -447,7 +447,18 @@ static tw_status gemm_i8_launch(const void* A, int M, int lda, tw_handle_t h, vo
     const int tm = h->G != 128 ? 128 : (forced == 64 || forced == 128) ? forced : (wgs128 <= 256 ? 64 : 128);
     e = twg::launch_tvw_i8(h->G, tm, g, (hipStream_t)stream);
   } else {
-    e = twg::launch_tw_i8(h->G, pick_tile_m_i8(M, h->n_tiles > 0 ? h->n_tiles : 1, h->G), g, (hipStream_t)stream);
+    // long K with too few tiles to fill the chip: split K inside the workgroup (as the fp16 path)
+    const int tm = pick_tile_m_i8(M, h->n_tiles > 0 ? h->n_tiles : 1, h->G);
+    const int ks = opt_ksplit.load();
+    int tmk = tm;
+    e = hipErrorInvalidValue;
+    // (from 12 stages of 64 rows on: below that the reduction through LDS costs more than it saves)
+    if (ks == 2 || (ks == 0 && h->max_kp >= 768 && use_ksplit(M, h->n_tiles, h->max_kp, &tmk))) {
+      if (ks == 2) tmk = tm == 256 ? 128 : tm;
+      if (h->G == 64) tmk = 128;
+      e = twg::launch_tw_i8(h->G, tmk, 2, g, (hipStream_t)stream);
+    }
+    if (e == hipErrorInvalidValue) e = twg::launch_tw_i8(h->G, tm, 1, g, (hipStream_t)stream);
   }
   if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;

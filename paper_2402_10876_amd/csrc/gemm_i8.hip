@@ -90,17 +90,23 @@ constexpr int D8 = 3;        // stages in flight
 
 }  // namespace
 
-template <int TM, int TN, int WAVES_M, bool DENSE, bool OUT8>
+// KSPLIT = 2: two groups of four waves own the same output tile; a stage then holds 128
+// condensed rows, group g multiplies rows 64g..64g+63 of it and the partial sums are added
+// through LDS before the epilogue (long K with too few tiles to fill the chip).
+template <int TM, int TN, int WAVES_M, bool DENSE, bool OUT8, int NWAVES = 4, int KSPLIT = 1>
 // (the 256 x 128 instance holds 128 accumulators per lane; its epilogue must not push the
 // register count past two waves per SIMD, which the 72 KiB of LDS allow)
-__global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i8_kernel(GemmI8Args g) {
-  constexpr int NWAVES = 4, NT = 256, D = D8;
-  constexpr int WAVES_N = NWAVES / WAVES_M;
+__global__ __launch_bounds__(NWAVES * 64, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i8_kernel(GemmI8Args g) {
+  constexpr int NT = NWAVES * 64, D = D8;
+  constexpr int WPG = NWAVES / KSPLIT;       // waves per K group
+  constexpr int KSS = KS8 * KSPLIT;          // condensed rows per pipeline stage
+  static_assert(!(DENSE && KSPLIT > 1), "the dense baseline does not split K");
+  constexpr int WAVES_N = WPG / WAVES_M;
   constexpr int WM = TM / WAVES_M, WN = TN / WAVES_N;
   constexpr int MB = WM / 32, NB = WN / 32;
   static_assert(MB >= 1 && NB >= 1, "wave tile must hold a 32x32 block");
   constexpr int RBA = TM, RBB = TN;                    // LDS row bytes
-  constexpr int STAGE_A = KS8 * RBA, STAGE_B = KS8 * RBB, STAGE = STAGE_A + STAGE_B;
+  constexpr int STAGE_A = KSS * RBA, STAGE_B = KSS * RBB, STAGE = STAGE_A + STAGE_B;
   static_assert(STAGE_A % (1024 * NWAVES) == 0 && STAGE_B % (1024 * NWAVES) == 0,
                 "a stage is a whole number of 1 KiB copies per wave");
   constexpr int NIA = STAGE_A / (1024 * NWAVES), NIB = STAGE_B / (1024 * NWAVES);
@@ -112,6 +118,8 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
   constexpr int HN = TN / 2;
   static_assert(HN % 32 == 0, "");
   constexpr int PIPE_BYTES = D * STAGE, EPI_BYTES = HN * CS;
+  constexpr int RED_BYTES = KSPLIT > 1 ? TM * TN * 4 : 0;      // partial sums of group 1
+  static_assert(RED_BYTES <= PIPE_BYTES, "the reduction reuses the pipeline buffers");
   constexpr int LDS_BYTES = PIPE_BYTES > EPI_BYTES ? PIPE_BYTES : EPI_BYTES;
   __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
 
@@ -126,12 +134,13 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
   tile_of_workgroup(g, blockIdx.x, n_gemm, mt, t);
   const int m0 = mt * TM;
 
-  int kp0, ns;                           // ns: stages of 64 rows
-  if constexpr (DENSE) { kp0 = 0; ns = g.K / KS8; }    // host guarantees K % 64 == 0
+  int kp0, ns64;                         // ns64: stages of 64 rows
+  if constexpr (DENSE) { kp0 = 0; ns64 = g.K / KS8; }  // host guarantees K % 64 == 0
   else {
     const int4v rec = scalar_load4(g.tile_sched + 4 * t);
-    t = rec[0]; kp0 = rec[1]; ns = rec[2] / KS8;
+    t = rec[0]; kp0 = rec[1]; ns64 = rec[2] / KS8;
   }
+  const int ns = (ns64 + KSPLIT - 1) / KSPLIT;         // pipeline stages of KSS rows
   const int8_t* Bt = DENSE ? g.vals + (size_t)t * TN : g.vals + (size_t)kp0 * TN;
   const uint32_t ldb = DENSE ? (uint32_t)g.ldb : (uint32_t)TN;
 
@@ -175,7 +184,7 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
     if constexpr (!DENSE) {
 #pragma unroll
       for (int j = 0; j < NIA; ++j) {
-        const int* rp = g.row_idx + kp0 + s * KS8 + (wave * NIA + j) * RPIA;
+        const int* rp = g.row_idx + kp0 + s * KSS + (wave * NIA + j) * RPIA;
         if constexpr (RPIA == 4) asm volatile("s_load_dwordx4 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
         else if constexpr (RPIA == 8) asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
         else asm volatile("s_load_dwordx16 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
@@ -193,7 +202,7 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
   auto issue = [&](int s, const Rows& rows) {     // copies of stage s; rows = its kept-row indices
     char* dstA = lds + (s % D) * STAGE;
     char* dstB = dstA + STAGE_A;
-    const uint32_t bs = (uint32_t)s * (uint32_t)KS8 * ldb;
+    const uint32_t bs = (uint32_t)s * (uint32_t)KSS * ldb;
 #pragma unroll
     for (int j = 0; j < NIB; ++j)
       __builtin_amdgcn_global_load_lds(GLOBAL_PTR(Bbase + (bs + b_off[j])),
@@ -201,7 +210,7 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
 #pragma unroll
     for (int j = 0; j < NIA; ++j) {
       int row;
-      if constexpr (DENSE) row = s * KS8 + (wave * NIA + j) * RPIA + a_rloc;
+      if constexpr (DENSE) row = s * KSS + (wave * NIA + j) * RPIA + a_rloc;
       else {
         row = rows.r[j][0];
 #pragma unroll
@@ -220,7 +229,9 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
 
-  const int wm = wave % WAVES_M, wn = wave / WAVES_M;
+  const int grp = KSPLIT == 1 ? 0 : wave / WPG;        // K group
+  const int wl = KSPLIT == 1 ? wave : wave % WPG;      // wave inside the group
+  const int wm = wl % WAVES_M, wn = wl / WAVES_M;
   // per-lane LDS byte address of each operand block at stage buffer 0, k-step 0
   const uint32_t lds0 = (uint32_t)(uintptr_t)LDS_PTR(char, lds);
   const int p = lane & 15, q = lane >> 4;
@@ -228,9 +239,10 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
   const int fcol = 16 * (q & 1) + 8 * (p & 1);
   uint32_t fa[MB], fb[NB];
 #pragma unroll
-  for (int i = 0; i < MB; ++i) fa[i] = lds0 + swz8<RBA>(frow, wm * WM + i * 32 + fcol);
+  for (int i = 0; i < MB; ++i) fa[i] = lds0 + grp * (KS8 * RBA) + swz8<RBA>(frow, wm * WM + i * 32 + fcol);
 #pragma unroll
-  for (int j = 0; j < NB; ++j) fb[j] = lds0 + STAGE_A + swz8<RBB>(frow, wn * WN + j * 32 + fcol);
+  for (int j = 0; j < NB; ++j)
+    fb[j] = lds0 + STAGE_A + grp * (KS8 * RBB) + swz8<RBB>(frow, wn * WN + j * 32 + fcol);
 
   constexpr int NF = MB + NB;
   Frag8 f0[NF], f1[NF];      // operands of k-steps 0 and 1 of a stage
@@ -272,6 +284,7 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
       if (d < ns) issue(d, pro[d]);
     rows_cur = pro[D - 1];
   }
+  bool live_prev = false;
   for (int s = 0; s < ns; ++s) {
     // own copies of stage s have landed: at most the copies of the one newer stage remain
     if (s + 1 < ns) wait_vm<NPS>();
@@ -281,18 +294,43 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
     fetch_rows(s + D < ns ? s + D : ns - 1, rows_next);   // needed by the next iteration
     const uint32_t boff = (uint32_t)((s % D) * STAGE);
     read_step(boff, K0{}, f0);
-    if (s > 0) mfma_step(f1);            // second k-step of the previous stage
+    if (KSPLIT == 1 ? s > 0 : live_prev) mfma_step(f1);   // second k-step of the previous stage
+    const bool live = KSPLIT == 1 || s * KSPLIT + grp < ns64;   // false only for group 1 on an odd tail
     wait_lds8<NF>(f0);                   // full wait: the scalar loads above are in as well
     tie_rows(rows_next);
     // the copies of stage s+D-1 go into the buffer of stage s-1, which every wave has
     // finished reading
     if (s + D - 1 < ns) issue(s + D - 1, rows_cur);
     read_step(boff, K32{}, f1);
-    mfma_step(f0);
+    if (live) mfma_step(f0);
+    live_prev = live;
     rows_cur = rows_next;
     wait_lds8<NF>(f1);
   }
-  if (ns > 0) mfma_step(f1);
+  if (KSPLIT == 1 ? ns > 0 : live_prev) mfma_step(f1);
+
+  if constexpr (KSPLIT > 1) {
+    // group 1 hands its partial sums to group 0: [wave in group][register][lane]
+    __syncthreads();
+    int* red = (int*)lds + wl * (MB * NB * 16 * 64) + lane;
+    if (grp == 1) {
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) red[((i * NB + j) * 16 + r) * 64] = acc[i][j][r];
+    }
+    __syncthreads();
+    if (grp == 0) {
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][j][r] += red[((i * NB + j) * 16 + r) * 64];
+    }
+  }
 
   if constexpr (OUT8) {
     // ---- epilogue, int8 output: requantise in registers, stage the whole tile as bytes
@@ -313,6 +351,7 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
       else cols[i] = g.col_idx[t * TN + n];
     }
     __syncthreads();                             // the pipeline buffers are free
+    if (grp == 0) {
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -328,6 +367,7 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
           *(uint32_t*)(lds + n * CS8 + mm) = pk;
         }
       }
+    }
     __syncthreads();
     int4v pc[NPASS];
 #pragma unroll
@@ -371,6 +411,7 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
       else cols[i] = g.col_idx[t * TN + n];
     }
     __syncthreads();                     // pipeline buffers / the previous half are free
+    if (grp == 0) {
 #pragma unroll
     for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -387,6 +428,7 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
           *(int4v*)(lds + n * CS + mm * 4) = v;
         }
       }
+    }
     __syncthreads();
     // all staged pieces into registers first (unconditional reads), then the stores
     int4v pc[NPASS];
@@ -414,15 +456,17 @@ __global__ __launch_bounds__(256, (TM * TN >= 256 * 128) ? 2 : 1) void tw_gemm_i
   }
 }
 
-template <int TM, int TN, int WAVES_M, bool DENSE>
+template <int TM, int TN, int WAVES_M, bool DENSE, int NWAVES = 4, int KSPLIT = 1>
 static hipError_t launch8(const GemmI8Args& g, hipStream_t stream) {
   const int grid = g.n_mtiles * g.n_tiles + g.n_zero;
   if (grid <= 0) return hipSuccess;
   (void)hipGetLastError();   // an error left behind by an earlier call of this thread is not this launch's
   if (g.c_i8)
-    hipLaunchKernelGGL((tw_gemm_i8_kernel<TM, TN, WAVES_M, DENSE, true>), dim3(grid), dim3(256), 0, stream, g);
+    hipLaunchKernelGGL((tw_gemm_i8_kernel<TM, TN, WAVES_M, DENSE, true, NWAVES, KSPLIT>), dim3(grid),
+                       dim3(NWAVES * 64), 0, stream, g);
   else
-    hipLaunchKernelGGL((tw_gemm_i8_kernel<TM, TN, WAVES_M, DENSE, false>), dim3(grid), dim3(256), 0, stream, g);
+    hipLaunchKernelGGL((tw_gemm_i8_kernel<TM, TN, WAVES_M, DENSE, false, NWAVES, KSPLIT>), dim3(grid),
+                       dim3(NWAVES * 64), 0, stream, g);
   return hipGetLastError();
 }
 
@@ -437,7 +481,14 @@ static hipError_t dispatch8(int G, int tm, GemmI8Args& g, hipStream_t stream) {
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_tw_i8(int G, int tm, GemmI8Args g, hipStream_t stream) {
+hipError_t launch_tw_i8(int G, int tm, int ksplit, GemmI8Args g, hipStream_t stream) {
+  if (ksplit == 2) {          // two K groups of four waves
+    g.n_mtiles = (g.M + tm - 1) / tm;
+    if (G == 128 && tm == 64) return launch8<64, 128, 1, false, 8, 2>(g, stream);
+    if (G == 128 && tm == 128) return launch8<128, 128, 2, false, 8, 2>(g, stream);
+    if (G == 64 && tm == 128) return launch8<128, 64, 2, false, 8, 2>(g, stream);
+    return hipErrorInvalidValue;
+  }
   return dispatch8<false>(G, tm, g, stream);
 }
 

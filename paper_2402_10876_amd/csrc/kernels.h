@@ -57,7 +57,8 @@ struct GemmI8Args {
 };
 // G / tn in {64, 128}, tm in {128, 256} (and 64 for G = 128); hipErrorInvalidValue when no instance exists.
 // The dense variant needs K % 64 == 0.
-hipError_t launch_tw_i8(int G, int tm, GemmI8Args g, hipStream_t stream);
+// ksplit = 2: two groups of four waves split K inside the workgroup (G = 128 with tm 64 / 128, G = 64 with tm 128).
+hipError_t launch_tw_i8(int G, int tm, int ksplit, GemmI8Args g, hipStream_t stream);
 hipError_t launch_dense_i8(int tn, int tm, GemmI8Args g, hipStream_t stream);
 // int8 TVW on the sparse matrix instruction (gemm_tvw_i8.hip): G = 128 with tm in {64, 128}, G = 64 with tm = 128.
 hipError_t launch_tvw_i8(int G, int tm, GemmI8Args g, hipStream_t stream);

@@ -15,8 +15,10 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(autouse=True)
 def _reset_options():
     tw.tw_set_option("tile_m", 0)
+    tw.tw_set_option("ksplit", 0)
     yield
     tw.tw_set_option("tile_m", 0)
+    tw.tw_set_option("ksplit", 0)
 
 
 def _case(seed, M, K, N, G, col_keep=0.8, row_keep=0.5):
@@ -258,3 +260,46 @@ def test_i8_refuses_what_the_32_bit_addressing_cannot_reach():
     C, _ = gu.run_tw_i8(tw, p, A, N)
     p.free()
     assert np.array_equal(C, og.gemm_i8_oracle(A, B, mask))
+
+
+@pytest.mark.parametrize("G,tile_m", [(128, 64), (128, 128), (64, 128)])
+@pytest.mark.parametrize("stages64", [1, 4, 7])
+@pytest.mark.parametrize("c_dtype", [0, 1])
+def test_i8_k_split_inside_the_workgroup(G, tile_m, stages64, c_dtype):
+    """Two K groups per workgroup: an odd number of 64-row stages leaves group 1 idle on the tail."""
+    M, N = 200, 300
+    K = 64 * stages64 + 90                        # kept rows per tile: 64*stages64 - 20 .. (ragged)
+    rng = np.random.default_rng(G + tile_m + stages64 + c_dtype)
+    mask = np.zeros((K, N), np.uint8)
+    cols = np.flatnonzero(rng.random(N) < 0.9)
+    for i in range(0, cols.size, G):
+        rows = rng.permutation(K)[:64 * stages64 - int(rng.integers(0, 40))]
+        mask[np.ix_(np.sort(rows), cols[i:i + G])] = 1
+    A, B = wl.rng_i8(90, (M, K)), wl.rng_i8(91, (K, N))
+    scale = 1.0 / 900.0
+    print(f"i8 ksplit G={G} tile_m={tile_m} stages64={stages64} c_dtype={c_dtype}", flush=True)
+    tw.tw_set_option("tile_m", tile_m)
+    tw.tw_set_option("ksplit", 2)
+    p = tw.tw_pack_i8(B, mask, G)
+    C, raw = gu.run_tw_i8(tw, p, A, N, c_dtype=c_dtype, scale=scale)
+    p.free()
+    want = og.gemm_i8_oracle(A, B, mask)
+    if c_dtype:
+        want = og.requantize_i8(want, scale).astype(np.int64)
+    assert np.array_equal(C, want)
+    assert (raw[:, M:] == -77).all()
+
+
+def test_i8_k_split_is_chosen_for_long_k_few_tiles():
+    """3072 x 768 at M = 4096 (the shape the automatic choice splits), sampled rows."""
+    M, K, N, G = 4096, 3072, 768, 128
+    A, B = wl.rng_i8(92, (M, K)), wl.rng_i8(93, (K, N), sigma=30.0)
+    mask = wl.tw_mask(B.astype(np.float16), G, density=0.25, col_frac=0.10)
+    p = tw.tw_pack_i8(B, mask, G)
+    C, _ = gu.run_tw_i8(tw, p, A, N, c_dtype=1, scale=1.0 / 2000.0)
+    p.free()
+    rng = np.random.default_rng(94)
+    rows = np.concatenate([[0, 63, 64, M - 1], rng.integers(0, M, 60)])
+    want = og.requantize_i8(og.gemm_i8_oracle(A[rows], B, mask), 1.0 / 2000.0)
+    assert (np.abs(want) > 10).any()
+    assert np.array_equal(C[rows], want.astype(np.int64))
