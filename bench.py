@@ -78,6 +78,8 @@ def main():
         sys.exit(2)
 
     import torch
+    from paper_2402_10876_amd import build as _build
+    _build.ensure_built()                   # compiles only if no library has been built
     import paper_2402_10876_amd as tw
     import workloads as wl
 

@@ -27,5 +27,11 @@ def build(verbose: bool = False) -> str:
     return LIB
 
 
+def ensure_built() -> str:
+    """Builds the library only if there is none (tests, the smoke check and the benchmark call
+    this; the binding itself never builds and fails loudly when the library is missing)."""
+    return LIB if os.path.exists(os.environ.get("TWGEMM_LIB") or LIB) else build()
+
+
 if __name__ == "__main__":
     print(build(verbose=True))
