@@ -30,17 +30,23 @@ def valid_positions(*, B: int, H: int, W: int, P: int, L: int) -> np.ndarray:
     return ((m // P) % L < H) & (m % P < W)
 
 
-def im2col_wide(X: np.ndarray, *, R: int, S: int, B: int, H: int, W: int, P: int, L: int) -> np.ndarray:
-    """The img2col matrix over the wide grid: (B*L*P) x (C*R*S), rows of invalid positions 0."""
+def im2col_wide(X: np.ndarray, *, R: int, S: int, B: int, H: int, W: int, P: int, L: int,
+                rows=None) -> np.ndarray:
+    """The img2col matrix over the wide grid: (B*L*P) x (C*R*S), rows of invalid positions 0.
+    `rows` (positions m of the wide grid) asks for those rows of the matrix only, in that order:
+    the same definition, for checks at sizes where the whole matrix is too large to multiply."""
     C, ldx = X.shape
     if L < H + R - 1 or P < W + S - 1 or ldx < B * L * P:
         raise ValueError("image block too small for the filter, or X too short")
-    mv = np.flatnonzero(valid_positions(B=B, H=H, W=W, P=P, L=L))
-    A = np.zeros((B * L * P, C * R * S), X.dtype)
+    valid = valid_positions(B=B, H=H, W=W, P=P, L=L)
+    pos = np.arange(B * L * P) if rows is None else np.asarray(rows, dtype=np.int64)
+    sel = np.flatnonzero(valid[pos])           # rows of the result that are output pixels
+    mv = pos[sel]
+    A = np.zeros((pos.size, C * R * S), X.dtype)
     for c in range(C):
         for r in range(R):
             for s in range(S):
-                A[mv, (c * R + r) * S + s] = X[c, mv + r * P + s]
+                A[sel, (c * R + r) * S + s] = X[c, mv + r * P + s]
     return A
 
 

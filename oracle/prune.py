@@ -18,12 +18,12 @@ Readings where the algorithms are silent:
     equal magnitudes the lower position is kept.
   * a last tile narrower than G scores its rows by the mean, not the sum, when
     one threshold is shared by all tiles.
-  * TEW's remedy step ("restore delta percent of the weight elements with the
-    highest importance scores", Section III-A; Algorithm 3, TEW: scores of kept
-    elements zeroed, threshold at the (1 - delta) percentile over all K*N
-    scores) is made deterministic as: of the elements the TW step pruned,
-    restore the floor(delta * K * N) highest by (score descending, flat index
-    ascending); fewer if fewer were pruned.
+  * TEW's remedy step (Section III-A; Algorithm 3, TEW, where the scores of kept
+    elements are zeroed and the threshold sits at the (1 - delta) percentile over
+    all K*N scores) puts back a delta share of the weight's elements, the
+    highest-scored ones.  Made deterministic as: of the elements the TW step
+    pruned, restore the floor(delta * K * N) highest by (score descending, flat
+    index ascending); fewer if fewer were pruned.
 """
 from __future__ import annotations
 

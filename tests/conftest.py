@@ -13,9 +13,15 @@ def pytest_configure(config):
 
 
 def pytest_sessionstart(session):
-    # load what is built; compile (hipcc cross-compiles without a GPU) only if nothing is
+    # load what is built if it matches the sources; otherwise compile (hipcc cross-compiles
+    # without a GPU)
     from paper_2402_10876_amd import build
     build.ensure_built()
+
+
+def pytest_report_header(config):
+    from paper_2402_10876_amd import build
+    return "libtwgemm: " + build.describe()
 
 
 @pytest.fixture(scope="session")

@@ -118,12 +118,8 @@ def test_conv_vgg_layer_on_sampled_positions(layer, G):
     valid = np.flatnonzero(oc.valid_positions(B=g.B, H=g.H, W=g.W, P=g.P, L=g.L))
     rng = np.random.default_rng(13)
     pos = np.concatenate([valid[:3], valid[-3:], rng.choice(valid, 58, replace=False)])
-    Bm = Bw.astype(np.float64) * (mask != 0)
-    for m in pos:
-        win = np.stack([X[:, m + r * g.P + s] for r in range(g.R) for s in range(g.S)], 1).reshape(-1)  # (c, r, s)
-        ref = win.astype(np.float64) @ Bm
-        S = np.abs(win.astype(np.float64)) @ np.abs(Bm)
-        assert (np.abs(Cw[m] - ref) <= 4e-3 * S + 1e-30).all()
+    A_rows = oc.im2col_wide(X, rows=pos, **g.ints())             # those rows of the img2col matrix
+    assert_C_close(Cw[pos], og.gemm_oracle(A_rows, Bw, mask), og.abs_bound(A_rows, Bw, mask))
     inval = ~oc.valid_positions(B=g.B, H=g.H, W=g.W, P=g.P, L=g.L)
     assert (raw[:, :g.Mp][:, inval].view(np.uint16) == 0).all()
 

@@ -102,3 +102,11 @@ def test_configured_layers_have_the_configured_sizes():
     (n1, g1, N1), (n2, g2, N2) = wl.CONV_LAYERS
     assert (g1.K, N1, g1.B * g1.H * g1.W) == (2304, 256, 25088)
     assert (g2.K, N2, g2.B * g2.H * g2.W) == (4608, 512, 1568)
+
+
+def test_row_subset_is_a_slice_of_the_matrix():
+    g = wl.same_geom(3, 3, 2, 2, 5, 4)
+    X = wl.make_conv_input(9, g)
+    full = oc.im2col_wide(X, **g.ints())
+    rows = np.array([0, g.Mp - 1, 7, 7, 3, g.P - 1, g.L * g.P + 2])      # valid and padding positions, a repeat
+    assert np.array_equal(oc.im2col_wide(X, rows=rows, **g.ints()), full[rows])
