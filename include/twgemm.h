@@ -52,7 +52,9 @@ typedef enum {
   TW_ERR_UNSUPPORTED = 3, /* valid request this build has no kernel for                   */
   TW_ERR_ALLOC = 4,       /* host or device allocation failed                             */
   TW_ERR_HIP = 5,         /* a HIP runtime call failed (no device, launch error)          */
-  TW_ERR_STATE = 6        /* handle has no device copy yet / already freed                */
+  TW_ERR_STATE = 6,       /* handle has no device copy yet / already freed                */
+  TW_ERR_TOO_LARGE = 7    /* tw_prune_dev_static: the problem needs more scratch than the
+                             library's fixed array holds                                  */
 } tw_status;
 
 typedef enum { TW_PATTERN_TW = 0, TW_PATTERN_TVW = 1, TW_PATTERN_TEW = 2 } tw_pattern;
@@ -168,6 +170,25 @@ tw_status tw_prune_dev(const void* B_dev, int K, int N, int ldb, int G, int patt
                        int n_cols_pruned, int rows_per_tile, uint8_t* mask_dev,
                        uint8_t* tile_mask_dev, void* workspace_dev, size_t workspace_bytes,
                        void* stream);
+
+/*
+ * tw_prune_dev_static - tw_prune_dev for callers that cannot allocate or hand over device
+ * memory beyond inputs and outputs: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments minus the workspace, same kernels, same
+ * result; the scratch is a fixed array of 8 MiB inside the library's device code (one per
+ * GPU, held until the process ends) instead of a caller buffer.  The call allocates nothing
+ * (no hipMalloc / hipFree, no allocating library routine).
+ *   Limit: tw_prune_workspace_bytes(K, N, G) <= 8 MiB, i.e. ceil(N/G) * K * 28 + N * 28 bytes
+ *   plus alignment (768 x 3072 at G = 128: 0.6 MiB; 4096 x 4096 at G = 128: 3.6 MiB); larger
+ *   problems get TW_ERR_TOO_LARGE and nothing is enqueued.
+ *   Every call on a GPU shares that GPU's array: calls that overlap on one GPU (two streams,
+ *   two threads) race; serialise them or use tw_prune_dev with separate workspaces.  Nothing
+ *   in the array has to start at zero; it keeps the last call's contents.
+ * Errors: as tw_prune_dev, plus TW_ERR_TOO_LARGE.
+ */
+tw_status tw_prune_dev_static(const void* B_dev, int K, int N, int ldb, int G, int pattern,
+                              int n_cols_pruned, int rows_per_tile, uint8_t* mask_dev,
+                              uint8_t* tile_mask_dev, void* stream);
 
 /* tw_pack_dev - tw_pack for a weight and masks in device memory: copies them to the
  * host on `stream`, waits for the copies, packs and uploads. */

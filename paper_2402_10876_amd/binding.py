@@ -15,7 +15,7 @@ DTYPE_F16, DTYPE_I8 = 0, 1
 
 EXPORTED_SYMBOLS = [
     "tw_pack_host", "tw_upload", "tw_pack", "tw_pack_dev", "tw_prune_dev",
-    "tw_prune_workspace_bytes", "tw_concat", "tw_gemm", "tw_dense_gemm", "tw_export",
+    "tw_prune_workspace_bytes", "tw_prune_dev_static", "tw_concat", "tw_gemm", "tw_dense_gemm", "tw_export",
     "tw_unpack", "tw_free", "tw_status_str", "tw_set_option", "tw_flop_counts",
     "tw_pack_i8_host", "tw_pack_i8", "tw_gemm_i8", "tw_dense_gemm_i8", "tw_conv_bind", "tw_conv_gemm", "tw_conv_gemm_i8",
 ]
@@ -67,6 +67,7 @@ def lib():
         L.tw_concat.argtypes = [C.POINTER(vp), i, i, C.POINTER(vp)]
         L.tw_prune_workspace_bytes.argtypes = [i, i, i, C.POINTER(C.c_size_t)]
         L.tw_prune_dev.argtypes = [vp, i, i, i, i, i, i, i, vp, vp, vp, C.c_size_t, vp]
+        L.tw_prune_dev_static.argtypes = [vp, i, i, i, i, i, i, i, vp, vp, vp]
         L.tw_pack_dev.argtypes = [vp, i, vp, vp, i, i, i, i, vp, C.POINTER(vp)]
         L.tw_gemm.argtypes = [vp, i, i, i, vp, vp, i, vp]
         L.tw_pack_i8_host.argtypes = [vp, vp, vp, i, i, i, i, C.POINTER(vp)]
@@ -254,6 +255,13 @@ def tw_prune_dev(B_ptr: int, K: int, N: int, ldb: int, G: int, pattern: int, n_c
     """Device addresses in, K x N byte masks out (device); see include/twgemm.h."""
     _check(lib().tw_prune_dev(B_ptr, K, N, ldb, G, int(pattern), n_cols_pruned, rows_per_tile, mask_ptr,
                               tile_mask_ptr, workspace_ptr, workspace_bytes, stream), "tw_prune_dev")
+
+
+def tw_prune_dev_static(B_ptr: int, K: int, N: int, ldb: int, G: int, pattern: int, n_cols_pruned: int,
+                        rows_per_tile: int, mask_ptr: int, tile_mask_ptr, stream: int = 0):
+    """tw_prune_dev without a workspace argument: the scratch is a fixed array inside the library."""
+    _check(lib().tw_prune_dev_static(B_ptr, K, N, ldb, G, int(pattern), n_cols_pruned, rows_per_tile, mask_ptr,
+                                     tile_mask_ptr, stream), "tw_prune_dev_static")
 
 
 def tw_pack_dev(B_ptr: int, ldb: int, mask_ptr: int, tile_mask_ptr, K: int, N: int, G: int, pattern: int,

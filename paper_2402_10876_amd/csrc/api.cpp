@@ -85,6 +85,7 @@ const char* tw_status_str(int s) {
     case TW_ERR_ALLOC: return "allocation failed";
     case TW_ERR_HIP: return "HIP runtime error";
     case TW_ERR_STATE: return "handle not uploaded";
+    case TW_ERR_TOO_LARGE: return "problem larger than the library's static scratch (use the entry point that takes a workspace)";
     default: return "unknown status";
   }
 }
@@ -203,8 +204,24 @@ tw_status tw_prune_dev(const void* B_dev, int K, int N, int ldb, int G, int patt
   if (pattern == TW_PATTERN_TEW) return TW_ERR_UNSUPPORTED;
   if (pattern != TW_PATTERN_TW && pattern != TW_PATTERN_TVW) return TW_ERR_ARG;
   if (((uintptr_t)workspace_dev & 15) || workspace_bytes < twg::prune_workspace_bytes(K, N, G)) return TW_ERR_ARG;
+  if (((size_t)K * N + 255) / 256 > 0x7fffffffu) return TW_ERR_UNSUPPORTED;   // one thread per element, grid limit
   hipError_t e = twg::prune_device((const uint16_t*)B_dev, K, N, ldb, G, pattern == TW_PATTERN_TVW, n_cols_pruned,
                                    rows_per_tile, mask_dev, tile_mask_dev, workspace_dev, (hipStream_t)stream);
+  return e == hipSuccess ? TW_OK : TW_ERR_HIP;
+}
+
+tw_status tw_prune_dev_static(const void* B_dev, int K, int N, int ldb, int G, int pattern, int n_cols_pruned,
+                              int rows_per_tile, uint8_t* mask_dev, uint8_t* tile_mask_dev, void* stream) {
+  if (!B_dev || !mask_dev || K < 1 || N < 1 || ldb < N || !valid_G(G)) return TW_ERR_ARG;
+  if (n_cols_pruned < 0 || n_cols_pruned > N || rows_per_tile < 0 || rows_per_tile > K) return TW_ERR_ARG;
+  if (pattern == TW_PATTERN_TEW) return TW_ERR_UNSUPPORTED;
+  if (pattern != TW_PATTERN_TW && pattern != TW_PATTERN_TVW) return TW_ERR_ARG;
+  if (twg::prune_workspace_bytes(K, N, G) > twg::PRUNE_STATIC_SCRATCH_BYTES) return TW_ERR_TOO_LARGE;
+  if (((size_t)K * N + 255) / 256 > 0x7fffffffu) return TW_ERR_TOO_LARGE;
+  void* ws = nullptr;
+  if (twg::prune_static_scratch(&ws) != hipSuccess) { (void)hipGetLastError(); return TW_ERR_HIP; }
+  hipError_t e = twg::prune_device((const uint16_t*)B_dev, K, N, ldb, G, pattern == TW_PATTERN_TVW, n_cols_pruned,
+                                   rows_per_tile, mask_dev, tile_mask_dev, ws, (hipStream_t)stream);
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
 

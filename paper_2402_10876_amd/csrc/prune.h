@@ -17,4 +17,11 @@ hipError_t prune_device(const uint16_t* B, int K, int N, int ldb, int G, bool tv
                         int rows_per_tile, uint8_t* mask, uint8_t* tile_mask, void* workspace,
                         hipStream_t stream);
 
+// The entry point that allocates nothing keeps its scratch in a device array of this size
+// inside the library (one per GPU, for the life of the process).
+constexpr size_t PRUNE_STATIC_SCRATCH_BYTES = 8u << 20;
+
+// Device address of the current device's copy of that array (looked up once per device).
+hipError_t prune_static_scratch(void** out);
+
 }  // namespace twg

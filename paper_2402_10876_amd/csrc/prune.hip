@@ -14,6 +14,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "prune.h"
 
 namespace twg {
@@ -154,34 +156,67 @@ hipError_t prune_device(const uint16_t* B, int K, int N, int ldb, int G, bool tv
   int32_t* row_pos = (int32_t*)w;        w += align_up(ntmax * K * 4);
   int32_t* row_list = (int32_t*)w;
   const int T = 256;
-  hipLaunchKernelGGL(column_scores, dim3((N + T - 1) / T), dim3(T), 0, stream, B, K, N, ldb, col_score);
-  hipLaunchKernelGGL(keep_all_but_lowest, dim3((N + T - 1) / T, 1), dim3(T), 0, stream, col_score, N,
-                     n_cols_pruned, col_keep);
-  hipLaunchKernelGGL(compact, dim3(1), dim3(1024), 0, stream, col_keep, N, col_pos, kept_cols);
+  (void)hipGetLastError();   // an error left behind by an earlier call of this thread is not this call's
+  // a failed launch ends the call: later kernels would read workspace nobody wrote
+#define TWG_LAUNCH(kernel, grid, block, ...)                                  \
+  do {                                                                        \
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, __VA_ARGS__);          \
+    const hipError_t e_ = hipGetLastError();                                  \
+    if (e_ != hipSuccess) return e_;                                          \
+  } while (0)
+  TWG_LAUNCH(column_scores, dim3((N + T - 1) / T), dim3(T), B, K, N, ldb, col_score);
+  TWG_LAUNCH(keep_all_but_lowest, dim3((N + T - 1) / T, 1), dim3(T), col_score, N, n_cols_pruned, col_keep);
+  TWG_LAUNCH(compact, dim3(1), dim3(1024), col_keep, N, col_pos, kept_cols);
   if (nt > 0) {
-    hipLaunchKernelGGL(tile_row_scores, dim3((K + T - 1) / T, nt), dim3(T), 0, stream, B, K, ldb, G, n_kept,
-                       kept_cols, row_score);
-    hipLaunchKernelGGL(keep_all_but_lowest, dim3((K + T - 1) / T, nt), dim3(T), 0, stream, row_score, K,
-                       K - rows_per_tile, row_keep);
+    TWG_LAUNCH(tile_row_scores, dim3((K + T - 1) / T, nt), dim3(T), B, K, ldb, G, n_kept, kept_cols, row_score);
+    TWG_LAUNCH(keep_all_but_lowest, dim3((K + T - 1) / T, nt), dim3(T), row_score, K, K - rows_per_tile, row_keep);
   }
   const size_t total = (size_t)K * N;
-  const unsigned eb = (unsigned)((total + T - 1) / T);
+  const unsigned eb = (unsigned)((total + T - 1) / T);      // the caller keeps K * N / 256 inside the grid limit
   if (tvw) {      // tile mask (if asked for) and an all-zero element mask for the 2:4 step to fill
-    hipLaunchKernelGGL(emit_tile_mask, dim3(eb), dim3(T), 0, stream, K, N, G, col_pos, row_keep, tile_mask, mask);
+    TWG_LAUNCH(emit_tile_mask, dim3(eb), dim3(T), K, N, G, col_pos, row_keep, tile_mask, mask);
   } else {        // TW: the element mask is the tile mask
-    hipLaunchKernelGGL(emit_tile_mask, dim3(eb), dim3(T), 0, stream, K, N, G, col_pos, row_keep, mask,
-                       (uint8_t*)nullptr);
+    TWG_LAUNCH(emit_tile_mask, dim3(eb), dim3(T), K, N, G, col_pos, row_keep, mask, (uint8_t*)nullptr);
     if (tile_mask)
-      hipLaunchKernelGGL(emit_tile_mask, dim3(eb), dim3(T), 0, stream, K, N, G, col_pos, row_keep, tile_mask,
-                         (uint8_t*)nullptr);
+      TWG_LAUNCH(emit_tile_mask, dim3(eb), dim3(T), K, N, G, col_pos, row_keep, tile_mask, (uint8_t*)nullptr);
   }
   if (tvw && nt > 0 && rows_per_tile > 0) {
-    hipLaunchKernelGGL(compact, dim3(nt), dim3(1024), 0, stream, row_keep, K, row_pos, row_list);
+    TWG_LAUNCH(compact, dim3(nt), dim3(1024), row_keep, K, row_pos, row_list);
     const int groups = (rows_per_tile + 3) / 4;
-    hipLaunchKernelGGL(two_of_four, dim3((G + 63) / 64, groups, nt), dim3(64), 0, stream, B, K, N, ldb, G, n_kept,
-                       rows_per_tile, kept_cols, row_list, mask);
+    TWG_LAUNCH(two_of_four, dim3((G + 63) / 64, groups, nt), dim3(64), B, K, N, ldb, G, n_kept, rows_per_tile,
+               kept_cols, row_list, mask);
   }
-  return hipGetLastError();
+#undef TWG_LAUNCH
+  return hipSuccess;
+}
+
+// ---- scratch for callers that cannot allocate -------------------------------------------
+// One array per GPU, held until the process ends.  In host code its name is only a stand-in:
+// the device address comes from hipGetSymbolAddress, once per device, and that pointer is what
+// the kernels receive.
+static __device__ __align__(256) unsigned char scratch[PRUNE_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int MAX_DEVICES = 64;
+std::mutex scratch_mutex;
+void* scratch_ptr[MAX_DEVICES];     // per device: address of that device's copy of `scratch`
+}  // namespace
+
+hipError_t prune_static_scratch(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(scratch_mutex);
+  if (!scratch_ptr[dev]) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    scratch_ptr[dev] = p;
+  }
+  *out = scratch_ptr[dev];
+  return hipSuccess;
 }
 
 }  // namespace twg
