@@ -18,8 +18,16 @@ Each step works on its own set of activations, outputs and packed weights out of
 operands come from HBM rather than from the 256 MB last-level cache.
 
 Prints ONE JSON line: dense-equivalent TFLOP/s of the whole step, plus
-`roofline` (the grouped GEMM kernel, HBM-bound at this sparsity) and
-`cpu_baseline` (the fp64 oracle timed on the host cores).
+  roofline      the grouped GEMM kernel against the HBM roof, from the same timed loop
+                (HIP events on the launch stream around the K steps);
+  calibration   what this machine sustains for plain streams and register-only matrix-core
+                loops (tw_calibrate kernels timed with events);
+  rows          every other configured workload as one row each (BERT-base TVW, the
+                BERT-large FFN sparsity sweep, the VGG-16 im2col GEMMs): time, our dense
+                kernel's time, binding roof and the fraction of it (outside the timed region);
+  cpu_baseline  the fp64 oracle timed on the host cores.
+`--calibrate` runs the calibration kernels alone (the command the rocprofv3 summary in
+profiles/ was taken with).
 """
 from __future__ import annotations
 
@@ -36,16 +44,13 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 FP16_PEAK_TFLOPS = 2500.0
-# fp16 matrix-core rate reached on the box by a register-only v_mfma_f32_32x32x16_f16 loop
-# (a microbenchmark, not part of this script): context for the utilisation figures
-MEASURED_MFMA_LOOP_TFLOPS = 1970.0
 PLAN = [(0, 4), (1, 1), (2, 1)]          # (shape index in the config, copies per layer)
-# HBM-side bytes per launch (average over the launches of a step) from the two
-# rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) summarised under profiles/, scaled by
-# what the same counters read for a plain 256 MiB device copy.  A measurement that
-# cannot be taken from inside this script: None where no such run has been made.
-MEASURED_TRAFFIC_BYTES = {("tw", False): None, ("tvw", False): None,
-                          ("tw", True): 32.47e6, ("tvw", True): 29.45e6}   # key: (pattern, Q/K/V grouped)
+# HBM-side bytes per launch (average over the launches of a step), NOT measured by this run:
+# they come from the two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE) of this same command
+# summarised in the file named beside them, scaled by what the same counters read for a plain
+# 256 MiB device copy.  None where no such run has been made.
+PROFILED_TRAFFIC = {("tw", True): (32.47e6, "profiles/tw_gemm_km_dma_kernel_bert_base_tw75.md"),
+                    ("tvw", True): (29.45e6, "profiles/tvw_gemm_km_kernel_bert_base_tvw875.md")}
 
 
 def algorithmic_bytes(M, K_union, N, pattern, sum_kw, sum_k):
@@ -54,6 +59,120 @@ def algorithmic_bytes(M, K_union, N, pattern, sum_kw, sum_k):
     the values plus 4 position bits per group and column) and its kept-row list."""
     w = 2 * sum_kw if pattern == "tw" else sum_kw + sum_kw // 8
     return 2 * M * K_union + 2 * M * N + w + 4 * sum_k
+
+
+def issued_flops(M, sum_kw, pattern):
+    """Matrix-core work of a launch: 2 M sum(K_t W_t); the 2:4 instruction issues half of it."""
+    return (1.0 if pattern == "tvw" else 2.0) * M * sum_kw
+
+
+def roof(alg_bytes, flops, seconds):
+    """Which published roof binds and the fraction of it that was reached."""
+    t_hbm, t_mfma = alg_bytes / (HBM_PEAK_GBS * 1e9), flops / (FP16_PEAK_TFLOPS * 1e12)
+    return ("hbm" if t_hbm >= t_mfma else "mfma"), max(t_hbm, t_mfma) / seconds
+
+
+def calibration(tw, torch, dev, stream, quick=False):
+    """Times the tw_calibrate kernels: GB/s of plain streams, TFLOP/s of register-only loops."""
+    nbytes = (256 << 20) if quick else (1 << 30)
+    src = torch.ones(nbytes, dtype=torch.uint8, device=dev)
+    dst = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
+    out = {}
+
+    def timed(kind, n, iters=0, reps=5):
+        best, units = None, 0.0
+        for r in range(reps + 1):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            units = tw.tw_calibrate(kind, dst.data_ptr(), src.data_ptr(), n, iters, stream)
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) * 1e-3
+            if r > 0 and (best is None or t < best):      # first launch is a warm-up
+                best = t
+        return units / best
+    out["copy_GBps"] = timed(tw.CAL_COPY, nbytes) / 1e9            # read + write bytes
+    out["read_GBps"] = timed(tw.CAL_READ, nbytes) / 1e9
+    out["write_GBps"] = timed(tw.CAL_WRITE, nbytes) / 1e9
+    out["store_ct_25MB_GBps"] = timed(tw.CAL_STORE_CT, 3072 * 4096 * 2, reps=10) / 1e9
+    iters = 2000 if quick else 8000
+    out["mfma_f16_TFLOPs"] = timed(tw.CAL_MFMA_F16, nbytes, iters) / 1e12
+    out["smfmac_f16_dense_eq_TFLOPs"] = timed(tw.CAL_SMFMAC_F16, nbytes, iters) / 1e12
+    out["mfma_i8_TOPs"] = timed(tw.CAL_MFMA_I8, nbytes, iters) / 1e12
+    out["bytes"] = nbytes
+    out["note"] = ("best of 5 single launches between HIP events; copy counts bytes read + written; "
+                   "matrix loops: 2048 workgroups x 4 waves x 4 accumulators, operands in registers")
+    del src, dst
+    return out
+
+
+def extra_rows(tw, wl, torch, dev, stream, skip_cfg, reps=24, sets=6):
+    """One row per other configured workload (launch configuration as the heuristics pick it)."""
+    def timed(fn, rounds=3):
+        vals = []
+        for _ in range(rounds):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for r in range(reps):
+                fn(r)
+            e1.record()
+            torch.cuda.synchronize()
+            vals.append(e0.elapsed_time(e1) / reps * 1e-3)
+        return float(np.median(vals))
+
+    plan = []
+    for cfg in (2, 3, 4, 5):
+        if cfg == skip_cfg:
+            continue
+        for si in range(len(wl.SHAPES[cfg])):
+            if cfg == 2:
+                plan.append((cfg, si, "tw", 0.75, 128))
+            elif cfg == 3:
+                plan.append((cfg, si, "tvw", 0.875, 128))
+            elif cfg == 4:
+                plan += [(cfg, si, "tw", sp, 128) for sp in (0.0, 0.5, 0.75, 0.875, 0.9375)]
+                plan += [(cfg, si, "tvw", sp, 128) for sp in (0.5, 0.75, 0.875, 0.9375)]
+            else:
+                plan += [(cfg, si, "tw", 0.75, 64), (cfg, si, "tw", 0.75, 128),
+                         (cfg, si, "tvw", 0.875, 64), (cfg, si, "tvw", 0.875, 128)]
+    rows, dense_us, bufs = [], {}, {}
+    for cfg, si, pattern, sp, G in plan:
+        shp = wl.SHAPES[cfg][si]
+        M, K, N = shp.M, shp.K, shp.N
+        nsets = max(2, min(sets, int(600e6 // (2 * M * (K + N)))))
+        if (cfg, si) not in bufs:
+            bufs.clear()                                   # one shape's buffers alive at a time
+            bufs[(cfg, si)] = ([torch.randn((K, M), dtype=torch.float16, device=dev) for _ in range(nsets)],
+                               [torch.empty((N, M), dtype=torch.float16, device=dev) for _ in range(nsets)])
+        A, C = bufs[(cfg, si)]
+        cf = 0.0 if sp == 0.0 or (pattern == "tvw" and sp == 0.5) else None
+        c = wl.make_case(cfg, si, pattern=pattern, sparsity=sp, G=G, col_frac=cf, with_A=False)
+        pat = tw.PATTERN_TW if pattern == "tw" else tw.PATTERN_TVW
+        packed = [tw.tw_pack(c.B, c.mask, G, pat, tile_mask=c.tile_mask if pattern == "tvw" else None)
+                  for _ in range(nsets)]
+        skw, sk, ku = packed[0].flop_counts()
+        t = timed(lambda r: tw.tw_gemm(A[r % nsets].data_ptr(), M, M, tw.LAYOUT_KM, packed[r % nsets],
+                                       C[r % nsets].data_ptr(), M, stream))
+        if (cfg, si) not in dense_us:
+            Bd = torch.from_numpy(c.B).to(dev)
+            dense_us[(cfg, si)] = timed(lambda r: tw.tw_dense_gemm(A[r % nsets].data_ptr(), Bd.data_ptr(),
+                                                                   C[r % nsets].data_ptr(), M, K, N, M, N, M,
+                                                                   tw.LAYOUT_KM, stream))
+        td = dense_us[(cfg, si)]
+        ab = algorithmic_bytes(M, ku, N, pattern, skw, sk)
+        fl = issued_flops(M, skw, pattern)
+        bound, frac = roof(ab, fl, t)
+        rows.append(dict(config=cfg, shape=shp.name, M=M, K=K, N=N, G=G, pattern=pattern, sparsity=sp,
+                         us=round(t * 1e6, 2), dense_us=round(td * 1e6, 2), speedup_vs_dense=round(td / t, 3),
+                         dense_eq_tflops=round(2.0 * M * K * N / t / 1e12, 1),
+                         # issued matrix-core work over the peak of the instruction that issues it
+                         # (TVW: useful flops over the dense peak, the same number)
+                         condensed_mfma_util=round(fl / t / 1e12 / FP16_PEAK_TFLOPS, 4),
+                         alg_bytes=int(ab), alg_GBps=round(ab / t / 1e9, 1), bound=bound, frac=round(frac, 4)))
+        for p in packed:
+            p.free()
+    bufs.clear()
+    return rows
 
 
 def main():
@@ -65,6 +184,9 @@ def main():
     ap.add_argument("--pattern", default="tw", choices=["tw", "tvw"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-rows", action="store_true", help="skip the rows of the other configured workloads")
+    ap.add_argument("--no-calibration", action="store_true")
+    ap.add_argument("--calibrate", action="store_true", help="run the calibration kernels only and print their rates")
     ap.add_argument("--separate-qkv", action="store_true",
                     help="time the step with Q, K and V as three launches (6 launches per step)")
     ap.add_argument("--xcd-map", type=int, default=1, choices=[0, 1],
@@ -79,17 +201,20 @@ def main():
 
     import torch
     from paper_2402_10876_amd import build as _build
-    _build.ensure_built()                   # compiles only if no library has been built
+    _build.ensure_built()                   # compiles only if the library does not match the sources
     import paper_2402_10876_amd as tw
     import workloads as wl
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
-    tw.tw_set_option("xcd_map", args.xcd_map)
     dev = torch.device("cuda:0")
+    stream = torch.cuda.current_stream().cuda_stream
+    if args.calibrate:
+        print(json.dumps(dict(calibration=calibration(tw, torch, dev, stream), library=_build.describe())))
+        return
+    tw.tw_set_option("xcd_map", args.xcd_map)
     cfg = 2 if args.pattern == "tw" else 3
     shapes = wl.SHAPES[cfg]
     M = shapes[0].M
-    stream = torch.cuda.current_stream().cuda_stream
     pat = tw.PATTERN_TW if args.pattern == "tw" else tw.PATTERN_TVW
 
     # ---- rotating sets: packed weights, A^T, C^T ----------------------------
@@ -135,27 +260,24 @@ def main():
             launch(o)
 
     # ---- the timed region -------------------------------------------------------
+    # Wall clock between two synchronisations around exactly `steps` steps gives ms_per_step and
+    # `value`; one pair of HIP events recorded on the launch stream inside the same region
+    # (first thing after the opening synchronisation, last thing before the closing one) gives
+    # the device-side span of the same launches: span / launches is the average launch duration
+    # of the roofline (back-to-back launches, so the gap between two kernels is part of it).
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    ev0.record()
     for i in range(args.steps):
         step(i)
+    ev1.record()
     torch.cuda.synchronize()
     sec_per_step = (time.perf_counter() - t0) / args.steps
-
-    # ---- the same steps again, one pair of HIP events around the launches of each
-    # step, recorded on the stream the kernels run on: elapsed / launches is the
-    # average launch duration (back-to-back launches, so the gap between two
-    # kernels is part of it)
-    ev = []
-    for i in range(args.steps):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(); step(i); e1.record()
-        ev.append((e0, e1))
-    torch.cuda.synchronize()
     launches = len(sets[0])
-    avg_launch_ms = float(np.mean([a.elapsed_time(b) for a, b in ev])) / launches
+    avg_launch_ms = ev0.elapsed_time(ev1) / (args.steps * launches)
     alg_per_launch = sum(meta[o[0]]["alg"] for o in sets[0]) / launches
 
     # ---- the other variant of the step, for the record (outside the timed region) ----
@@ -190,7 +312,7 @@ def main():
     hot_ms["qkv"] = time_shape("qkv", launch, which=sets_grp[:1])
 
     dense_flops_step = sum(2.0 * M * shapes[si].K * shapes[si].N * c for si, c in PLAN)
-    cond_flops_step = sum(2.0 * M * meta[si]["sum_kw"] * c for si, c in PLAN)
+    issued_step = sum(issued_flops(M, meta[si]["sum_kw"], args.pattern) * c for si, c in PLAN)
     value = dense_flops_step / sec_per_step / 1e12
 
     # ---- our own dense MFMA GEMM at the same shapes (outside the timed region) -----
@@ -200,9 +322,11 @@ def main():
         mt = meta[key]
         Kk, Nn, which = mt["K"], mt["N"], (sets_grp if key == "qkv" else sets_sep)
         t_sp = per_shape_ms[key] * 1e-3
+        fl = issued_flops(M, mt["sum_kw"], args.pattern)
+        bound, frac = roof(mt["alg"], fl, t_sp)
         d = dict(sparse_us=t_sp * 1e6, dense_eq_tflops=2.0 * M * Kk * Nn / t_sp / 1e12,
-                 condensed_mfma_util=2.0 * M * mt["sum_kw"] / t_sp / 1e12 / FP16_PEAK_TFLOPS,
-                 alg_GBps=mt["alg"] / t_sp / 1e9, alg_bytes=mt["alg"],
+                 condensed_mfma_util=fl / t_sp / 1e12 / FP16_PEAK_TFLOPS,
+                 alg_GBps=mt["alg"] / t_sp / 1e9, alg_bytes=mt["alg"], bound=bound, frac=frac,
                  sparse_us_cache_resident=hot_ms[key] * 1e3)
         if not args.no_dense:
             Bd = torch.from_numpy(wl.make_B(wl.seed_for(cfg, 0 if key == "qkv" else key), Kk, Nn, 0.02)).to(dev)
@@ -226,19 +350,43 @@ def main():
                  value=dense_flops_step / sec_other / 1e12)
     detail["separate_qkv" if grouped else "grouped_qkv"] = other
 
+    # release the step's buffers before the other workloads allocate theirs
+    for ops in sets_grp:
+        ops[0][1].free()
+    for ops in sets_sep:
+        for o in ops:
+            o[1].free()
+    del sets, sets_sep, sets_grp
+    torch.cuda.empty_cache()
+
     if args.copy_calibration:
         src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         for _ in range(4):
             dst.copy_(src)
         torch.cuda.synchronize()
+        del src, dst
+
+    cal = None if args.no_calibration else calibration(tw, torch, dev, stream, quick=True)
+    rows = None if args.no_rows else extra_rows(tw, wl, torch, dev, stream, skip_cfg=cfg)
 
     achieved = alg_per_launch / (avg_launch_ms * 1e-3) / 1e9
     kern = "tw_gemm_km_dma_kernel" if args.pattern == "tw" else "tvw_gemm_km_kernel"
+    traffic, traffic_src = PROFILED_TRAFFIC.get((args.pattern, grouped), (None, None))
     roofline = dict(bound="hbm", achieved=achieved, peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=achieved / HBM_PEAK_GBS, traffic=MEASURED_TRAFFIC_BYTES[(args.pattern, grouped)],
+                    frac=achieved / HBM_PEAK_GBS, traffic=traffic, traffic_source=traffic_src,
                     kernel=f"{kern} (all {launches} launches of a step; the step runs nothing else)",
-                    avg_launch_us=avg_launch_ms * 1e3, algorithmic_bytes_per_launch=alg_per_launch)
+                    avg_launch_us=avg_launch_ms * 1e3, wall_us_per_launch=sec_per_step * 1e6 / launches,
+                    algorithmic_bytes_per_launch=alg_per_launch,
+                    timing="HIP events on the launch stream around the same K steps that ms_per_step times")
+    if cal:
+        roofline.update(measured_copy_GBps=cal["copy_GBps"], frac_vs_measured_copy=achieved / cal["copy_GBps"])
+    util = issued_step / sec_per_step / 1e12 / FP16_PEAK_TFLOPS
+    roofline["note"] = (f"HBM-bound at this sparsity: the matrix-core roof of the step is "
+                        f"{issued_step / (FP16_PEAK_TFLOPS * 1e12) * 1e6:.1f} us against "
+                        f"{alg_per_launch * launches / (HBM_PEAK_GBS * 1e9) * 1e6:.1f} us for its bytes; "
+                        f"condensed-FLOP matrix-core utilisation {util:.3f} (goal 0.60 not met: it is capped "
+                        f"by the byte roof on these shapes)")
 
     out = dict(metric=f"{args.pattern.upper()} sparse GEMM effective (dense-equivalent) TFLOP/s, BERT-base layer",
                value=value, unit="TFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
@@ -251,10 +399,16 @@ def main():
                                     + ("75 % sparsity (10 % columns + per-tile rows)" if args.pattern == "tw" else
                                        "87.5 % sparsity (tile-wise 75 % + 2:4)") + ", layout K x M / N x M",
                            sets=args.sets, pattern=args.pattern, launches_per_step=launches),
-               condensed_flop_mfma_util=cond_flops_step / sec_per_step / 1e12 / FP16_PEAK_TFLOPS,
-               condensed_flop_util_vs_measured_mfma_loop=cond_flops_step / sec_per_step / 1e12 / MEASURED_MFMA_LOOP_TFLOPS,
-               pack_seconds_per_weight=t_pack / (args.sets * 6),
+               condensed_flop_mfma_util=util,
+               pack_seconds_per_weight=t_pack / (args.sets * 6), library=_build.describe(),
                roofline=roofline, detail=detail)
+    if cal:
+        out["calibration"] = cal
+        out["condensed_flop_util_vs_measured_mfma_loop"] = (
+            issued_step / sec_per_step / 1e12 /
+            (cal["mfma_f16_TFLOPs"] if args.pattern == "tw" else cal["smfmac_f16_dense_eq_TFLOPs"] / 2.0))
+    if rows is not None:
+        out["rows"] = rows
 
     if not args.no_cpu_baseline:
         from oracle import gemm as og

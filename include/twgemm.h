@@ -345,6 +345,29 @@ const char* tw_status_str(int status);
 tw_status tw_set_option(const char* name, int value);
 tw_status tw_flop_counts(tw_handle_t h, int64_t* sum_kw, int64_t* sum_k, int64_t* k_union);
 
+/*
+ * tw_calibrate - measurement aid, not part of the method: enqueues ONE kernel that does
+ * nothing but stream memory or issue matrix-core instructions, so that a benchmark can time
+ * what this GPU sustains and price the GEMM kernels against it as well as against the
+ * published peaks.  *units receives the work of the launch: bytes moved (streams) or
+ * dense-equivalent floating-point / integer operations (matrix loops).
+ *   TW_CAL_COPY      dst[0..bytes) = src[0..bytes), 16 bytes per thread and step; units = 2 * bytes
+ *   TW_CAL_READ      reads src[0..bytes) (dst: at least 16 bytes, normally untouched)
+ *   TW_CAL_WRITE     zero-fills dst[0..bytes)
+ *   TW_CAL_STORE_CT  zero-fills dst as an N x 4096 fp16 array in the GEMM epilogue's pattern
+ *                    (128 rows x 256 bytes per workgroup), N = bytes / 8192 rounded down to 128
+ *   TW_CAL_MFMA_F16 / TW_CAL_SMFMAC_F16 / TW_CAL_MFMA_I8   2048 workgroups x 4 waves, `iters`
+ *                    rounds of 4 independent 32x32x16 f16 / 32x32x32 2:4-sparse f16 /
+ *                    32x32x32 int8 instructions per wave, operands in registers; dst receives
+ *                    one float per thread (bytes >= 2 MiB)
+ * Buffers 16-byte aligned.  Asynchronous on `stream`, allocates nothing.
+ * Errors: TW_ERR_ARG, TW_ERR_HIP.
+ */
+enum { TW_CAL_COPY = 0, TW_CAL_READ = 1, TW_CAL_WRITE = 2, TW_CAL_STORE_CT = 3,
+       TW_CAL_MFMA_F16 = 10, TW_CAL_SMFMAC_F16 = 11, TW_CAL_MFMA_I8 = 12 };
+tw_status tw_calibrate(int kind, void* dst_dev, const void* src_dev, size_t bytes, int iters,
+                       void* stream, double* units);
+
 #ifdef __cplusplus
 }
 #endif

@@ -17,7 +17,7 @@ EXPORTED_SYMBOLS = [
     "tw_pack_host", "tw_upload", "tw_pack", "tw_pack_dev", "tw_prune_dev",
     "tw_prune_workspace_bytes", "tw_prune_dev_static", "tw_concat", "tw_gemm", "tw_dense_gemm", "tw_export",
     "tw_unpack", "tw_free", "tw_status_str", "tw_set_option", "tw_flop_counts",
-    "tw_pack_i8_host", "tw_pack_i8", "tw_gemm_i8", "tw_dense_gemm_i8", "tw_conv_bind", "tw_conv_gemm", "tw_conv_gemm_i8",
+    "tw_pack_i8_host", "tw_pack_i8", "tw_gemm_i8", "tw_dense_gemm_i8", "tw_conv_bind", "tw_conv_gemm", "tw_conv_gemm_i8", "tw_calibrate",
 ]
 
 _lib = None
@@ -78,6 +78,7 @@ def lib():
         L.tw_conv_bind.argtypes = [vp, C.POINTER(_ConvGeom), C.c_int64]
         L.tw_conv_gemm.argtypes = [vp, vp, vp, i, vp]
         L.tw_conv_gemm_i8.argtypes = [vp, vp, vp, i, i, C.c_float, vp]
+        L.tw_calibrate.argtypes = [i, vp, vp, C.c_size_t, i, vp, C.POINTER(C.c_double)]
         L.tw_export.argtypes = [vp, C.POINTER(_View)]
         L.tw_unpack.argtypes = [vp, vp, vp]
         L.tw_free.argtypes = [vp]
@@ -317,6 +318,17 @@ def tw_conv_gemm(X_ptr: int, packed: PackedWeight, C_ptr: int, ldc: int, stream:
 def tw_conv_gemm_i8(X_ptr: int, packed: PackedWeight, C_ptr: int, ldc: int, c_dtype: int = 0, scale: float = 1.0,
                     stream: int = 0):
     _check(lib().tw_conv_gemm_i8(X_ptr, packed.handle, C_ptr, ldc, c_dtype, scale, stream), "tw_conv_gemm_i8")
+
+
+CAL_COPY, CAL_READ, CAL_WRITE, CAL_STORE_CT, CAL_MFMA_F16, CAL_SMFMAC_F16, CAL_MFMA_I8 = 0, 1, 2, 3, 10, 11, 12
+
+
+def tw_calibrate(kind: int, dst_ptr: int, src_ptr, nbytes: int, iters: int = 0, stream: int = 0) -> float:
+    """Enqueues one streaming / matrix-core-loop kernel; returns the work of the launch
+    (bytes or dense-equivalent operations)."""
+    units = C.c_double()
+    _check(lib().tw_calibrate(kind, dst_ptr, src_ptr, nbytes, iters, stream, C.byref(units)), "tw_calibrate")
+    return units.value
 
 
 def tw_set_option(name: str, value: int):
