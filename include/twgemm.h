@@ -226,6 +226,40 @@ tw_status tw_gemm(const void* A_dev, int M, int lda, int layout, tw_handle_t h,
                   void* C_dev, int ldc, void* stream);
 
 /*
+ * tw_gemm_ex - tw_gemm with the launch options of THIS call (nothing process-wide is read when
+ * `opts` is given, so threads may launch the same handle with different options at the same
+ * time), and optionally a workspace that lets the library split long kept-row lists across
+ * workgroups (Section V: few or uneven tiles leave the device under-used; one launch for all
+ * tiles lets the scheduler even that out, and a weight with fewer (M-tile, N-tile) pairs than
+ * the GPU has compute units needs its K loop shared out as well).
+ *   opts          NULL = the defaults (tw_launch_opts_init's values); else every field as
+ *                 described at tw_set_option, 0 = heuristic / default:
+ *                   tile_m 0|64|128|256, kernel 0..2, depth 0|3..8, waves 0|4|8, ksplit 0..2,
+ *                   xcd_map -1 (default) | 0 | 1 | 2,
+ *                   wg_split 0 = automatic when a workspace is given, 1 = never,
+ *                            2..8 = that many workgroups per (M-tile, N-tile) pair
+ *   workspace_dev device memory, 256-byte aligned, at least tw_gemm_workspace_bytes(h, M) bytes,
+ *                 prepared ONCE with tw_workspace_init (its first 4 KiB are counters that every
+ *                 launch leaves at zero again).  Launches that share a workspace must not
+ *                 overlap (same stream, or ordered otherwise); after a failed launch call
+ *                 tw_workspace_init again.  fp32 partial tiles are added in a fixed order before
+ *                 the one rounding: results do not depend on timing.  TW pattern, TW_LAYOUT_KM,
+ *                 G = 64 or 128; other launches ignore the workspace.
+ * Asynchronous on `stream`; allocates nothing.  Errors: as tw_gemm; TW_ERR_ARG also for an
+ * invalid option value, a misaligned workspace, or wg_split > 1 with a workspace too small.
+ */
+typedef struct {
+  int32_t tile_m, kernel, depth, waves, ksplit, xcd_map, wg_split;
+  void* workspace_dev;
+  size_t workspace_bytes;
+} tw_launch_opts;
+tw_status tw_launch_opts_init(tw_launch_opts* opts);
+tw_status tw_gemm_workspace_bytes(tw_handle_t h, int M, size_t* bytes);
+tw_status tw_workspace_init(void* workspace_dev, size_t workspace_bytes, void* stream);
+tw_status tw_gemm_ex(const void* A_dev, int M, int lda, int layout, tw_handle_t h,
+                     void* C_dev, int ldc, const tw_launch_opts* opts, void* stream);
+
+/*
  * tw_dense_gemm - the dense baseline C = A . B on the same matrix cores, same
  * layouts and precision (Section V: the dense tiled GEMM the method starts from).
  *   B_dev  device fp16, K x N row-major, ldb >= N, multiple of 8, 16-byte aligned.
@@ -285,24 +319,28 @@ tw_status tw_dense_gemm_i8(const void* A_dev, const void* B_dev, void* C_dev, in
  * zero-padded layout sit depends on the caller's (R-1)/2, (S-1)/2 shift; this call does not
  * care), pruned output channels +0.
  *
- * tw_conv_bind - fix the geometry for an uploaded TW or TVW handle (fp16 or int8) with
- *   K = C*R*S (the per-tile kept-row lists become element offsets on the device; allocates;
- *   binding again replaces the previous geometry).  With c = 8 (fp16) or 16 (int8) elements
- *   per 16-byte copy: ldx a multiple of c, ldx >= roundup_c(B*L*P) + (R-1)*P + S-1 so that the
- *   windows of the last positions stay inside channel rows of ldx elements; C*ldx < 2^31.
+ * tw_conv_bind - bind a geometry to an uploaded TW or TVW handle (fp16 or int8) with
+ *   K = C*R*S: *out receives a binding that owns the per-tile kept-row lists as element offsets
+ *   on the device (allocates).  The handle is not changed: several bindings (geometries) of one
+ *   handle may exist and launch at the same time; the handle must outlive them.  With c = 8
+ *   (fp16) or 16 (int8) elements per 16-byte copy: ldx a multiple of c,
+ *   ldx >= roundup_c(B*L*P) + (R-1)*P + S-1 so that the windows of the last positions stay
+ *   inside channel rows of ldx elements; C*ldx < 2^31.
  *   Errors: TW_ERR_ARG, TW_ERR_STATE (not uploaded), TW_ERR_UNSUPPORTED (G = 32, TEW),
  *   TW_ERR_ALLOC, TW_ERR_HIP.
+ * tw_conv_free - release a binding (NULL is a no-op).
  * tw_conv_gemm - the launch.  X_dev fp16, C rows of ldx elements, 16-byte aligned; C_dev fp16
  *   N x ldc, ldc >= B*L*P, multiple of 8, 16-byte aligned.  Asynchronous on `stream`,
- *   allocates nothing.  Errors: TW_ERR_ARG (also: an int8 handle), TW_ERR_STATE (no geometry
- *   bound), TW_ERR_HIP.
+ *   allocates nothing.  Errors: TW_ERR_ARG (also: a binding of an int8 handle), TW_ERR_HIP.
  * tw_conv_gemm_i8 - the same for an int8 handle: X_dev int8, C_dev int32 (c_dtype 0) or int8
  *   requantised with `scale` (c_dtype 1) as in tw_gemm_i8, ldc >= B*L*P, multiple of 16.
  */
 typedef struct { int32_t C, R, S, B, H, W, P, L; } tw_conv_geom;
-tw_status tw_conv_bind(tw_handle_t h, const tw_conv_geom* geom, int64_t ldx);
-tw_status tw_conv_gemm(const void* X_dev, tw_handle_t h, void* C_dev, int ldc, void* stream);
-tw_status tw_conv_gemm_i8(const void* X_dev, tw_handle_t h, void* C_dev, int ldc, int c_dtype,
+typedef struct tw_conv_s* tw_conv_t; /* opaque: a geometry bound to a packed weight */
+tw_status tw_conv_bind(tw_handle_t h, const tw_conv_geom* geom, int64_t ldx, tw_conv_t* out);
+tw_status tw_conv_free(tw_conv_t binding);
+tw_status tw_conv_gemm(const void* X_dev, tw_conv_t binding, void* C_dev, int ldc, void* stream);
+tw_status tw_conv_gemm_i8(const void* X_dev, tw_conv_t binding, void* C_dev, int ldc, int c_dtype,
                           float scale, void* stream);
 
 /* tw_export - fill *out with the logical view (host pointers owned by h). */
@@ -320,8 +358,10 @@ const char* tw_status_str(int status);
 
 /*
  * Tuning / introspection (not needed for correct use).
- * tw_set_option: process-wide integer knobs read at the next tw_gemm /
- * tw_dense_gemm call.  Unknown names give TW_ERR_ARG.
+ * tw_set_option: process-wide DEFAULTS of the launch options, read once at the start of every
+ * call that is not given options of its own (tw_gemm, tw_dense_gemm, the int8 and convolution
+ * launches, tw_launch_opts_init); meant for tests and experiments: code that launches from
+ * several threads passes tw_launch_opts to tw_gemm_ex instead.  Unknown names give TW_ERR_ARG.
  *   "tile_m"   0 = heuristic, else force the M-tile (64, 128 or 256)
  *   "xcd_map"  1 (default) = remap workgroup ids so that one XCD walks all
  *              N-tiles of an M-band; 0 = plain order; 2 = as 1, and the
@@ -332,7 +372,10 @@ const char* tw_status_str(int status);
  *   "waves"    4 (default) or 8 waves per workgroup in the asynchronous pipeline
  *   "ksplit"   0 = automatic, 1 = never, 2 = always split K between two wave groups
  *              of a workgroup (long K, few tiles)
- *   "depth"    stages in flight of the asynchronous pipeline: 3 (default) or 4
+ *   "depth"    stages in flight of the asynchronous pipeline: 3 (default) .. 8 (6 and 8 exist for
+              4-wave tiles of 64 x 128, 128 x 128 and 128 x 64 only; TVW: 3 or 4)
+   "wg_split" K split across workgroups (tw_gemm_ex with a workspace): 0 / 1 = off,
+              2..8 = workgroups per (M-tile, N-tile) pair
  *   "tile_order"  read by tw_pack / tw_concat: 1 (default) = tiles are launched longest
  *              kept-row list first (uneven tiles, Section V "load imbalance"); 0 = in
  *              column order

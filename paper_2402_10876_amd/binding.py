@@ -17,7 +17,8 @@ EXPORTED_SYMBOLS = [
     "tw_pack_host", "tw_upload", "tw_pack", "tw_pack_dev", "tw_prune_dev",
     "tw_prune_workspace_bytes", "tw_prune_dev_static", "tw_concat", "tw_gemm", "tw_dense_gemm", "tw_export",
     "tw_unpack", "tw_free", "tw_status_str", "tw_set_option", "tw_flop_counts",
-    "tw_pack_i8_host", "tw_pack_i8", "tw_gemm_i8", "tw_dense_gemm_i8", "tw_conv_bind", "tw_conv_gemm", "tw_conv_gemm_i8", "tw_calibrate",
+    "tw_pack_i8_host", "tw_pack_i8", "tw_gemm_i8", "tw_dense_gemm_i8", "tw_conv_bind", "tw_conv_free", "tw_conv_gemm", "tw_conv_gemm_i8", "tw_calibrate",
+    "tw_gemm_ex", "tw_launch_opts_init", "tw_gemm_workspace_bytes", "tw_workspace_init",
 ]
 
 _lib = None
@@ -40,6 +41,13 @@ class _View(C.Structure):
                 ("tile_col_off", C.POINTER(C.c_int32)), ("ew_nnz", C.c_int64),
                 ("ew_col_ptr", C.POINTER(C.c_int32)), ("ew_row", C.POINTER(C.c_int32)),
                 ("ew_val", C.POINTER(C.c_uint16)), ("dtype", C.c_int32)]
+
+
+class LaunchOpts(C.Structure):
+    """tw_launch_opts: per-call launch options (see include/twgemm.h)."""
+    _fields_ = [("tile_m", C.c_int32), ("kernel", C.c_int32), ("depth", C.c_int32), ("waves", C.c_int32),
+                ("ksplit", C.c_int32), ("xcd_map", C.c_int32), ("wg_split", C.c_int32),
+                ("workspace_dev", C.c_void_p), ("workspace_bytes", C.c_size_t)]
 
 
 def lib_path() -> str:
@@ -75,7 +83,12 @@ def lib():
         L.tw_gemm_i8.argtypes = [vp, i, i, vp, vp, i, i, C.c_float, vp]
         L.tw_dense_gemm_i8.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, C.c_float, vp]
         L.tw_dense_gemm.argtypes = [vp, vp, vp, i, i, i, i, i, i, i, vp]
-        L.tw_conv_bind.argtypes = [vp, C.POINTER(_ConvGeom), C.c_int64]
+        L.tw_conv_bind.argtypes = [vp, C.POINTER(_ConvGeom), C.c_int64, C.POINTER(C.c_void_p)]
+        L.tw_conv_free.argtypes = [vp]
+        L.tw_gemm_ex.argtypes = [vp, i, i, i, vp, vp, i, C.POINTER(LaunchOpts), vp]
+        L.tw_launch_opts_init.argtypes = [C.POINTER(LaunchOpts)]
+        L.tw_gemm_workspace_bytes.argtypes = [vp, i, C.POINTER(C.c_size_t)]
+        L.tw_workspace_init.argtypes = [vp, C.c_size_t, vp]
         L.tw_conv_gemm.argtypes = [vp, vp, vp, i, vp]
         L.tw_conv_gemm_i8.argtypes = [vp, vp, vp, i, i, C.c_float, vp]
         L.tw_calibrate.argtypes = [i, vp, vp, C.c_size_t, i, vp, C.POINTER(C.c_double)]
@@ -305,19 +318,72 @@ def tw_dense_gemm_i8(A_ptr: int, B_ptr: int, C_ptr: int, M: int, K: int, N: int,
            "tw_dense_gemm_i8")
 
 
-def tw_conv_bind(packed: PackedWeight, geom, ldx: int):
+class ConvBinding:
+    """Owner of a tw_conv_t; keeps its packed weight alive."""
+
+    def __init__(self, handle, packed):
+        self._b, self._packed = handle, packed
+
+    @property
+    def handle(self):
+        if self._b is None:
+            raise ValueError("binding already freed")
+        return self._b
+
+    def free(self):
+        if self._b is not None:
+            b, self._b = self._b, None
+            _check(lib().tw_conv_free(b), "tw_conv_free")
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def tw_conv_bind(packed: PackedWeight, geom, ldx: int) -> ConvBinding:
     """geom: anything with integer attributes C, R, S, B, H, W, P, L (see tw_conv_geom)."""
     g = _ConvGeom(*(int(getattr(geom, n)) for n in ("C", "R", "S", "B", "H", "W", "P", "L")))
-    _check(lib().tw_conv_bind(packed.handle, C.byref(g), int(ldx)), "tw_conv_bind")
+    b = C.c_void_p()
+    _check(lib().tw_conv_bind(packed.handle, C.byref(g), int(ldx), C.byref(b)), "tw_conv_bind")
+    return ConvBinding(b, packed)
 
 
-def tw_conv_gemm(X_ptr: int, packed: PackedWeight, C_ptr: int, ldc: int, stream: int = 0):
-    _check(lib().tw_conv_gemm(X_ptr, packed.handle, C_ptr, ldc, stream), "tw_conv_gemm")
+def tw_conv_gemm(X_ptr: int, binding: ConvBinding, C_ptr: int, ldc: int, stream: int = 0):
+    _check(lib().tw_conv_gemm(X_ptr, binding.handle, C_ptr, ldc, stream), "tw_conv_gemm")
 
 
-def tw_conv_gemm_i8(X_ptr: int, packed: PackedWeight, C_ptr: int, ldc: int, c_dtype: int = 0, scale: float = 1.0,
+def tw_conv_gemm_i8(X_ptr: int, binding: ConvBinding, C_ptr: int, ldc: int, c_dtype: int = 0, scale: float = 1.0,
                     stream: int = 0):
-    _check(lib().tw_conv_gemm_i8(X_ptr, packed.handle, C_ptr, ldc, c_dtype, scale, stream), "tw_conv_gemm_i8")
+    _check(lib().tw_conv_gemm_i8(X_ptr, binding.handle, C_ptr, ldc, c_dtype, scale, stream), "tw_conv_gemm_i8")
+
+
+def tw_launch_opts(**kw) -> LaunchOpts:
+    """The default launch options with the given fields replaced."""
+    o = LaunchOpts()
+    _check(lib().tw_launch_opts_init(C.byref(o)), "tw_launch_opts_init")
+    for k, v in kw.items():
+        if not hasattr(o, k):
+            raise TypeError(f"tw_launch_opts has no field {k!r}")
+        setattr(o, k, v)
+    return o
+
+
+def tw_gemm_workspace_bytes(packed: PackedWeight, M: int) -> int:
+    n = C.c_size_t()
+    _check(lib().tw_gemm_workspace_bytes(packed.handle, M, C.byref(n)), "tw_gemm_workspace_bytes")
+    return n.value
+
+
+def tw_workspace_init(ws_ptr: int, ws_bytes: int, stream: int = 0):
+    _check(lib().tw_workspace_init(ws_ptr, ws_bytes, stream), "tw_workspace_init")
+
+
+def tw_gemm_ex(A_ptr: int, M: int, lda: int, layout: int, packed: PackedWeight, C_ptr: int, ldc: int,
+               opts: LaunchOpts | None = None, stream: int = 0):
+    _check(lib().tw_gemm_ex(A_ptr, M, lda, layout, packed.handle, C_ptr, ldc,
+                            C.byref(opts) if opts is not None else None, stream), "tw_gemm_ex")
 
 
 CAL_COPY, CAL_READ, CAL_WRITE, CAL_STORE_CT, CAL_MFMA_F16, CAL_SMFMAC_F16, CAL_MFMA_I8 = 0, 1, 2, 3, 10, 11, 12

@@ -19,6 +19,39 @@ std::atomic<int> opt_kernel{0};   // 0 = automatic, 1 = register-staged, 2 = asy
 std::atomic<int> opt_depth{3};
 std::atomic<int> opt_waves{4};
 std::atomic<int> opt_ksplit{0};   // 0 = automatic, 1 = off, 2 = two K groups per workgroup
+std::atomic<int> opt_wg_split{0}; // 0 = automatic (needs a workspace), 1 = off, 2..8 = workgroups per tile
+
+// What one launch runs with: the caller's tw_launch_opts, or the process defaults above
+// (tw_set_option) when there is none.  Read once per call, never shared between calls.
+struct Opts {
+  int tile_m, xcd_map, kernel, depth, waves, ksplit, wg_split;
+  void* ws;
+  size_t ws_bytes;
+};
+Opts default_opts() {
+  return Opts{opt_tile_m.load(), opt_xcd_map.load(), opt_kernel.load(), opt_depth.load(), opt_waves.load(),
+              opt_ksplit.load(), opt_wg_split.load(), nullptr, 0};
+}
+bool opts_from(const tw_launch_opts* in, Opts* o) {
+  *o = default_opts();
+  if (!in) return true;
+  if (in->tile_m != 0 && in->tile_m != 64 && in->tile_m != 128 && in->tile_m != 256) return false;
+  if (in->kernel < 0 || in->kernel > 2 || in->ksplit < 0 || in->ksplit > 2) return false;
+  if (in->depth != 0 && (in->depth < 3 || in->depth > 8)) return false;
+  if (in->waves != 0 && in->waves != 4 && in->waves != 8) return false;
+  if (in->xcd_map < -1 || in->xcd_map > 2 || in->wg_split < 0 || in->wg_split > 8) return false;
+  if (in->workspace_dev && ((uintptr_t)in->workspace_dev & 255)) return false;
+  o->tile_m = in->tile_m; o->kernel = in->kernel; o->ksplit = in->ksplit; o->wg_split = in->wg_split;
+  o->depth = in->depth ? in->depth : 3;
+  o->waves = in->waves ? in->waves : 4;
+  o->xcd_map = in->xcd_map < 0 ? 1 : in->xcd_map;
+  o->ws = in->workspace_dev; o->ws_bytes = in->workspace_dev ? in->workspace_bytes : 0;
+  return true;
+}
+
+// Workspace of the K split across workgroups: 1024 counters, then the fp32 partial tiles.
+constexpr size_t WS_COUNTER_BYTES = 4096;
+constexpr int WS_MAX_PAIRS = (int)(WS_COUNTER_BYTES / 4);
 
 bool valid_G(int G) { return G == 32 || G == 64 || G == 128; }
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
@@ -29,8 +62,8 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 
 // and a half workgroups per CU still take the larger tile (128 rows; 256 for G = 64):
 // they are bound by the L2 -> LDS traffic, which is (tm + G) / (tm G) per product
 // (measured on the 3 x 3 convolution 256 -> 256 at 56 x 56: 17.0 against 21.7 us).
-int pick_tile_m(int M, int n_tiles, int G, int max_k) {
-  const int forced = opt_tile_m.load();
+int pick_tile_m(const Opts& o, int M, int n_tiles, int G, int max_k) {
+  const int forced = o.tile_m;
   if (forced == 64 || forced == 128 || forced == 256) {
     if (!(G == 32 && forced == 64)) return forced;
   }
@@ -51,8 +84,8 @@ int pick_tile_m(int M, int n_tiles, int G, int max_k) {
 // Measured on the configured shapes: 3-13 % on the BERT-base ones, while large grids and
 // long K loops (the weight tile is re-read per workgroup) keep 128.  The 256-row instance
 // (8 waves) is within 3 % of the 128-row one everywhere and only used when asked for.
-int pick_tile_m_tvw(int G, int M, int n_tiles) {
-  const int forced = opt_tile_m.load();
+int pick_tile_m_tvw(const Opts& o, int G, int M, int n_tiles) {
+  const int forced = o.tile_m;
   if (G != 128) return 128;
   if (forced == 64 || forced == 128 || forced == 256) return forced;
   const long wgs128 = (long)((M + 127) / 128) * n_tiles;
@@ -72,7 +105,37 @@ bool use_ksplit(int M, int n_tiles, int max_k, int* tm) {
   return true;
 }
 
+// K split across workgroups (needs a workspace).  *tm = M-tile, *S = workgroups per pair
+// (1 = do not split).  Only on request: measured on the few-tile shapes it is built for
+// (3072 x 768 at M = 4096; 4608 x 512 at M = 1568) it never beat the split inside the workgroup
+// (two wave groups, partial sums through LDS): 18.7 against 11.9 us and 12.6 against 10.8 us at
+// best.  The partial tiles have to pass through memory that is coherent across the XCDs' L2
+// caches, and that traffic (4 bytes per output element and workgroup, written and read) costs
+// more than the shorter K loops save.
+void pick_wg_split(const Opts& o, int M, int n_tiles, int G, int max_k, int* tm, int* S) {
+  *S = 1;
+  if (o.wg_split < 2) return;
+  const int forced_tm = (o.tile_m == 64 || o.tile_m == 128) ? o.tile_m : 0;
+  int t = forced_tm ? forced_tm : 128;
+  if (G == 64) t = 128;                       // the one split instance for G = 64
+  const int stages = max_k / 32;
+  int s = o.wg_split;
+  if (s > stages) s = stages > 0 ? stages : 1;
+  (void)M; (void)n_tiles;
+  *tm = t;
+  *S = s;
+}
+
 }  // namespace
+
+// A convolution geometry bound to a packed weight: the kept-row lists of the handle's device
+// image turned into element offsets for that geometry.  The handle itself is not changed.
+struct tw_conv_s {
+  tw_handle_t h = nullptr;
+  tw_conv_geom geom{};
+  int64_t ldx = 0;
+  int32_t* d_off = nullptr;
+};
 
 extern "C" {
 
@@ -264,15 +327,15 @@ tw_status tw_concat(const tw_handle_t* parts, int n, int upload, tw_handle_t* ou
 
 // The launch behind tw_gemm and tw_conv_gemm.  conv: A is the wide input, the row list holds
 // window offsets (lda = 1) and M counts the wide grid.
-static tw_status gemm_launch(const void* A, int M, int lda, int layout, tw_handle_t h, void* C, int ldc,
-                             void* stream, bool conv) {
+static tw_status gemm_launch(const Opts& o, const void* A, int M, int lda, int layout, tw_handle_t h, void* C,
+                             int ldc, void* stream, const tw_conv_s* conv) {
   twg::GemmArgs g{};
   g.A = (const _Float16*)A; g.C = (_Float16*)C; g.M = M; g.lda = lda; g.ldc = ldc;
   g.vals = (const _Float16*)h->img.d_vals;
   g.row_idx = h->img.d_row_idx; g.tile_kp_off = h->img.d_tile_kp_off;
   if (conv) {
-    g.row_idx = h->d_conv_off;
-    g.conv_P = h->conv.P; g.conv_L = h->conv.L; g.conv_H = h->conv.H; g.conv_W = h->conv.W;
+    g.row_idx = conv->d_off;
+    g.conv_P = conv->geom.P; g.conv_L = conv->geom.L; g.conv_H = conv->geom.H; g.conv_W = conv->geom.W;
   }
   g.col_idx = h->img.d_col_idx; g.tile_order = h->img.d_tile_order;
   g.tile_sched = h->img.d_tile_sched;
@@ -280,23 +343,20 @@ static tw_status gemm_launch(const void* A, int M, int lda, int layout, tw_handl
   g.meta = h->img.d_meta;
   g.ew_ptr = h->img.d_ew_ptr; g.ew_pairs = h->img.d_ew_pairs;
   g.ew_last = h->img.ew_pairs.empty() ? 0 : (int)h->img.ew_pairs.size() - 1;
-  g.n_tiles = h->n_tiles; g.K = h->K; g.N = h->N; g.xcd_map = opt_xcd_map.load();
-#ifdef TWG_TRACE
-  static int trace_launch = 0;
-  g.trace_slot = trace_launch++ & 1;
-#endif
+  g.n_tiles = h->n_tiles; g.K = h->K; g.N = h->N; g.xcd_map = o.xcd_map;
+  g.wg_split = 1;
   if (layout == TW_LAYOUT_MK) {
     hipError_t e = twg::launch_tw_mk(h->G, g, (hipStream_t)stream);
     if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
     return e == hipSuccess ? TW_OK : TW_ERR_HIP;
   }
   if (h->pattern == TW_PATTERN_TVW) {
-    const int tvw_tm = pick_tile_m_tvw(h->G, M, h->n_tiles > 0 ? h->n_tiles : 1);
-    hipError_t e = twg::launch_tvw_km(h->G, tvw_tm, opt_depth.load(), g, (hipStream_t)stream);
+    const int tvw_tm = pick_tile_m_tvw(o, h->G, M, h->n_tiles > 0 ? h->n_tiles : 1);
+    hipError_t e = twg::launch_tvw_km(h->G, tvw_tm, o.depth > 4 ? 4 : o.depth, g, (hipStream_t)stream);
     if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
     return e == hipSuccess ? TW_OK : TW_ERR_HIP;
   }
-  int tm = pick_tile_m(M, h->n_tiles > 0 ? h->n_tiles : 1, h->G, h->max_kp);
+  int tm = pick_tile_m(o, M, h->n_tiles > 0 ? h->n_tiles : 1, h->G, h->max_kp);
   // no 64 x 64 instance of the asynchronous kernel (tried: one matrix instruction per wave and
   // k-step is too little work per barrier; plain TW falls back to the register-staged kernel)
   if ((h->pattern == TW_PATTERN_TEW || conv) && h->G == 64 && tm == 64) tm = 128;
@@ -304,31 +364,75 @@ static tw_status gemm_launch(const void* A, int M, int lda, int layout, tw_handl
   // TEW: the same kernels with the restored elements added in the epilogue (3 stages only)
   const bool tew = h->pattern == TW_PATTERN_TEW;
   auto launch_dma = tew ? twg::launch_tew_km_dma : twg::launch_tw_km_dma;
-  const int depth = tew ? 3 : opt_depth.load();
+  const int depth = tew ? 3 : o.depth;
   // the asynchronous kernel addresses A with 32-bit byte offsets
   const bool a_fits32 = conv || (unsigned long long)h->K * (unsigned long long)lda * 2ull < (1ull << 32);
-  if ((opt_kernel.load() != 1 || tew || conv) && h->G != 32 && a_fits32) {
+  // K split across workgroups: few tiles, long kept-row lists, and a workspace to reduce through
+  if (!tew && o.kernel != 1 && h->G != 32 && a_fits32 && o.ws && o.wg_split != 1 && h->n_tiles > 0) {
+    int stm = 0, S = 0;
+    pick_wg_split(o, M, h->n_tiles, h->G, h->max_kp, &stm, &S);
+    if (S > 1) {
+      const long pairs = (long)((M + stm - 1) / stm) * h->n_tiles;
+      const size_t need = WS_COUNTER_BYTES + (size_t)pairs * S * stm * h->G * 4;
+      if (pairs <= WS_MAX_PAIRS && need <= o.ws_bytes) {
+        g.wg_split = S;
+        g.ws_counters = (int*)o.ws;
+        g.ws_partials = (float*)((char*)o.ws + WS_COUNTER_BYTES);
+        hipError_t es = twg::launch_tw_km_dma_split(h->G, stm, g, (hipStream_t)stream);
+        if (es != hipErrorInvalidValue) return es == hipSuccess ? TW_OK : TW_ERR_HIP;
+        g.wg_split = 1;
+      } else if (o.wg_split > 1) {
+        return TW_ERR_ARG;          // a split was asked for and the workspace cannot hold it
+      }
+    }
+  }
+  if ((o.kernel != 1 || tew || conv) && h->G != 32 && a_fits32) {
     // long K with too few tiles to fill the chip: split K inside the workgroup
     // 256-row tiles run with 8 waves (64 x 64 per wave): half the registers per wave, two
     // workgroups per CU
-    int variant = (opt_waves.load() == 8 || (tm == 256 && h->G == 128)) ? twg::DMA_WAVES8 : twg::DMA_WAVES4;
+    int variant = (o.waves == 8 || (tm == 256 && h->G == 128)) ? twg::DMA_WAVES8 : twg::DMA_WAVES4;
     int tmk = tm;
-    const int ks = opt_ksplit.load();
+    const int ks = o.ksplit;
     if (ks == 2 || (ks == 0 && use_ksplit(M, h->n_tiles, h->max_kp, &tmk))) variant = twg::DMA_KSPLIT2;
     if (variant == twg::DMA_KSPLIT2 && ks == 2) tmk = tm == 256 ? 128 : tm;
-    if (variant == twg::DMA_KSPLIT2 && h->G == 64 && conv) tmk = 128;   // the one K-split instance for G = 64
+    if (variant == twg::DMA_KSPLIT2 && h->G == 64) tmk = 128;   // the one K-split instance for G = 64
     e = launch_dma(h->G, variant == twg::DMA_KSPLIT2 ? tmk : tm, depth, variant, g, (hipStream_t)stream);
     if (e == hipErrorInvalidValue && variant != twg::DMA_WAVES4)
       e = launch_dma(h->G, tm, depth, twg::DMA_WAVES4, g, (hipStream_t)stream);
   }
-  if (e == hipErrorInvalidValue && opt_kernel.load() != 2 && !tew && !conv)
+  if (e == hipErrorInvalidValue && o.kernel != 2 && !tew && !conv)
     e = twg::launch_tw_km(h->G, tm, g, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
 
-tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void* C, int ldc,
-                  void* stream) {
+tw_status tw_launch_opts_init(tw_launch_opts* opts) {
+  if (!opts) return TW_ERR_ARG;
+  const Opts d = default_opts();
+  opts->tile_m = d.tile_m; opts->kernel = d.kernel; opts->depth = d.depth; opts->waves = d.waves;
+  opts->ksplit = d.ksplit; opts->xcd_map = d.xcd_map; opts->wg_split = d.wg_split;
+  opts->workspace_dev = nullptr; opts->workspace_bytes = 0;
+  return TW_OK;
+}
+
+tw_status tw_gemm_workspace_bytes(tw_handle_t h, int M, size_t* bytes) {
+  if (!h || !bytes || M < 1) return TW_ERR_ARG;
+  // enough for any split the library may choose at this M: 64-row tiles, 8 workgroups per pair,
+  // as long as the pairs fit the counters (beyond that no split is used)
+  const long pairs64 = (long)((M + 63) / 64) * (h->n_tiles > 0 ? h->n_tiles : 1);
+  const long pairs = pairs64 < WS_MAX_PAIRS ? pairs64 : WS_MAX_PAIRS;
+  *bytes = WS_COUNTER_BYTES + (size_t)pairs * 8 * 64 * 128 * 4;
+  return TW_OK;
+}
+
+tw_status tw_workspace_init(void* workspace_dev, size_t workspace_bytes, void* stream) {
+  if (!workspace_dev || ((uintptr_t)workspace_dev & 255) || workspace_bytes < WS_COUNTER_BYTES) return TW_ERR_ARG;
+  return twg::launch_zero_words((uint32_t*)workspace_dev, WS_COUNTER_BYTES / 4, (hipStream_t)stream) == hipSuccess
+             ? TW_OK : TW_ERR_HIP;
+}
+
+tw_status tw_gemm_ex(const void* A, int M, int lda, int layout, tw_handle_t h, void* C, int ldc,
+                     const tw_launch_opts* opts, void* stream) {
   if (!A || !C || !h || M < 1) return TW_ERR_ARG;
   if (layout != TW_LAYOUT_KM && layout != TW_LAYOUT_MK) return TW_ERR_ARG;
   if (!aligned16(A) || !aligned16(C) || lda % 8 || ldc % 8) return TW_ERR_ARG;
@@ -340,10 +444,19 @@ tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void
   } else if (lda < M || ldc < M) {
     return TW_ERR_ARG;
   }
-  return gemm_launch(A, M, lda, layout, h, C, ldc, stream, false);
+  Opts o;
+  if (!opts_from(opts, &o)) return TW_ERR_ARG;
+  return gemm_launch(o, A, M, lda, layout, h, C, ldc, stream, nullptr);
 }
 
-tw_status tw_conv_bind(tw_handle_t h, const tw_conv_geom* cg, int64_t ldx) {
+tw_status tw_gemm(const void* A, int M, int lda, int layout, tw_handle_t h, void* C, int ldc,
+                  void* stream) {
+  return tw_gemm_ex(A, M, lda, layout, h, C, ldc, nullptr, stream);
+}
+
+tw_status tw_conv_bind(tw_handle_t h, const tw_conv_geom* cg, int64_t ldx, tw_conv_t* out) {
+  if (!out) return TW_ERR_ARG;
+  *out = nullptr;
   if (!h || !cg) return TW_ERR_ARG;
   if (cg->C < 1 || cg->R < 1 || cg->S < 1 || cg->B < 1 || cg->H < 1 || cg->W < 1) return TW_ERR_ARG;
   if (cg->P < cg->W + cg->S - 1 || cg->L < cg->H + cg->R - 1) return TW_ERR_ARG;
@@ -359,9 +472,12 @@ tw_status tw_conv_bind(tw_handle_t h, const tw_conv_geom* cg, int64_t ldx) {
   if (hipGetDevice(&dev) != hipSuccess) return TW_ERR_HIP;
   if (dev != h->img.device) return TW_ERR_STATE;
   std::vector<int32_t> off;
+  tw_conv_s* b = new (std::nothrow) tw_conv_s();
+  if (!b) return TW_ERR_ALLOC;
   try {
     off.resize(h->img.row_idx.size());
   } catch (const std::bad_alloc&) {
+    delete b;
     return TW_ERR_ALLOC;
   }
   const int RS = cg->R * cg->S;
@@ -370,23 +486,30 @@ tw_status tw_conv_bind(tw_handle_t h, const tw_conv_geom* cg, int64_t ldx) {
     off[i] = (int32_t)((int64_t)c * ldx + (int64_t)r * cg->P + s);
   }
   int32_t* d = nullptr;
-  if (hipMalloc((void**)&d, off.size() * 4 + 4) != hipSuccess) { (void)hipGetLastError(); return TW_ERR_ALLOC; }
+  if (hipMalloc((void**)&d, off.size() * 4 + 4) != hipSuccess) { (void)hipGetLastError(); delete b; return TW_ERR_ALLOC; }
   if (hipMemcpy(d, off.data(), off.size() * 4, hipMemcpyHostToDevice) != hipSuccess) {
     (void)hipFree(d);
+    delete b;
     return TW_ERR_HIP;
   }
-  if (h->d_conv_off) (void)hipFree(h->d_conv_off);
-  h->d_conv_off = d; h->conv = *cg; h->conv_ldx = ldx;
+  b->h = h; b->geom = *cg; b->ldx = ldx; b->d_off = d;
+  *out = b;
   return TW_OK;
 }
 
-tw_status tw_conv_gemm(const void* X, tw_handle_t h, void* C, int ldc, void* stream) {
-  if (!X || !C || !h) return TW_ERR_ARG;
-  if (h->dtype != TW_DTYPE_F16) return TW_ERR_ARG;
-  if (!h->d_conv_off) return TW_ERR_STATE;
-  const int Mp = h->conv.B * h->conv.L * h->conv.P;
+tw_status tw_conv_free(tw_conv_t b) {
+  if (!b) return TW_OK;
+  const tw_status st = (b->d_off && hipFree(b->d_off) != hipSuccess) ? TW_ERR_HIP : TW_OK;
+  delete b;
+  return st;
+}
+
+tw_status tw_conv_gemm(const void* X, tw_conv_t b, void* C, int ldc, void* stream) {
+  if (!X || !C || !b || !b->h) return TW_ERR_ARG;
+  if (b->h->dtype != TW_DTYPE_F16) return TW_ERR_ARG;
+  const int Mp = b->geom.B * b->geom.L * b->geom.P;
   if (!aligned16(X) || !aligned16(C) || ldc % 8 || ldc < Mp) return TW_ERR_ARG;
-  return gemm_launch(X, Mp, 1, TW_LAYOUT_KM, h, C, ldc, stream, true);
+  return gemm_launch(default_opts(), X, Mp, 1, TW_LAYOUT_KM, b->h, C, ldc, stream, b);
 }
 
 tw_status tw_dense_gemm(const void* A, const void* B, void* C, int M, int K, int N, int lda,
@@ -406,27 +529,29 @@ tw_status tw_dense_gemm(const void* A, const void* B, void* C, int M, int K, int
   g.vals = (const _Float16*)B; g.ldb = ldb; g.K = K; g.N = N;
   const int tn = 128;
   g.n_tiles = (N + tn - 1) / tn;
-  g.xcd_map = opt_xcd_map.load();
+  const Opts o = default_opts();
+  g.xcd_map = o.xcd_map;
+  g.wg_split = 1;
   if (layout == TW_LAYOUT_MK) {
     hipError_t em = twg::launch_dense_mk(tn, g, (hipStream_t)stream);
     return em == hipSuccess ? TW_OK : TW_ERR_HIP;
   }
-  const int tm = pick_tile_m(M, g.n_tiles, tn, K);
+  const int tm = pick_tile_m(o, M, g.n_tiles, tn, K);
   hipError_t e = hipErrorInvalidValue;
   const bool fits32 = (unsigned long long)K * (unsigned long long)lda * 2ull < (1ull << 32) &&
                       (unsigned long long)K * (unsigned long long)ldb * 2ull < (1ull << 32);
-  if (opt_kernel.load() != 1 && K % 32 == 0 && fits32) {
-    int variant = (opt_waves.load() == 8 || tm == 256) ? twg::DMA_WAVES8 : twg::DMA_WAVES4;
+  if (o.kernel != 1 && K % 32 == 0 && fits32) {
+    int variant = (o.waves == 8 || tm == 256) ? twg::DMA_WAVES8 : twg::DMA_WAVES4;
     int tmk = tm;
-    const int ks = opt_ksplit.load();
+    const int ks = o.ksplit;
     if (K % 64 == 0 && (ks == 2 || (ks == 0 && use_ksplit(M, g.n_tiles, K, &tmk)))) variant = twg::DMA_KSPLIT2;
     if (variant == twg::DMA_KSPLIT2 && ks == 2) tmk = tm == 256 ? 128 : tm;
-    e = twg::launch_dense_km_dma(tn, variant == twg::DMA_KSPLIT2 ? tmk : tm, opt_depth.load(), variant, g,
+    e = twg::launch_dense_km_dma(tn, variant == twg::DMA_KSPLIT2 ? tmk : tm, o.depth, variant, g,
                                  (hipStream_t)stream);
     if (e == hipErrorInvalidValue && variant != twg::DMA_WAVES4)
-      e = twg::launch_dense_km_dma(tn, tm, opt_depth.load(), twg::DMA_WAVES4, g, (hipStream_t)stream);
+      e = twg::launch_dense_km_dma(tn, tm, o.depth, twg::DMA_WAVES4, g, (hipStream_t)stream);
   }
-  if (e == hipErrorInvalidValue && opt_kernel.load() != 2)
+  if (e == hipErrorInvalidValue && o.kernel != 2)
     e = twg::launch_dense_km(tn, tm, g, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;
@@ -435,38 +560,39 @@ tw_status tw_dense_gemm(const void* A, const void* B, void* C, int M, int K, int
 // int8 M-tile: 256 rows while that still gives every CU two workgroups, else 128.  The 64-row
 // instance (G = 128) is only used on request: it measured no better than 128 rows on the small
 // BERT-base launches and worse on the dense baseline.
-static int pick_tile_m_i8(int M, int n_tiles, int G) {
-  const int forced = opt_tile_m.load();
+static int pick_tile_m_i8(const Opts& o, int M, int n_tiles, int G) {
+  const int forced = o.tile_m;
   if (forced == 128 || forced == 256 || (forced == 64 && G == 128)) return forced;
   return (long)((M + 255) / 256) * n_tiles >= 512 ? 256 : 128;
 }
 
 // The launch behind tw_gemm_i8 and tw_conv_gemm_i8 (conv: see gemm_launch).
 static tw_status gemm_i8_launch(const void* A, int M, int lda, tw_handle_t h, void* C, int ldc, int c_dtype,
-                                float scale, void* stream, bool conv) {
+                                float scale, void* stream, const tw_conv_s* conv) {
+  const Opts o = default_opts();
   twg::GemmI8Args g{};
   g.A = (const int8_t*)A; g.C = C; g.M = M; g.lda = lda; g.ldc = ldc;
   g.c_i8 = c_dtype; g.scale = scale;
   g.vals = (const int8_t*)h->img.d_vals;
   g.row_idx = h->img.d_row_idx; g.col_idx = h->img.d_col_idx; g.tile_sched = h->img.d_tile_sched;
   if (conv) {
-    g.row_idx = h->d_conv_off;
-    g.conv_P = h->conv.P; g.conv_L = h->conv.L; g.conv_H = h->conv.H; g.conv_W = h->conv.W;
+    g.row_idx = conv->d_off;
+    g.conv_P = conv->geom.P; g.conv_L = conv->geom.L; g.conv_H = conv->geom.H; g.conv_W = conv->geom.W;
   }
   g.zero_cols = h->img.d_zero_cols; g.n_zero = (int)h->img.zero_cols.size();
-  g.n_tiles = h->n_tiles; g.K = h->K; g.N = h->N; g.xcd_map = opt_xcd_map.load() ? 1 : 0;
+  g.n_tiles = h->n_tiles; g.K = h->K; g.N = h->N; g.xcd_map = o.xcd_map ? 1 : 0;
   g.meta = h->img.d_meta;
   hipError_t e;
   if (h->pattern == TW_PATTERN_TVW) {
     // 64-row tiles where 128-row tiles would not give every CU a workgroup
-    const int forced = opt_tile_m.load();
+    const int forced = o.tile_m;
     const long wgs128 = (long)((M + 127) / 128) * (h->n_tiles > 0 ? h->n_tiles : 1);
     const int tm = h->G != 128 ? 128 : (forced == 64 || forced == 128) ? forced : (wgs128 <= 256 ? 64 : 128);
     e = twg::launch_tvw_i8(h->G, tm, g, (hipStream_t)stream);
   } else {
     // long K with too few tiles to fill the chip: split K inside the workgroup (as the fp16 path)
-    const int tm = pick_tile_m_i8(M, h->n_tiles > 0 ? h->n_tiles : 1, h->G);
-    const int ks = opt_ksplit.load();
+    const int tm = pick_tile_m_i8(o, M, h->n_tiles > 0 ? h->n_tiles : 1, h->G);
+    const int ks = o.ksplit;
     int tmk = tm;
     e = hipErrorInvalidValue;
     // (from 12 stages of 64 rows on: below that the reduction through LDS costs more than it saves)
@@ -489,18 +615,17 @@ tw_status tw_gemm_i8(const void* A, int M, int lda, tw_handle_t h, void* C, int 
   if (!h->img.blob) return TW_ERR_STATE;
   if (h->G == 32 || h->K > 131071) return TW_ERR_UNSUPPORTED;
   if ((unsigned long long)h->K * (unsigned long long)lda >= (1ull << 32)) return TW_ERR_UNSUPPORTED;
-  return gemm_i8_launch(A, M, lda, h, C, ldc, c_dtype, scale, stream, false);
+  return gemm_i8_launch(A, M, lda, h, C, ldc, c_dtype, scale, stream, nullptr);
 }
 
-tw_status tw_conv_gemm_i8(const void* X, tw_handle_t h, void* C, int ldc, int c_dtype, float scale,
+tw_status tw_conv_gemm_i8(const void* X, tw_conv_t b, void* C, int ldc, int c_dtype, float scale,
                           void* stream) {
-  if (!X || !C || !h || (c_dtype != 0 && c_dtype != 1)) return TW_ERR_ARG;
-  if (h->dtype != TW_DTYPE_I8) return TW_ERR_ARG;
-  if (!h->d_conv_off) return TW_ERR_STATE;
-  const int Mp = h->conv.B * h->conv.L * h->conv.P;
+  if (!X || !C || !b || !b->h || (c_dtype != 0 && c_dtype != 1)) return TW_ERR_ARG;
+  if (b->h->dtype != TW_DTYPE_I8) return TW_ERR_ARG;
+  const int Mp = b->geom.B * b->geom.L * b->geom.P;
   if (!aligned16(X) || !aligned16(C) || ldc % 16 || ldc < Mp) return TW_ERR_ARG;
-  if (h->K > 131071) return TW_ERR_UNSUPPORTED;
-  return gemm_i8_launch(X, Mp, 1, h, C, ldc, c_dtype, scale, stream, true);
+  if (b->h->K > 131071) return TW_ERR_UNSUPPORTED;
+  return gemm_i8_launch(X, Mp, 1, b->h, C, ldc, c_dtype, scale, stream, b);
 }
 
 tw_status tw_dense_gemm_i8(const void* A, const void* B, void* C, int M, int K, int N, int lda, int ldb,
@@ -518,8 +643,9 @@ tw_status tw_dense_gemm_i8(const void* A, const void* B, void* C, int M, int K, 
   g.vals = (const int8_t*)B; g.ldb = ldb; g.K = K; g.N = N;
   const int tn = 128;
   g.n_tiles = (N + tn - 1) / tn;
-  g.xcd_map = opt_xcd_map.load() ? 1 : 0;
-  hipError_t e = twg::launch_dense_i8(tn, pick_tile_m_i8(M, g.n_tiles, tn), g, (hipStream_t)stream);
+  const Opts o = default_opts();
+  g.xcd_map = o.xcd_map ? 1 : 0;
+  hipError_t e = twg::launch_dense_i8(tn, pick_tile_m_i8(o, M, g.n_tiles, tn), g, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
@@ -552,7 +678,6 @@ tw_status tw_free(tw_handle_t h) {
   if (!h) return TW_OK;
   tw_status st = TW_OK;
   if (h->img.blob && hipFree(h->img.blob) != hipSuccess) st = TW_ERR_HIP;
-  if (h->d_conv_off && hipFree(h->d_conv_off) != hipSuccess) st = TW_ERR_HIP;
   delete h;
   return st;
 }
@@ -564,8 +689,9 @@ tw_status tw_set_option(const char* name, int value) {
   if (!std::strcmp(name, "kernel")) { opt_kernel.store(value); return TW_OK; }
   if (!std::strcmp(name, "waves")) { opt_waves.store(value == 8 ? 8 : 4); return TW_OK; }
   if (!std::strcmp(name, "ksplit")) { opt_ksplit.store(value); return TW_OK; }
+  if (!std::strcmp(name, "wg_split")) { opt_wg_split.store(value < 0 || value > 8 ? 0 : value); return TW_OK; }
   if (!std::strcmp(name, "tile_order")) { twg::longest_first.store(value != 0); return TW_OK; }
-  if (!std::strcmp(name, "depth")) { opt_depth.store(value == 4 ? 4 : 3); return TW_OK; }
+  if (!std::strcmp(name, "depth")) { opt_depth.store(value >= 3 && value <= 8 ? value : 3); return TW_OK; }
   return TW_ERR_ARG;
 }
 

@@ -21,48 +21,6 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 constexpr int KS = 32;        // condensed rows per main-loop stage
 constexpr int NTHREADS = 256;
 
-// Developer build only (-DTWG_TRACE): wave 0 of the first workgroups records
-// constant-rate (100 MHz) timestamps at the phase boundaries of the main loop.
-#ifdef TWG_TRACE
-constexpr int TRACE_WGS = 2048, TRACE_SLOTS = 48;
-static __device__ unsigned long long twg_trace[2 * TRACE_WGS * TRACE_SLOTS];  // one per source file; two launches
-#if TWG_TRACE >= 2   // slot 0: where the workgroup runs (HW_ID, XCC_ID hardware registers)
-#define TWG_TRACE_INIT()                                         \
-  const bool trace_on = threadIdx.x == 0 && blockIdx.x < TRACE_WGS; \
-  int trace_n = 0;                                                  \
-  if (trace_on)                                                     \
-    twg_trace[(g.trace_slot * TRACE_WGS + blockIdx.x) * TRACE_SLOTS + trace_n++] =                    \
-        (unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 4) |                                \
-        ((unsigned long long)__builtin_amdgcn_s_getreg((31 << 11) | 20) << 32)
-// shader-clock counter into a fixed slot (46: first call, 47: second call)
-#define TWG_STAMP_CLK(which)                                                                          \
-  do {                                                                                                \
-    if (trace_on)                                                                                     \
-      twg_trace[(g.trace_slot * TRACE_WGS + blockIdx.x) * TRACE_SLOTS + 46 + (which)] = __builtin_amdgcn_s_memtime(); \
-  } while (0)
-#else
-#define TWG_STAMP_CLK(which) do {} while (0)
-#define TWG_TRACE_INIT()                                         \
-  const bool trace_on = threadIdx.x == 0 && blockIdx.x < TRACE_WGS; \
-  int trace_n = 0
-#endif
-#define TWG_STAMP()                                                                   \
-  do {                                                                                \
-    if (trace_on && trace_n < TRACE_SLOTS - 2)                                          \
-      twg_trace[(g.trace_slot * TRACE_WGS + blockIdx.x) * TRACE_SLOTS + trace_n++] = __builtin_amdgcn_s_memrealtime(); \
-  } while (0)
-#if TWG_TRACE == 2
-#define TWG_STAMP_FINE() TWG_STAMP()     // per-iteration stamps perturb the pipeline: level 2 only (3 = 2 without them)
-#else
-#define TWG_STAMP_FINE() do {} while (0)
-#endif
-#else
-#define TWG_TRACE_INIT() do {} while (0)
-#define TWG_STAMP_CLK(which) do {} while (0)
-#define TWG_STAMP() do {} while (0)
-#define TWG_STAMP_FINE() do {} while (0)
-#endif
-
 // XOR mask applied to the byte offset inside a row of a k-major LDS tile with
 // RB bytes per row.  The LDS has 64 banks of 4 bytes; one half-wave of a
 // transposing read touches 4 consecutive rows x 64 bytes, and the mask sends

@@ -74,7 +74,19 @@ __device__ __forceinline__ int4v scalar_load4(const void* p) {
 
 template <int N>
 __device__ __forceinline__ void wait_vm() {
+  static_assert(N >= 0 && N <= 63, "vmcnt is a 6-bit counter");
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// Waits until at most `newer` stages of NPS copies each are outstanding (newer <= MAXN; in the
+// steady state newer == MAXN and the first comparison decides).
+template <int NPS, int MAXN>
+__device__ __forceinline__ void wait_stage(int newer) {
+  if constexpr (MAXN == 0) wait_vm<0>();
+  else {
+    if (newer >= MAXN) wait_vm<MAXN * NPS>();
+    else wait_stage<NPS, MAXN - 1>(newer);
+  }
 }
 
 }  // namespace
@@ -169,7 +181,13 @@ __device__ __forceinline__ void ew_fill_column(const GemmArgs& g, int which) {
   }
 }
 
-template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KSPLIT = 1, bool EW = false>
+// SPLIT: K split across workgroups.  g.wg_split workgroups own the same (M-tile, N-tile) pair,
+// each a contiguous share of the tile's stages; every one writes its fp32 partial tile to the
+// workspace and takes a ticket at the pair's counter; the one that arrives last adds all partial
+// tiles in split order (so the sum does not depend on who was last), runs the epilogue and puts
+// the counter back to zero.  Nobody waits for anybody: a workgroup that is not last is done.
+template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KSPLIT = 1, bool EW = false,
+          bool SPLIT = false>
 // (the TEW epilogue must not cost the 128 x 128 instance its third wave per SIMD: the second
 // launch-bound asks the compiler to keep the register count within that occupancy)
 __global__ __launch_bounds__(NWAVES * 64, (EW && TM <= 128 && TN <= 128 && NWAVES == 4) ? 3 : 1)
@@ -188,7 +206,7 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
   constexpr int NIA = STAGE_A / (1024 * NWAVES), NIB = STAGE_B / (1024 * NWAVES);   // copy instructions per wave and stage
   constexpr int RPIA = 1024 / RBA, RPIB = 1024 / RBB;         // tile rows per copy instruction
   static_assert((RPIA == 2 || RPIA == 4 || RPIA == 8) && (NIA == 1 || NIA == 2 || NIA == 4), "");
-  static_assert(D == 3 || D == 4, "the stage wait below handles up to two newer stages");
+  static_assert(D >= 3 && D <= 8, "stages in flight");
   constexpr int NPS = NIA + NIB;
   constexpr int CA = TM / 8;
   // epilogue row bytes: fp16, 66 dwords mod 64 banks = 2; with restored elements to add (EW) the
@@ -198,22 +216,39 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
   constexpr int PIPE_BYTES = D * STAGE, EPI_BYTES = (EW ? TN / 2 : TN) * CS;   // EW stages half a tile at a time
   constexpr int RED_BYTES = KSPLIT > 1 ? TM * TN * 4 : 0;      // partial accumulators of group 1
   static_assert(RED_BYTES <= PIPE_BYTES, "the reduction reuses the pipeline buffers");
-  constexpr int LDS_BYTES = PIPE_BYTES > EPI_BYTES ? PIPE_BYTES : EPI_BYTES;
+  // kept-row lists travel through LDS as well: a ring of two chunks of 8 stages' indices behind
+  // the pipeline buffers (the epilogue staging reuses the pipeline buffers only)
+  constexpr int CH = 8 * KSS;                              // indices per chunk
+  constexpr int NCI = CH * 4 / 1024;                       // 1 KiB copy instructions per chunk
+  static_assert(NCI >= 1 && NCI <= NWAVES && CH * 4 % 1024 == 0, "");
+  constexpr int MAIN_BYTES = PIPE_BYTES > EPI_BYTES ? PIPE_BYTES : EPI_BYTES;
+  constexpr int IDX_OFF = (MAIN_BYTES + 1023) / 1024 * 1024;
+  constexpr int LDS_BYTES = IDX_OFF + (DENSE ? 0 : 2 * CH * 4);
   __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int n_gemm = g.n_mtiles * g.n_tiles;
-  TWG_TRACE_INIT();
-  TWG_STAMP();
-  TWG_STAMP_CLK(0);
+  static_assert(!SPLIT || (!DENSE && !EW && KSPLIT == 1), "the split across workgroups exists for plain TW");
+  const int S = SPLIT ? g.wg_split : 1;
+  const int n_gemm = g.n_mtiles * g.n_tiles * S;
   if ((int)blockIdx.x >= n_gemm) {
     if constexpr (EW) ew_fill_column(g, blockIdx.x - n_gemm);
     else zero_fill_column(g, blockIdx.x - n_gemm);
     return;
   }
   int mt, t;                             // t: launch position of the tile, then the tile itself
-  tile_of_workgroup(g, blockIdx.x, n_gemm, mt, t);
+  int pair = 0, split = 0;
+  if constexpr (SPLIT) {
+    // the workgroups of a pair are neighbours in the XCD's contiguous range of logical ids:
+    // they run on the same XCD at about the same time, and their partial tiles meet in its L2
+    const int lid = g.xcd_map ? xcd_remap(blockIdx.x, n_gemm) : (int)blockIdx.x;
+    pair = lid / S;
+    split = lid - pair * S;
+    mt = pair / g.n_tiles;
+    t = pair - mt * g.n_tiles;
+  } else {
+    tile_of_workgroup(g, blockIdx.x, n_gemm, mt, t);
+  }
   const int m0 = mt * TM;
 
   int kp0, ns32;                                       // ns32: stages of 32 rows
@@ -221,6 +256,11 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
   else {
     const int4v rec = scalar_load4(g.tile_sched + 4 * t);
     t = rec[0]; kp0 = rec[1]; ns32 = rec[2] / KS;
+  }
+  if constexpr (SPLIT) {                               // this workgroup's share of the stages
+    const int first = ns32 * split / S, last = ns32 * (split + 1) / S;
+    kp0 += first * KS;
+    ns32 = last - first;
   }
   const int ns = (ns32 + KSPLIT - 1) / KSPLIT;         // pipeline stages of KSS rows
   const _Float16* Bt = DENSE ? g.vals + (size_t)t * TN : g.vals + (size_t)kp0 * TN;
@@ -267,32 +307,37 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
   for (int j = 0; j < NIB; ++j)
     b_off[j] = (uint32_t)((wave * NIB + j) * RPIB + b_rloc) * ldb2 + (uint32_t)b_el[j] * 2u;
 
-  // Row indices of a stage for copy instruction j: RPIA consecutive entries of
-  // the kept-row list at a wave-uniform address.  They are fetched with scalar
-  // loads written in assembly: a vector load would share the in-order counter
-  // of the asynchronous copies, and waiting for it would drain the pipeline.
-  // Scalar loads return out of order, so they are always waited for with a full
-  // lgkmcnt(0); each fetch is issued right after a stage barrier and waited for
-  // together with the first operand reads of that stage, one iteration before
-  // its rows are needed.
-  typedef int sidx_t __attribute__((ext_vector_type(RPIA)));
-  struct Rows { sidx_t r[NIA]; };
-  auto fetch_rows = [&](int s, Rows& dst) {
+  // Row indices (Listing 1: CTO_k) reach the lanes through LDS.  Chunk c of a tile's kept-row
+  // list (8 stages' worth) is copied into half c % 2 of a small ring by the same asynchronous
+  // copies as the operand tiles, so it is tracked by the same in-order counter and has landed,
+  // at no extra wait, long before its first stage is issued; every lane then picks the index
+  // of the row it copies with one ds_read_b32 per copy instruction, issued next to the operand
+  // reads of the stage and waited for with them.  (Scalar loads of the list, the earlier
+  // scheme, miss the scalar cache on every stage and return out of order: their full round
+  // trip to L2 sat in every iteration, 0.15 us per stage where one workgroup has a CU to itself.)
+  struct Rows { int r[NIA]; };
+  const uint32_t idx_lds0 = (uint32_t)(uintptr_t)LDS_PTR(char, lds) + IDX_OFF;
+  auto issue_chunk = [&](int c) {        // waves 0 .. NCI-1: 1 KiB of the list each
+    if constexpr (!DENSE) {
+      if (wave < NCI)
+        __builtin_amdgcn_global_load_lds(GLOBAL_PTR((const char*)(g.row_idx + kp0) + ((size_t)c * CH * 4 + wave * 1024 + lb)),
+                                         LDS_PTR(void, lds + IDX_OFF + (c & 1) * (CH * 4) + wave * 1024), 16, 0, 0);
+    }
+  };
+  auto fetch_rows = [&](int s, Rows& dst) {      // this lane's rows of stage s; valid after the next LDS wait
     if constexpr (!DENSE) {
 #pragma unroll
       for (int j = 0; j < NIA; ++j) {
-        const int* rp = g.row_idx + kp0 + s * KSS + (wave * NIA + j) * RPIA;
-        if constexpr (RPIA == 2) asm volatile("s_load_dwordx2 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
-        else if constexpr (RPIA == 4) asm volatile("s_load_dwordx4 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
-        else asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
+        const uint32_t pos = (uint32_t)(s * KSS + (wave * NIA + j) * RPIA + a_rloc) & (2 * CH - 1);
+        asm volatile("ds_read_b32 %0, %1" : "=v"(dst.r[j]) : "v"(idx_lds0 + pos * 4));
       }
     }
   };
   auto tie_rows = [&](Rows& x) {      // after a wait: no use of x may be moved above this point
     if constexpr (!DENSE) {
-      if constexpr (NIA == 1) asm volatile("" : "+s"(x.r[0]));
-      else if constexpr (NIA == 2) asm volatile("" : "+s"(x.r[0]), "+s"(x.r[1]));
-      else asm volatile("" : "+s"(x.r[0]), "+s"(x.r[1]), "+s"(x.r[2]), "+s"(x.r[3]));
+      if constexpr (NIA == 1) asm volatile("" : "+v"(x.r[0]));
+      else if constexpr (NIA == 2) asm volatile("" : "+v"(x.r[0]), "+v"(x.r[1]));
+      else asm volatile("" : "+v"(x.r[0]), "+v"(x.r[1]), "+v"(x.r[2]), "+v"(x.r[3]));
     }
   };
   auto issue = [&](int s, const Rows& rows) {     // copies of stage s; rows = its kept-row indices
@@ -307,11 +352,7 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
     for (int j = 0; j < NIA; ++j) {
       int row;
       if constexpr (DENSE) row = s * KSS + (wave * NIA + j) * RPIA + a_rloc;
-      else {
-        row = rows.r[j][0];
-#pragma unroll
-        for (int q = 1; q < RPIA; ++q) row = (a_rloc == q) ? rows.r[j][q] : row;
-      }
+      else row = rows.r[j];
       __builtin_amdgcn_global_load_lds(GLOBAL_PTR(Abase + ((uint32_t)row * lda2 + (uint32_t)a_el[j] * 2u)),
                                        LDS_PTR(void, dstA + (wave * NIA + j) * 1024), 16, 0, 0);
     }
@@ -365,51 +406,105 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
   using K0 = std::integral_constant<int, 0>;
   using K16 = std::integral_constant<int, 16>;
 
-  Rows rows_cur, rows_next;
+  Rows rows_next;
   if (ns > 0) {
-    // kept-row lists of the first D stages in one round trip, then D-1 stages of copies
-    Rows pro[D];
+    // the first two chunks of the kept-row list, then the indices and copies of D-1 stages
+    issue_chunk(0);
+    if (ns > 8) issue_chunk(1);
+    Rows pro[D - 1];
+    if constexpr (!DENSE) {
+      wait_vm<0>();
+      asm volatile("s_barrier" ::: "memory");
+    }
 #pragma unroll
-    for (int d = 0; d < D; ++d) fetch_rows(d < ns ? d : ns - 1, pro[d]);
+    for (int d = 0; d < D - 1; ++d) fetch_rows(d < ns ? d : ns - 1, pro[d]);
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-    for (int d = 0; d < D; ++d) tie_rows(pro[d]);
+    for (int d = 0; d < D - 1; ++d) tie_rows(pro[d]);
 #pragma unroll
     for (int d = 0; d < D - 1; ++d)
       if (d < ns) issue(d, pro[d]);
-    rows_cur = pro[D - 1];
   }
-  TWG_STAMP_FINE();
   bool live_prev = false;
   for (int s = 0; s < ns; ++s) {
     // own copies of stage s have landed: at most the copies of the newer stages remain
+    // (a wave that also copies list chunks waits for one copy more at times: harmless)
     int newer = ns - 1 - s;
     if (newer > D - 2) newer = D - 2;
-    if (newer >= 2) wait_vm<2 * NPS>();
-    else if (newer == 1) wait_vm<NPS>();
-    else wait_vm<0>();
-    TWG_STAMP_FINE();
+    wait_stage<NPS, D - 2>(newer);
     // everybody's copies of stage s have landed, everybody is done reading stage s-1
     asm volatile("s_barrier" ::: "memory");
-    TWG_STAMP_FINE();
-    fetch_rows(s + D < ns ? s + D : ns - 1, rows_next);   // needed by the next iteration
+    const int sn = s + D - 1;                              // the stage this iteration issues
+    fetch_rows(sn < ns ? sn : ns - 1, rows_next);
     const uint32_t boff = (uint32_t)((s % D) * STAGE);
     read_step(boff, K0{}, f0);
     if (s > 0 && live_prev) mfma_step(f1);   // second k-step of the previous stage
     const bool live = s * KSPLIT + grp < ns32;   // false only for group 1 on an odd tail
-    wait_lds<NF>(f0);                    // full wait: the scalar loads above are in as well
+    wait_lds<NF>(f0);                    // full wait: the index reads above are in as well
     tie_rows(rows_next);
-    // the copies of stage s+D-1 go into the buffer of stage s-1, which every wave
-    // has finished reading
-    if (s + D - 1 < ns) issue(s + D - 1, rows_cur);
+    // the copies of stage sn go into the buffer of stage s-1, which every wave has finished
+    // reading; when sn opens chunk c >= 1 of the list, chunk c+1 follows it into the half of
+    // the ring whose last reader (stage 8c-1, one iteration ago) is behind this barrier
+    if (sn < ns) {
+      issue(sn, rows_next);
+      if ((sn & 7) == 0 && sn >= 8 && sn + 8 < ns) issue_chunk((sn >> 3) + 1);
+    }
     read_step(boff, K16{}, f1);
     if (live) mfma_step(f0);
     live_prev = live;
-    rows_cur = rows_next;
     wait_lds<NF>(f1);
-    TWG_STAMP_FINE();
   }
   if (ns > 0 && live_prev) mfma_step(f1);
+
+  if constexpr (SPLIT) {
+    if (S > 1) {
+      __shared__ int ticket;
+      constexpr int TILE = TM * TN;                       // floats per partial tile
+      // partial tile as [wave][block][register][lane]: every store instruction of a wave is 256
+      // contiguous bytes
+      float* tile0 = g.ws_partials + (size_t)pair * S * TILE + wave * (MB * NB * 16 * 64) + lane;
+      float* mine = tile0 + (size_t)split * TILE;
+      // Partial tiles travel as device-scope relaxed atomic stores and loads: each access is
+      // performed at the level that is coherent across the XCDs' L2 caches, so no cache-wide
+      // write-back or invalidate is needed (a device-scope fence costs one of each per
+      // workgroup and made the launch several times slower).  Order: own stores complete
+      // (vmcnt), the workgroup's waves meet, then the ticket; the last arriver loads after it
+      // has seen every ticket taken.
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r)
+            __hip_atomic_store(mine + ((i * NB + j) * 16 + r) * 64, acc[i][j][r], __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+      wait_vm<0>();
+      __syncthreads();
+      if (tid == 0)
+        ticket = __hip_atomic_fetch_add(g.ws_counters + pair, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __syncthreads();
+      if (ticket != S - 1) return;                        // not the last one: done
+#pragma unroll
+      for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+      for (int q = 0; q < S; ++q) {                       // fixed order: the result does not depend on who is last
+        const float* part = tile0 + (size_t)q * TILE;
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+          for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+              acc[i][j][r] += __hip_atomic_load(part + ((i * NB + j) * 16 + r) * 64, __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT);
+      }
+      if (tid == 0)                                       // ready for the next launch
+        __hip_atomic_store(g.ws_counters + pair, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
 
   // ---- epilogue: fp32 -> fp16 (RNE), stage as [n][m], store rows of C^T ----
   const int m = m0 + c * 8;
@@ -417,7 +512,6 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
 #pragma unroll
   for (int i = 0; i < NPASS; ++i)
     dst_off[i] = (cols[i] < 0 || m >= g.M) ? -1 : (long long)cols[i] * g.ldc + m;
-  TWG_STAMP_FINE();
   __syncthreads();
   if constexpr (KSPLIT > 1) {
     // group 1 hands its fp32 partial sums to group 0: [wave in group][register][lane]
@@ -518,8 +612,7 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
         }
     }
     __syncthreads();
-    TWG_STAMP_FINE();
-    // all staged chunks into registers first, then the stores back to back; C is
+      // all staged chunks into registers first, then the stores back to back; C is
     // written once and not read again here: streaming (non-temporal) stores keep it
     // from lingering dirty in L2 until the end-of-kernel write-back
     union Chunk { uint2 h[2]; u32x4 v; };   // staging rows are 8-byte aligned only
@@ -547,16 +640,15 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
       }
     }
   }
-  TWG_STAMP();
-  TWG_STAMP_CLK(1);
 }
 
-template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KSPLIT = 1, bool EW = false>
+template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KSPLIT = 1, bool EW = false,
+          bool SPLIT = false>
 static hipError_t launch(const GemmArgs& g, hipStream_t stream) {
-  const int grid = g.n_mtiles * g.n_tiles + g.n_zero;
+  const int grid = g.n_mtiles * g.n_tiles * (SPLIT ? g.wg_split : 1) + g.n_zero;
   if (grid <= 0) return hipSuccess;
   (void)hipGetLastError();   // an error left behind by an earlier call of this thread is not this launch's
-  hipLaunchKernelGGL((tw_gemm_km_dma_kernel<TM, TN, WAVES_M, D, DENSE, NWAVES, KSPLIT, EW>), dim3(grid),
+  hipLaunchKernelGGL((tw_gemm_km_dma_kernel<TM, TN, WAVES_M, D, DENSE, NWAVES, KSPLIT, EW, SPLIT>), dim3(grid),
                      dim3(NWAVES * 64), 0, stream, g);
   return hipGetLastError();
 }
@@ -602,18 +694,34 @@ static hipError_t dispatch(int G, int tm, int depth, int variant, GemmArgs& g, h
   TWG_CASE(64, 128, 1, 4) TWG_CASE(128, 128, 2, 4) TWG_CASE(256, 128, 2, 4)
   TWG_CASE(128, 64, 2, 3) TWG_CASE(256, 64, 4, 3)
   TWG_CASE(128, 64, 2, 4) TWG_CASE(256, 64, 4, 4)
+  // deep pipelines for launches with about one workgroup per CU: LDS is there to be used
+  TWG_CASE(64, 128, 1, 6) TWG_CASE(128, 128, 2, 6) TWG_CASE(128, 64, 2, 6)
+  TWG_CASE(64, 128, 1, 8) TWG_CASE(128, 128, 2, 8) TWG_CASE(128, 64, 2, 8)
 #undef TWG_CASE
   return hipErrorInvalidValue;
 }
 
-#ifdef TWG_TRACE
-extern "C" int tw_debug_read_trace_dma(unsigned long long* out, int n) {
-  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(twg_trace), sizeof(unsigned long long) * n);
-}
-#endif
-
 hipError_t launch_tw_km_dma(int G, int tm, int depth, int variant, GemmArgs g, hipStream_t stream) {
   return dispatch<false>(G, tm, depth, variant, g, stream);
+}
+static __global__ void zero_words(uint32_t* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0u;
+}
+hipError_t launch_zero_words(uint32_t* p, int n, hipStream_t stream) {
+  if (n <= 0) return hipSuccess;
+  (void)hipGetLastError();
+  hipLaunchKernelGGL(zero_words, dim3((n + 255) / 256), dim3(256), 0, stream, p, n);
+  return hipGetLastError();
+}
+
+hipError_t launch_tw_km_dma_split(int G, int tm, GemmArgs g, hipStream_t stream) {
+  if (g.wg_split < 1 || !g.ws_partials || !g.ws_counters) return hipErrorInvalidValue;
+  g.n_mtiles = (g.M + tm - 1) / tm;
+  if (G == 128 && tm == 128) return launch<128, 128, 2, 3, false, 4, 1, false, true>(g, stream);
+  if (G == 128 && tm == 64) return launch<64, 128, 1, 3, false, 4, 1, false, true>(g, stream);
+  if (G == 64 && tm == 128) return launch<128, 64, 2, 3, false, 4, 1, false, true>(g, stream);
+  return hipErrorInvalidValue;
 }
 hipError_t launch_tew_km_dma(int G, int tm, int depth, int variant, GemmArgs g, hipStream_t stream) {
   if (depth != 3) return hipErrorInvalidValue;

@@ -62,8 +62,6 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_gemm = g.n_mtiles * g.n_tiles;
-  TWG_TRACE_INIT();
-  TWG_STAMP();
 
   // ---- extra workgroups: +0 into the pruned columns of C -----------------
   if ((int)blockIdx.x >= n_gemm) {
@@ -198,9 +196,7 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
   auto body = [&](int s, auto P_, auto LOAD_) {
     constexpr int P = decltype(P_)::value;
     constexpr bool LOAD = decltype(LOAD_)::value;
-    TWG_STAMP();
     store_stage(s & 1, ra[P], rb[P]);
-    TWG_STAMP();
     if constexpr (LOAD) {
       // issue order matters (loads retire in order): index list of stage s+3
       // first, then the data of stage s+2, so that waiting for an index list
@@ -213,7 +209,6 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
     }
     // LDS writes done, then workgroup barrier; outstanding global loads stay in flight
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    TWG_STAMP();
     const char* As = lds + (s & 1) * (STAGE_A + STAGE_B);
     const char* Bs = As + STAGE_A;
 #pragma unroll
@@ -260,9 +255,7 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
 #pragma unroll
   for (int i = 0; i < NPASS; ++i)
     dst_off[i] = (cols[i] < 0 || m >= g.M) ? -1 : (long long)cols[i] * g.ldc + m;
-  TWG_STAMP();
   __syncthreads();
-  TWG_STAMP();
 #pragma unroll
   for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -298,7 +291,6 @@ __global__ __launch_bounds__(NTHREADS) void tw_gemm_km_kernel(GemmArgs g) {
       }
     }
   }
-  TWG_STAMP();
 }
 
 template <int TM, int TN, int WAVES_M, bool DENSE, bool MK>
@@ -332,11 +324,6 @@ static hipError_t dispatch_mk(int G, GemmArgs& g, hipStream_t stream) {
   return hipErrorInvalidValue;
 }
 
-#ifdef TWG_TRACE
-extern "C" int tw_debug_read_trace(unsigned long long* out, int n) {
-  return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(twg_trace), sizeof(unsigned long long) * n);
-}
-#endif
 
 hipError_t launch_tw_km(int G, int tm, GemmArgs g, hipStream_t stream) {
   return dispatch<false>(G, tm, g, stream);

@@ -30,9 +30,12 @@ struct GemmArgs {
   // element offsets, lda = 1) and M counts the positions of the wide grid, P per line, L lines
   // per image block; positions with x >= W or y >= H are written as +0.
   int conv_P, conv_L, conv_H, conv_W;
-#ifdef TWG_TRACE
-  int trace_slot;                // developer build: which of two trace buffers this launch writes
-#endif
+  // K split across workgroups (1 = off): wg_split workgroups share one (M-tile, N-tile) pair on
+  // disjoint ranges of the kept rows; fp32 partial tiles go to ws_partials, the workgroup that
+  // arrives last at ws_counters[pair] adds them up in split order and runs the epilogue.
+  int wg_split;
+  float* ws_partials;            // [pair][split][tile] fp32
+  int* ws_counters;              // one per pair; zero between launches (the last arriver resets it)
 };
 
 // Int8 operands, int32 sums (gemm_i8.hip); layouts as the KM kernels above.
@@ -77,9 +80,14 @@ hipError_t launch_dense_mk(int tn, GemmArgs g, hipStream_t stream);
 // the workgroup (dense: K % 64 == 0).
 enum { DMA_WAVES4 = 0, DMA_WAVES8 = 1, DMA_KSPLIT2 = 2 };
 hipError_t launch_tw_km_dma(int G, int tm, int depth, int variant, GemmArgs g, hipStream_t stream);
+// The same with K split across g.wg_split workgroups per tile (4 waves, 3 stages): (G, tm) in
+// {(128, 128), (128, 64), (64, 128)}.
+hipError_t launch_tw_km_dma_split(int G, int tm, GemmArgs g, hipStream_t stream);
 // The same with the restored elements of a TEW weight added in the epilogue (g.ew_*).
 hipError_t launch_tew_km_dma(int G, int tm, int depth, int variant, GemmArgs g, hipStream_t stream);
 hipError_t launch_dense_km_dma(int tn, int tm, int depth, int variant, GemmArgs g, hipStream_t stream);
+// Zero fill of n 32-bit words (the counters of a workspace).
+hipError_t launch_zero_words(uint32_t* p, int n, hipStream_t stream);
 // TVW (2:4 inside the kept rows) on the sparse matrix instruction (gemm_tvw.hip).
 hipError_t launch_tvw_km(int G, int tm, int depth, GemmArgs g, hipStream_t stream);
 

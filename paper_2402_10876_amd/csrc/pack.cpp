@@ -302,9 +302,10 @@ void build_device_image(tw_handle_s* h) {
     d.tile_kp_off[t + 1] = d.tile_kp_off[t] + kp;
     h->max_kp = std::max(h->max_kp, kp);
   }
-  // one stage of slack behind the last tile: the K-split kernel copies stages of
-  // 64 rows and may run one 32-row stage past a tile's end (it never multiplies it)
-  d.row_idx.assign((size_t)d.tile_kp_off[nt] + KSTEP_I8_TVW, 0);
+  // slack behind the last tile (valid row 0): the K-split kernel copies stages of 64 rows and
+  // may run one 32-row stage past a tile's end (it never multiplies it), and the TW kernel
+  // stages the list through LDS in chunks of 8 stages, up to two chunks past a short tile
+  d.row_idx.assign((size_t)d.tile_kp_off[nt] + ROW_IDX_SLACK, 0);
   for (int t = 0; t < nt; ++t) {
     const int k0 = h->tile_k_off[t], kt = h->tile_k_off[t + 1] - k0;
     const int kp0 = d.tile_kp_off[t], kp = d.tile_kp_off[t + 1] - kp0;

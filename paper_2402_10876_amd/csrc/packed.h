@@ -17,6 +17,7 @@ constexpr int KSTEP_TW = 32;
 constexpr int KSTEP_TVW = 64;
 constexpr int KSTEP_I8 = 64;     // int8 TW: one stage = two 32x32x32 matrix-core steps
 constexpr int KSTEP_I8_TVW = 128; // int8 TVW: one stage = two 32x32x64 sparse steps
+constexpr int ROW_IDX_SLACK = 1024 + KSTEP_I8_TVW;   // readable entries behind the last tile's list
 
 struct DeviceImage {
   // host staging (filled by the packer)
@@ -63,11 +64,6 @@ struct tw_handle_s {
   int32_t k_union = 0;  // K rows kept by at least one tile
   int32_t max_kp = 0;  // largest padded K_t
   twg::DeviceImage img;
-  // implicit img2col binding (tw_conv_bind): geometry and the device list of window offsets
-  // parallel to img.row_idx
-  tw_conv_geom conv{};
-  int64_t conv_ldx = 0;
-  int32_t* d_conv_off = nullptr;
 };
 
 namespace twg {

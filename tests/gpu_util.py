@@ -142,10 +142,11 @@ def run_conv(tw, packed, X16, geom, N, *, ldc=None, fill=float("nan")):
     torch = _torch()
     Mp = geom.Mp
     Xd = torch.from_numpy(np.ascontiguousarray(X16)).cuda()
-    tw.tw_conv_bind(packed, geom, X16.shape[1])
+    b = tw.tw_conv_bind(packed, geom, X16.shape[1])
     Ct, ldc = new_C(N, Mp, ldc, fill)
-    tw.tw_conv_gemm(Xd.data_ptr(), packed, Ct.data_ptr(), ldc, torch.cuda.current_stream().cuda_stream)
+    tw.tw_conv_gemm(Xd.data_ptr(), b, Ct.data_ptr(), ldc, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
+    b.free()
     raw = Ct.cpu().numpy()
     return raw[:, :Mp].T.astype(np.float64), raw
 
@@ -156,9 +157,10 @@ def run_conv_i8(tw, packed, X8, geom, N, *, c_dtype=0, scale=1.0, ldc=None, fill
     torch = _torch()
     Mp = geom.Mp
     Xd = torch.from_numpy(np.ascontiguousarray(X8)).cuda()
-    tw.tw_conv_bind(packed, geom, X8.shape[1])
+    b = tw.tw_conv_bind(packed, geom, X8.shape[1])
     Ct, ldc = new_C_i8(N, Mp, c_dtype, ldc, fill)
-    tw.tw_conv_gemm_i8(Xd.data_ptr(), packed, Ct.data_ptr(), ldc, c_dtype, scale, torch.cuda.current_stream().cuda_stream)
+    tw.tw_conv_gemm_i8(Xd.data_ptr(), b, Ct.data_ptr(), ldc, c_dtype, scale, torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
+    b.free()
     raw = Ct.cpu().numpy()
     return raw[:, :Mp].T.astype(np.int64), raw

@@ -26,14 +26,13 @@ def test_bind_argument_errors_need_no_device():
     assert _status(tw.tw_conv_bind, p, wl.ConvGeom(4, 3, 3, 1, 6, 6, 7, 8), ldx) == 1     # P < W+S-1
     assert _status(tw.tw_conv_bind, p, wl.ConvGeom(4, 3, 3, 1, 6, 6, 8, 7), ldx) == 1     # L < H+R-1
     assert _status(tw.tw_conv_bind, p, wl.same_geom(5, 3, 3, 1, 6, 6), ldx) == 1          # K != C*R*S
-    assert _status(tw.tw_conv_gemm, 0x10000, p, 0x20000, 64) == 6           # no geometry bound
     p32 = tw.tw_pack_host(np.ones((K, 32), np.float16), np.ones((K, 32), np.uint8), 32, tw.PATTERN_TW)
     assert _status(tw.tw_conv_bind, p32, g, ldx) == 3                       # G = 32
     p8 = tw.tw_pack_i8_host(np.ones((K, N), np.int8), np.ones((K, N), np.uint8), G)
     assert _status(tw.tw_conv_bind, p8, g, wl.conv_ldx(g, 16)) == 6         # int8 binds too, once uploaded
     assert _status(tw.tw_conv_bind, p8, g, wl.conv_ldx(g, 16) + 8) == 1     # int8 rows: multiples of 16
-    assert _status(tw.tw_conv_gemm, 0x10000, p8, 0x20000, 64) == 1          # fp16 launch, int8 handle
-    assert _status(tw.tw_conv_gemm_i8, 0x10000, p, 0x20000, 64) == 1        # int8 launch, fp16 handle
+    assert tw.lib().tw_conv_gemm(0x10000, None, 0x20000, 64, None) == 1     # a launch needs a binding
+    assert tw.lib().tw_conv_free(None) == 0
     for q in (p, p32, p8):
         q.free()
 

@@ -27,7 +27,7 @@ def test_captured_step_replays_bit_exactly():
     p_i8 = tw.tw_pack_i8(B8, mask, G)
     p_cv = tw.tw_pack(Bc, cmask, G, tw.PATTERN_TW)
     ldx = wl.conv_ldx(g)
-    tw.tw_conv_bind(p_cv, g, ldx)
+    b_cv = tw.tw_conv_bind(p_cv, g, ldx)
     ld, ld8 = 304, 304
     A16 = torch.randn((K, ld), dtype=torch.float16, device=dev)
     A8 = torch.randint(-127, 128, (K, ld8), dtype=torch.int8, device=dev)
@@ -40,7 +40,7 @@ def test_captured_step_replays_bit_exactly():
         tw.tw_gemm(A16.data_ptr(), M, ld, tw.LAYOUT_KM, p_tw, outs[0].data_ptr(), ld, stream)
         tw.tw_gemm(A16.data_ptr(), M, ld, tw.LAYOUT_KM, p_tvw, outs[1].data_ptr(), ld, stream)
         tw.tw_gemm_i8(A8.data_ptr(), M, ld8, p_i8, outs[2].data_ptr(), ld8, 1, 1.0 / 300.0, stream)
-        tw.tw_conv_gemm(X.data_ptr(), p_cv, outs[3].data_ptr(), ldc_cv, stream)
+        tw.tw_conv_gemm(X.data_ptr(), b_cv, outs[3].data_ptr(), ldc_cv, stream)
 
     step(torch.cuda.current_stream().cuda_stream)
     torch.cuda.synchronize()
