@@ -237,7 +237,8 @@ tw_status tw_gemm(const void* A_dev, int M, int lda, int layout, tw_handle_t h,
  *                   tile_m 0|64|128|256, kernel 0..2, depth 0|3..8, waves 0|4|8, ksplit 0..2,
  *                   xcd_map -1 (default) | 0 | 1 | 2,
  *                   wg_split 0 = automatic when a workspace is given, 1 = never,
- *                            2..8 = that many workgroups per (M-tile, N-tile) pair
+ *                            2..8 = that many workgroups per (M-tile, N-tile) pair,
+ *                   idx_route 0 = automatic, 1 = kept-row lists by scalar loads, 2 = through LDS
  *   workspace_dev device memory, 256-byte aligned, at least tw_gemm_workspace_bytes(h, M) bytes,
  *                 prepared ONCE with tw_workspace_init (its first 4 KiB are counters that every
  *                 launch leaves at zero again).  Launches that share a workspace must not
@@ -249,7 +250,7 @@ tw_status tw_gemm(const void* A_dev, int M, int lda, int layout, tw_handle_t h,
  * invalid option value, a misaligned workspace, or wg_split > 1 with a workspace too small.
  */
 typedef struct {
-  int32_t tile_m, kernel, depth, waves, ksplit, xcd_map, wg_split;
+  int32_t tile_m, kernel, depth, waves, ksplit, xcd_map, wg_split, idx_route;
   void* workspace_dev;
   size_t workspace_bytes;
 } tw_launch_opts;
@@ -374,6 +375,9 @@ const char* tw_status_str(int status);
  *              of a workgroup (long K, few tiles)
  *   "depth"    stages in flight of the asynchronous pipeline: 3 (default) .. 8 (6 and 8 exist for
               4-wave tiles of 64 x 128, 128 x 128 and 128 x 64 only; TVW: 3 or 4)
+   "idx_route" how the asynchronous TW kernel reads a tile's kept-row list: 0 = automatic
+              (through LDS where at most two 4-wave workgroups share a CU, scalar loads
+              otherwise), 1 = scalar loads, 2 = through LDS
    "wg_split" K split across workgroups (tw_gemm_ex with a workspace): 0 / 1 = off,
               2..8 = workgroups per (M-tile, N-tile) pair
  *   "tile_order"  read by tw_pack / tw_concat: 1 (default) = tiles are launched longest

@@ -19,18 +19,19 @@ std::atomic<int> opt_kernel{0};   // 0 = automatic, 1 = register-staged, 2 = asy
 std::atomic<int> opt_depth{3};
 std::atomic<int> opt_waves{4};
 std::atomic<int> opt_ksplit{0};   // 0 = automatic, 1 = off, 2 = two K groups per workgroup
-std::atomic<int> opt_wg_split{0}; // 0 = automatic (needs a workspace), 1 = off, 2..8 = workgroups per tile
+std::atomic<int> opt_wg_split{0}; // 0 / 1 = off, 2..8 = workgroups per tile (needs a workspace)
+std::atomic<int> opt_idx_route{0};// kept-row lists: 0 = automatic, 1 = scalar loads, 2 = through LDS
 
 // What one launch runs with: the caller's tw_launch_opts, or the process defaults above
 // (tw_set_option) when there is none.  Read once per call, never shared between calls.
 struct Opts {
-  int tile_m, xcd_map, kernel, depth, waves, ksplit, wg_split;
+  int tile_m, xcd_map, kernel, depth, waves, ksplit, wg_split, idx_route;
   void* ws;
   size_t ws_bytes;
 };
 Opts default_opts() {
   return Opts{opt_tile_m.load(), opt_xcd_map.load(), opt_kernel.load(), opt_depth.load(), opt_waves.load(),
-              opt_ksplit.load(), opt_wg_split.load(), nullptr, 0};
+              opt_ksplit.load(), opt_wg_split.load(), opt_idx_route.load(), nullptr, 0};
 }
 bool opts_from(const tw_launch_opts* in, Opts* o) {
   *o = default_opts();
@@ -40,8 +41,10 @@ bool opts_from(const tw_launch_opts* in, Opts* o) {
   if (in->depth != 0 && (in->depth < 3 || in->depth > 8)) return false;
   if (in->waves != 0 && in->waves != 4 && in->waves != 8) return false;
   if (in->xcd_map < -1 || in->xcd_map > 2 || in->wg_split < 0 || in->wg_split > 8) return false;
+  if (in->idx_route < 0 || in->idx_route > 2) return false;
   if (in->workspace_dev && ((uintptr_t)in->workspace_dev & 255)) return false;
   o->tile_m = in->tile_m; o->kernel = in->kernel; o->ksplit = in->ksplit; o->wg_split = in->wg_split;
+  o->idx_route = in->idx_route;
   o->depth = in->depth ? in->depth : 3;
   o->waves = in->waves ? in->waves : 4;
   o->xcd_map = in->xcd_map < 0 ? 1 : in->xcd_map;
@@ -396,9 +399,16 @@ static tw_status gemm_launch(const Opts& o, const void* A, int M, int lda, int l
     if (ks == 2 || (ks == 0 && use_ksplit(M, h->n_tiles, h->max_kp, &tmk))) variant = twg::DMA_KSPLIT2;
     if (variant == twg::DMA_KSPLIT2 && ks == 2) tmk = tm == 256 ? 128 : tm;
     if (variant == twg::DMA_KSPLIT2 && h->G == 64) tmk = 128;   // the one K-split instance for G = 64
-    e = launch_dma(h->G, variant == twg::DMA_KSPLIT2 ? tmk : tm, depth, variant, g, (hipStream_t)stream);
+    // kept-row lists through LDS where at most two 4-wave workgroups share a CU (nothing else
+    // there hides the scalar loads' round trip); by scalar loads for 8-wave tiles and full CUs
+    const int tmu = variant == twg::DMA_KSPLIT2 ? tmk : tm;
+    auto lidx_for = [&](int v, int t) {
+      if (o.idx_route) return o.idx_route == 2;
+      return v != twg::DMA_WAVES8 && (long)((M + t - 1) / t) * h->n_tiles <= 512;
+    };
+    e = launch_dma(h->G, tmu, depth, variant, lidx_for(variant, tmu), g, (hipStream_t)stream);
     if (e == hipErrorInvalidValue && variant != twg::DMA_WAVES4)
-      e = launch_dma(h->G, tm, depth, twg::DMA_WAVES4, g, (hipStream_t)stream);
+      e = launch_dma(h->G, tm, depth, twg::DMA_WAVES4, lidx_for(twg::DMA_WAVES4, tm), g, (hipStream_t)stream);
   }
   if (e == hipErrorInvalidValue && o.kernel != 2 && !tew && !conv)
     e = twg::launch_tw_km(h->G, tm, g, (hipStream_t)stream);
@@ -410,7 +420,7 @@ tw_status tw_launch_opts_init(tw_launch_opts* opts) {
   if (!opts) return TW_ERR_ARG;
   const Opts d = default_opts();
   opts->tile_m = d.tile_m; opts->kernel = d.kernel; opts->depth = d.depth; opts->waves = d.waves;
-  opts->ksplit = d.ksplit; opts->xcd_map = d.xcd_map; opts->wg_split = d.wg_split;
+  opts->ksplit = d.ksplit; opts->xcd_map = d.xcd_map; opts->wg_split = d.wg_split; opts->idx_route = d.idx_route;
   opts->workspace_dev = nullptr; opts->workspace_bytes = 0;
   return TW_OK;
 }
@@ -689,6 +699,7 @@ tw_status tw_set_option(const char* name, int value) {
   if (!std::strcmp(name, "kernel")) { opt_kernel.store(value); return TW_OK; }
   if (!std::strcmp(name, "waves")) { opt_waves.store(value == 8 ? 8 : 4); return TW_OK; }
   if (!std::strcmp(name, "ksplit")) { opt_ksplit.store(value); return TW_OK; }
+  if (!std::strcmp(name, "idx_route")) { opt_idx_route.store(value < 0 || value > 2 ? 0 : value); return TW_OK; }
   if (!std::strcmp(name, "wg_split")) { opt_wg_split.store(value < 0 || value > 8 ? 0 : value); return TW_OK; }
   if (!std::strcmp(name, "tile_order")) { twg::longest_first.store(value != 0); return TW_OK; }
   if (!std::strcmp(name, "depth")) { opt_depth.store(value >= 3 && value <= 8 ? value : 3); return TW_OK; }

@@ -186,8 +186,9 @@ __device__ __forceinline__ void ew_fill_column(const GemmArgs& g, int which) {
 // workspace and takes a ticket at the pair's counter; the one that arrives last adds all partial
 // tiles in split order (so the sum does not depend on who was last), runs the epilogue and puts
 // the counter back to zero.  Nobody waits for anybody: a workgroup that is not last is done.
+// LIDX: the kept-row list reaches the lanes through LDS (see fetch_rows) instead of scalar loads.
 template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KSPLIT = 1, bool EW = false,
-          bool SPLIT = false>
+          bool SPLIT = false, bool LIDX = true>
 // (the TEW epilogue must not cost the 128 x 128 instance its third wave per SIMD: the second
 // launch-bound asks the compiler to keep the register count within that occupancy)
 __global__ __launch_bounds__(NWAVES * 64, (EW && TM <= 128 && TN <= 128 && NWAVES == 4) ? 3 : 1)
@@ -223,7 +224,7 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
   static_assert(NCI >= 1 && NCI <= NWAVES && CH * 4 % 1024 == 0, "");
   constexpr int MAIN_BYTES = PIPE_BYTES > EPI_BYTES ? PIPE_BYTES : EPI_BYTES;
   constexpr int IDX_OFF = (MAIN_BYTES + 1023) / 1024 * 1024;
-  constexpr int LDS_BYTES = IDX_OFF + (DENSE ? 0 : 2 * CH * 4);
+  constexpr int LDS_BYTES = IDX_OFF + ((DENSE || !LIDX) ? 0 : 2 * CH * 4);
   __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -307,37 +308,55 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
   for (int j = 0; j < NIB; ++j)
     b_off[j] = (uint32_t)((wave * NIB + j) * RPIB + b_rloc) * ldb2 + (uint32_t)b_el[j] * 2u;
 
-  // Row indices (Listing 1: CTO_k) reach the lanes through LDS.  Chunk c of a tile's kept-row
-  // list (8 stages' worth) is copied into half c % 2 of a small ring by the same asynchronous
-  // copies as the operand tiles, so it is tracked by the same in-order counter and has landed,
-  // at no extra wait, long before its first stage is issued; every lane then picks the index
-  // of the row it copies with one ds_read_b32 per copy instruction, issued next to the operand
-  // reads of the stage and waited for with them.  (Scalar loads of the list, the earlier
-  // scheme, miss the scalar cache on every stage and return out of order: their full round
-  // trip to L2 sat in every iteration, 0.15 us per stage where one workgroup has a CU to itself.)
-  struct Rows { int r[NIA]; };
+  // Row indices (Listing 1: CTO_k), two ways, both issued right after a stage barrier and
+  // waited for with the first operand reads of that stage (one lgkmcnt(0) wait covers both).
+  // LIDX: through LDS.  Chunk c of a tile's kept-row list (8 stages' worth) is copied into
+  //   half c % 2 of a small ring by the same asynchronous copies as the operand tiles, so it
+  //   is tracked by the same in-order counter and has landed, at no extra wait, long before
+  //   its first stage is issued; every lane then picks the index of the row it copies with
+  //   one ds_read_b32 per copy instruction.
+  // else: scalar loads of the RPIA consecutive entries a copy instruction covers (wave-uniform
+  //   address), the lane selects its own.  They miss the scalar cache on every stage and
+  //   return out of order, so their whole round trip to L2 sits in the iteration.
+  // Measured on the same box: with at most two 4-wave workgroups per CU (or the K-split
+  // instances) the LDS route is 5-22 % faster, since nothing else on the CU hides that round
+  // trip; with many workgroups per CU it is hidden anyway and the ring's extra barrier and
+  // reads cost 3-5 %.  The host picks per launch.
+  typedef int sidx_t __attribute__((ext_vector_type(RPIA)));
+  struct Rows { std::conditional_t<LIDX, int, sidx_t> r[NIA]; };
   const uint32_t idx_lds0 = (uint32_t)(uintptr_t)LDS_PTR(char, lds) + IDX_OFF;
   auto issue_chunk = [&](int c) {        // waves 0 .. NCI-1: 1 KiB of the list each
-    if constexpr (!DENSE) {
+    if constexpr (!DENSE && LIDX) {
       if (wave < NCI)
         __builtin_amdgcn_global_load_lds(GLOBAL_PTR((const char*)(g.row_idx + kp0) + ((size_t)c * CH * 4 + wave * 1024 + lb)),
                                          LDS_PTR(void, lds + IDX_OFF + (c & 1) * (CH * 4) + wave * 1024), 16, 0, 0);
     }
   };
-  auto fetch_rows = [&](int s, Rows& dst) {      // this lane's rows of stage s; valid after the next LDS wait
+  auto fetch_rows = [&](int s, Rows& dst) {      // rows of stage s; valid after the next lgkmcnt(0) wait
     if constexpr (!DENSE) {
 #pragma unroll
       for (int j = 0; j < NIA; ++j) {
-        const uint32_t pos = (uint32_t)(s * KSS + (wave * NIA + j) * RPIA + a_rloc) & (2 * CH - 1);
-        asm volatile("ds_read_b32 %0, %1" : "=v"(dst.r[j]) : "v"(idx_lds0 + pos * 4));
+        if constexpr (LIDX) {
+          const uint32_t pos = (uint32_t)(s * KSS + (wave * NIA + j) * RPIA + a_rloc) & (2 * CH - 1);
+          asm volatile("ds_read_b32 %0, %1" : "=v"(dst.r[j]) : "v"(idx_lds0 + pos * 4));
+        } else {
+          const int* rp = g.row_idx + kp0 + s * KSS + (wave * NIA + j) * RPIA;
+          if constexpr (RPIA == 2) asm volatile("s_load_dwordx2 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
+          else if constexpr (RPIA == 4) asm volatile("s_load_dwordx4 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
+          else asm volatile("s_load_dwordx8 %0, %1, 0x0" : "=s"(dst.r[j]) : "s"(rp));
+        }
       }
     }
   };
   auto tie_rows = [&](Rows& x) {      // after a wait: no use of x may be moved above this point
-    if constexpr (!DENSE) {
+    if constexpr (!DENSE && LIDX) {
       if constexpr (NIA == 1) asm volatile("" : "+v"(x.r[0]));
       else if constexpr (NIA == 2) asm volatile("" : "+v"(x.r[0]), "+v"(x.r[1]));
       else asm volatile("" : "+v"(x.r[0]), "+v"(x.r[1]), "+v"(x.r[2]), "+v"(x.r[3]));
+    } else if constexpr (!DENSE) {
+      if constexpr (NIA == 1) asm volatile("" : "+s"(x.r[0]));
+      else if constexpr (NIA == 2) asm volatile("" : "+s"(x.r[0]), "+s"(x.r[1]));
+      else asm volatile("" : "+s"(x.r[0]), "+s"(x.r[1]), "+s"(x.r[2]), "+s"(x.r[3]));
     }
   };
   auto issue = [&](int s, const Rows& rows) {     // copies of stage s; rows = its kept-row indices
@@ -352,7 +371,12 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
     for (int j = 0; j < NIA; ++j) {
       int row;
       if constexpr (DENSE) row = s * KSS + (wave * NIA + j) * RPIA + a_rloc;
-      else row = rows.r[j];
+      else if constexpr (LIDX) row = rows.r[j];
+      else {
+        row = rows.r[j][0];
+#pragma unroll
+        for (int q = 1; q < RPIA; ++q) row = (a_rloc == q) ? rows.r[j][q] : row;
+      }
       __builtin_amdgcn_global_load_lds(GLOBAL_PTR(Abase + ((uint32_t)row * lda2 + (uint32_t)a_el[j] * 2u)),
                                        LDS_PTR(void, dstA + (wave * NIA + j) * 1024), 16, 0, 0);
     }
@@ -406,24 +430,26 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
   using K0 = std::integral_constant<int, 0>;
   using K16 = std::integral_constant<int, 16>;
 
-  Rows rows_next;
+  Rows rows_cur, rows_next;
   if (ns > 0) {
-    // the first two chunks of the kept-row list, then the indices and copies of D-1 stages
+    // (LIDX: the first two chunks of the kept-row list,) the indices of the first D stages in
+    // one round trip, then the copies of D-1 stages
     issue_chunk(0);
     if (ns > 8) issue_chunk(1);
-    Rows pro[D - 1];
-    if constexpr (!DENSE) {
+    Rows pro[D];
+    if constexpr (!DENSE && LIDX) {
       wait_vm<0>();
       asm volatile("s_barrier" ::: "memory");
     }
 #pragma unroll
-    for (int d = 0; d < D - 1; ++d) fetch_rows(d < ns ? d : ns - 1, pro[d]);
+    for (int d = 0; d < D; ++d) fetch_rows(d < ns ? d : ns - 1, pro[d]);
     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-    for (int d = 0; d < D - 1; ++d) tie_rows(pro[d]);
+    for (int d = 0; d < D; ++d) tie_rows(pro[d]);
 #pragma unroll
     for (int d = 0; d < D - 1; ++d)
       if (d < ns) issue(d, pro[d]);
+    rows_cur = pro[D - 1];
   }
   bool live_prev = false;
   for (int s = 0; s < ns; ++s) {
@@ -434,24 +460,27 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
     wait_stage<NPS, D - 2>(newer);
     // everybody's copies of stage s have landed, everybody is done reading stage s-1
     asm volatile("s_barrier" ::: "memory");
-    const int sn = s + D - 1;                              // the stage this iteration issues
-    fetch_rows(sn < ns ? sn : ns - 1, rows_next);
+    // rows of stage s+D: needed by the next iteration, so that the addresses of its copies
+    // can be formed ahead of the wait that completes this fetch
+    fetch_rows(s + D < ns ? s + D : ns - 1, rows_next);
     const uint32_t boff = (uint32_t)((s % D) * STAGE);
     read_step(boff, K0{}, f0);
     if (s > 0 && live_prev) mfma_step(f1);   // second k-step of the previous stage
     const bool live = s * KSPLIT + grp < ns32;   // false only for group 1 on an odd tail
-    wait_lds<NF>(f0);                    // full wait: the index reads above are in as well
+    wait_lds<NF>(f0);                    // full wait: the index fetch above is in as well
     tie_rows(rows_next);
-    // the copies of stage sn go into the buffer of stage s-1, which every wave has finished
-    // reading; when sn opens chunk c >= 1 of the list, chunk c+1 follows it into the half of
-    // the ring whose last reader (stage 8c-1, one iteration ago) is behind this barrier
+    // the copies of stage sn = s+D-1 go into the buffer of stage s-1, which every wave has
+    // finished reading; when sn opens chunk c >= 1 of the list, chunk c+1 follows it into the
+    // half of the ring whose last reader (stage 8c-1, two iterations ago) is behind this barrier
+    const int sn = s + D - 1;
     if (sn < ns) {
-      issue(sn, rows_next);
+      issue(sn, rows_cur);
       if ((sn & 7) == 0 && sn >= 8 && sn + 8 < ns) issue_chunk((sn >> 3) + 1);
     }
     read_step(boff, K16{}, f1);
     if (live) mfma_step(f0);
     live_prev = live;
+    rows_cur = rows_next;
     wait_lds<NF>(f1);
   }
   if (ns > 0 && live_prev) mfma_step(f1);
@@ -643,12 +672,12 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
 }
 
 template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KSPLIT = 1, bool EW = false,
-          bool SPLIT = false>
+          bool SPLIT = false, bool LIDX = true>
 static hipError_t launch(const GemmArgs& g, hipStream_t stream) {
   const int grid = g.n_mtiles * g.n_tiles * (SPLIT ? g.wg_split : 1) + g.n_zero;
   if (grid <= 0) return hipSuccess;
   (void)hipGetLastError();   // an error left behind by an earlier call of this thread is not this launch's
-  hipLaunchKernelGGL((tw_gemm_km_dma_kernel<TM, TN, WAVES_M, D, DENSE, NWAVES, KSPLIT, EW, SPLIT>), dim3(grid),
+  hipLaunchKernelGGL((tw_gemm_km_dma_kernel<TM, TN, WAVES_M, D, DENSE, NWAVES, KSPLIT, EW, SPLIT, LIDX>), dim3(grid),
                      dim3(NWAVES * 64), 0, stream, g);
   return hipGetLastError();
 }
@@ -672,10 +701,18 @@ static hipError_t dispatch_ew(int G, int tm, int variant, GemmArgs& g, hipStream
   return hipErrorInvalidValue;
 }
 
+// Both index routes of an instance (the dense baseline has no kept-row list: one instance).
+template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4>
+static hipError_t launch2(bool lidx, const GemmArgs& g, hipStream_t stream) {
+  if constexpr (DENSE) return launch<TM, TN, WAVES_M, D, true, NWAVES>(g, stream);
+  else if (lidx) return launch<TM, TN, WAVES_M, D, false, NWAVES, 1, false, false, true>(g, stream);
+  else return launch<TM, TN, WAVES_M, D, false, NWAVES, 1, false, false, false>(g, stream);
+}
+
 template <bool DENSE>
-static hipError_t dispatch(int G, int tm, int depth, int variant, GemmArgs& g, hipStream_t stream) {
+static hipError_t dispatch(int G, int tm, int depth, int variant, bool lidx, GemmArgs& g, hipStream_t stream) {
   g.n_mtiles = (g.M + tm - 1) / tm;
-  if (variant == DMA_KSPLIT2) {   // two K-split groups of four waves
+  if (variant == DMA_KSPLIT2) {   // two K-split groups of four waves (kept-row list through LDS)
     if (G == 128 && tm == 128 && depth == 3) return launch<128, 128, 2, 3, DENSE, 8, 2>(g, stream);
     if (G == 128 && tm == 64 && depth == 3) return launch<64, 128, 1, 3, DENSE, 8, 2>(g, stream);
     if (G == 128 && tm == 64 && depth == 4) return launch<64, 128, 1, 4, DENSE, 8, 2>(g, stream);
@@ -683,27 +720,31 @@ static hipError_t dispatch(int G, int tm, int depth, int variant, GemmArgs& g, h
     return hipErrorInvalidValue;
   }
   if (variant == DMA_WAVES8) {    // 512-thread workgroups: 64 x 32 (m x n) per wave
-    if (G == 128 && tm == 128 && depth == 3) return launch<128, 128, 2, 3, DENSE, 8>(g, stream);
-    if (G == 128 && tm == 128 && depth == 4) return launch<128, 128, 2, 4, DENSE, 8>(g, stream);
-    if (G == 128 && tm == 256 && depth == 3) return launch<256, 128, 4, 3, DENSE, 8>(g, stream);
+    if (G == 128 && tm == 128 && depth == 3) return launch2<128, 128, 2, 3, DENSE, 8>(lidx, g, stream);
+    if (G == 128 && tm == 128 && depth == 4) return launch2<128, 128, 2, 4, DENSE, 8>(lidx, g, stream);
+    if (G == 128 && tm == 256 && depth == 3) return launch2<256, 128, 4, 3, DENSE, 8>(lidx, g, stream);
     return hipErrorInvalidValue;
   }
 #define TWG_CASE(TM_, TN_, WM_, D_) \
-  if (G == TN_ && tm == TM_ && depth == D_) return launch<TM_, TN_, WM_, D_, DENSE>(g, stream);
+  if (G == TN_ && tm == TM_ && depth == D_) return launch2<TM_, TN_, WM_, D_, DENSE>(lidx, g, stream);
   TWG_CASE(64, 128, 1, 3) TWG_CASE(128, 128, 2, 3) TWG_CASE(256, 128, 2, 3)
   TWG_CASE(64, 128, 1, 4) TWG_CASE(128, 128, 2, 4) TWG_CASE(256, 128, 2, 4)
   TWG_CASE(128, 64, 2, 3) TWG_CASE(256, 64, 4, 3)
   TWG_CASE(128, 64, 2, 4) TWG_CASE(256, 64, 4, 4)
-  // deep pipelines for launches with about one workgroup per CU: LDS is there to be used
+#undef TWG_CASE
+  // deep pipelines for launches with about one workgroup per CU (kept-row list through LDS)
+#define TWG_CASE(TM_, TN_, WM_, D_) \
+  if (G == TN_ && tm == TM_ && depth == D_) return launch<TM_, TN_, WM_, D_, DENSE>(g, stream);
   TWG_CASE(64, 128, 1, 6) TWG_CASE(128, 128, 2, 6) TWG_CASE(128, 64, 2, 6)
   TWG_CASE(64, 128, 1, 8) TWG_CASE(128, 128, 2, 8) TWG_CASE(128, 64, 2, 8)
 #undef TWG_CASE
   return hipErrorInvalidValue;
 }
 
-hipError_t launch_tw_km_dma(int G, int tm, int depth, int variant, GemmArgs g, hipStream_t stream) {
-  return dispatch<false>(G, tm, depth, variant, g, stream);
+hipError_t launch_tw_km_dma(int G, int tm, int depth, int variant, bool lidx, GemmArgs g, hipStream_t stream) {
+  return dispatch<false>(G, tm, depth, variant, lidx, g, stream);
 }
+
 static __global__ void zero_words(uint32_t* p, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0u;
@@ -723,12 +764,12 @@ hipError_t launch_tw_km_dma_split(int G, int tm, GemmArgs g, hipStream_t stream)
   if (G == 64 && tm == 128) return launch<128, 64, 2, 3, false, 4, 1, false, true>(g, stream);
   return hipErrorInvalidValue;
 }
-hipError_t launch_tew_km_dma(int G, int tm, int depth, int variant, GemmArgs g, hipStream_t stream) {
+hipError_t launch_tew_km_dma(int G, int tm, int depth, int variant, bool, GemmArgs g, hipStream_t stream) {
   if (depth != 3) return hipErrorInvalidValue;
   return dispatch_ew(G, tm, variant, g, stream);
 }
 hipError_t launch_dense_km_dma(int tn, int tm, int depth, int variant, GemmArgs g, hipStream_t stream) {
-  return dispatch<true>(tn, tm, depth, variant, g, stream);
+  return dispatch<true>(tn, tm, depth, variant, true, g, stream);
 }
 
 }  // namespace twg

@@ -79,12 +79,14 @@ hipError_t launch_dense_mk(int tn, GemmArgs g, hipStream_t stream);
 // (tm in {128, 256}, G = 128); DMA_KSPLIT2 = two groups of 4 waves splitting K inside
 // the workgroup (dense: K % 64 == 0).
 enum { DMA_WAVES4 = 0, DMA_WAVES8 = 1, DMA_KSPLIT2 = 2 };
-hipError_t launch_tw_km_dma(int G, int tm, int depth, int variant, GemmArgs g, hipStream_t stream);
+// lidx: kept-row list through LDS (true) or by scalar loads (false; 4-wave and 8-wave instances
+// at depth 3 / 4 have both routes, the others ignore it).
+hipError_t launch_tw_km_dma(int G, int tm, int depth, int variant, bool lidx, GemmArgs g, hipStream_t stream);
 // The same with K split across g.wg_split workgroups per tile (4 waves, 3 stages): (G, tm) in
 // {(128, 128), (128, 64), (64, 128)}.
 hipError_t launch_tw_km_dma_split(int G, int tm, GemmArgs g, hipStream_t stream);
 // The same with the restored elements of a TEW weight added in the epilogue (g.ew_*).
-hipError_t launch_tew_km_dma(int G, int tm, int depth, int variant, GemmArgs g, hipStream_t stream);
+hipError_t launch_tew_km_dma(int G, int tm, int depth, int variant, bool lidx, GemmArgs g, hipStream_t stream);
 hipError_t launch_dense_km_dma(int tn, int tm, int depth, int variant, GemmArgs g, hipStream_t stream);
 // Zero fill of n 32-bit words (the counters of a workspace).
 hipError_t launch_zero_words(uint32_t* p, int n, hipStream_t stream);

@@ -125,6 +125,26 @@ def test_pipeline_depths(depth, tile_m, G, K):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("route", [1, 2])
+@pytest.mark.parametrize("tile_m,waves,G,depth", [(128, 4, 128, 3), (64, 4, 128, 4), (256, 8, 128, 3), (128, 8, 128, 3), (256, 4, 64, 3),
+                                                 (128, 4, 64, 4)])
+def test_both_routes_of_the_kept_row_list(route, tile_m, waves, G, depth):
+    """Scalar loads and the LDS ring give the same bits (same products in the same order); K = 1300
+    sends the list through the ring twice."""
+    rng = np.random.default_rng(tile_m + waves + G + depth)
+    M, K, N = 290, 1300, 200
+    mask = random_tw_mask(rng, K, N, G, col_keep=0.85, row_keep=0.5)
+    A, B = wl.make_A(61, M, K), wl.make_B(61, K, N, 0.1)
+    print(f"case idx_route={route} tile_m={tile_m} waves={waves} G={G} depth={depth}", flush=True)
+    p = tw.tw_pack(B, mask, G, tw.PATTERN_TW)
+    C, raw = _run_ex(p, A, N, tw.tw_launch_opts(tile_m=tile_m, waves=waves, depth=depth, kernel=2, ksplit=1, idx_route=route))
+    C2, raw2 = _run_ex(p, A, N, tw.tw_launch_opts(tile_m=tile_m, waves=waves, depth=depth, kernel=2, ksplit=1, idx_route=3 - route))
+    p.free()
+    assert_C_close(C, og.gemm_oracle(A, B, mask), og.abs_bound(A, B, mask))
+    assert np.array_equal(raw.view(np.uint16)[:, :M], raw2.view(np.uint16)[:, :M])
+
+
+@pytest.mark.gpu
 def test_one_handle_two_threads_different_options_and_geometries():
     """Per-call options and bindings: two host threads launch the same handle at the same time
     with different tile heights (on their own streams), and two convolution geometries bound to
