@@ -190,8 +190,18 @@ tw_status tw_prune_dev_static(const void* B_dev, int K, int N, int ldb, int G, i
                               int n_cols_pruned, int rows_per_tile, uint8_t* mask_dev,
                               uint8_t* tile_mask_dev, void* stream);
 
-/* tw_pack_dev - tw_pack for a weight and masks in device memory: copies them to the
- * host on `stream`, waits for the copies, packs and uploads. */
+/*
+ * tw_pack_dev - tw_pack for a weight and masks in device memory (Algorithm 3's Condense and
+ * Section V's offline condensing, run by kernels on `stream`).  TW and TVW: the kept-column
+ * list, the per-tile kept-row lists, the condensed values, the 2:4 positions and the
+ * kernel-facing image are all produced on the device; only the index lists (a few KB) visit
+ * the host, which lays out offsets, padding and the launch order of the tiles exactly as for
+ * tw_pack.  The result is the same handle bit for bit; its logical values are copied to the
+ * host only when tw_export, tw_unpack or tw_concat ask for them.  TEW goes through the host
+ * packer (the weight and masks are copied to the host).  Allocates device memory and waits
+ * for `stream`: an offline step like tw_pack.  Arguments and errors as tw_pack_host, B with
+ * leading dimension ldb >= N; TW_ERR_HIP for a failed runtime call.
+ */
 tw_status tw_pack_dev(const void* B_dev, int ldb, const uint8_t* mask_dev,
                       const uint8_t* tile_mask_dev, int K, int N, int G, int pattern,
                       void* stream, tw_handle_t* out);

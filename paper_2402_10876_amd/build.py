@@ -15,7 +15,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 LIB = os.path.join(PKG, "libtwgemm.so")
 HASH_FILE = LIB + ".srchash"
-SOURCES = ["api.cpp", "pack.cpp", "gemm_kernels.hip", "gemm_dma.hip", "gemm_tvw.hip", "gemm_i8.hip", "gemm_tvw_i8.hip", "prune.hip", "calibrate.hip"]
+SOURCES = ["api.cpp", "pack.cpp", "gemm_kernels.hip", "gemm_dma.hip", "gemm_tvw.hip", "gemm_i8.hip", "gemm_tvw_i8.hip", "prune.hip", "pack_dev.hip", "calibrate.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed-fp32 instruction selection is switched off for all device code
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -179,20 +179,23 @@ tw_status tw_upload(tw_handle_t h) {
   int dev = -1;
   if (hipGetDevice(&dev) != hipSuccess) return TW_ERR_HIP;
   // one allocation, 256-byte aligned parts
-  struct Part { const void* src; size_t bytes; size_t off; };
+  // (value parts are sized by n_vals / n_meta: a device-packed weight has no host copy of them)
+  struct Part { const void* src; size_t bytes; size_t off; bool copy; };
+  const bool i8 = h->dtype == TW_DTYPE_I8;
+  const bool have_vals = i8 ? !d.vals8.empty() : !d.vals.empty();
   Part parts[10] = {
-      {d.col_idx.data(), d.col_idx.size() * 4, 0},   {d.tile_kp_off.data(), d.tile_kp_off.size() * 4, 0},
-      {d.row_idx.data(), d.row_idx.size() * 4, 0},   {d.zero_cols.data(), d.zero_cols.size() * 4, 0},
-      {d.tile_order.data(), d.tile_order.size() * 4, 0},
-      h->dtype == TW_DTYPE_I8 ? Part{d.vals8.data(), d.vals8.size(), 0} : Part{d.vals.data(), d.vals.size() * 2, 0},
-      {d.meta.data(), d.meta.size() * 4, 0}, {d.tile_sched.data(), d.tile_sched.size() * 4, 0},
-      {d.ew_ptr.data(), d.ew_ptr.size() * 4, 0}, {d.ew_pairs.data(), d.ew_pairs.size() * 4, 0}};
+      {d.col_idx.data(), d.col_idx.size() * 4, 0, true},   {d.tile_kp_off.data(), d.tile_kp_off.size() * 4, 0, true},
+      {d.row_idx.data(), d.row_idx.size() * 4, 0, true},   {d.zero_cols.data(), d.zero_cols.size() * 4, 0, true},
+      {d.tile_order.data(), d.tile_order.size() * 4, 0, true},
+      i8 ? Part{d.vals8.data(), d.n_vals, 0, have_vals} : Part{d.vals.data(), d.n_vals * 2, 0, have_vals},
+      {d.meta.data(), d.n_meta * 4, 0, !d.meta.empty()}, {d.tile_sched.data(), d.tile_sched.size() * 4, 0, true},
+      {d.ew_ptr.data(), d.ew_ptr.size() * 4, 0, true}, {d.ew_pairs.data(), d.ew_pairs.size() * 4, 0, true}};
   size_t total = 0;
   for (auto& p : parts) { p.off = total; total += align_up(p.bytes ? p.bytes : 1, 256); }
   void* blob = nullptr;
   if (hipMalloc(&blob, total) != hipSuccess) { (void)hipGetLastError(); return TW_ERR_ALLOC; }
   for (auto& p : parts) {
-    if (!p.bytes) continue;
+    if (!p.bytes || !p.copy) continue;
     if (hipMemcpy((char*)blob + p.off, p.src, p.bytes, hipMemcpyHostToDevice) != hipSuccess) {
       (void)hipFree(blob);
       return TW_ERR_HIP;
@@ -271,6 +274,7 @@ tw_status tw_prune_dev(const void* B_dev, int K, int N, int ldb, int G, int patt
   if (pattern != TW_PATTERN_TW && pattern != TW_PATTERN_TVW) return TW_ERR_ARG;
   if (((uintptr_t)workspace_dev & 15) || workspace_bytes < twg::prune_workspace_bytes(K, N, G)) return TW_ERR_ARG;
   if (((size_t)K * N + 255) / 256 > 0x7fffffffu) return TW_ERR_UNSUPPORTED;   // one thread per element, grid limit
+  if ((N + G - 1) / G > 65535 || (K + 255) / 256 > 65535 || (N + 255) / 256 > 65535) return TW_ERR_UNSUPPORTED;
   hipError_t e = twg::prune_device((const uint16_t*)B_dev, K, N, ldb, G, pattern == TW_PATTERN_TVW, n_cols_pruned,
                                    rows_per_tile, mask_dev, tile_mask_dev, workspace_dev, (hipStream_t)stream);
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;
@@ -284,6 +288,7 @@ tw_status tw_prune_dev_static(const void* B_dev, int K, int N, int ldb, int G, i
   if (pattern != TW_PATTERN_TW && pattern != TW_PATTERN_TVW) return TW_ERR_ARG;
   if (twg::prune_workspace_bytes(K, N, G) > twg::PRUNE_STATIC_SCRATCH_BYTES) return TW_ERR_TOO_LARGE;
   if (((size_t)K * N + 255) / 256 > 0x7fffffffu) return TW_ERR_TOO_LARGE;
+  if ((N + G - 1) / G > 65535 || (K + 255) / 256 > 65535 || (N + 255) / 256 > 65535) return TW_ERR_TOO_LARGE;
   void* ws = nullptr;
   if (twg::prune_static_scratch(&ws) != hipSuccess) { (void)hipGetLastError(); return TW_ERR_HIP; }
   hipError_t e = twg::prune_device((const uint16_t*)B_dev, K, N, ldb, G, pattern == TW_PATTERN_TVW, n_cols_pruned,
@@ -295,20 +300,30 @@ tw_status tw_pack_dev(const void* B_dev, int ldb, const uint8_t* mask_dev, const
                       int N, int G, int pattern, void* stream, tw_handle_t* out) try {
   if (!out) return TW_ERR_ARG;
   *out = nullptr;
-  if (!B_dev || !mask_dev || K < 1 || N < 1 || ldb < N) return TW_ERR_ARG;
-  std::vector<uint16_t> B((size_t)K * N);
-  std::vector<uint8_t> mask((size_t)K * N), tmask(tile_mask_dev ? (size_t)K * N : 0);
+  if (!B_dev || !mask_dev || K < 1 || N < 1 || ldb < N || !valid_G(G)) return TW_ERR_ARG;
+  if (pattern != TW_PATTERN_TW && pattern != TW_PATTERN_TVW && pattern != TW_PATTERN_TEW) return TW_ERR_ARG;
   hipStream_t s = (hipStream_t)stream;
+  if (pattern != TW_PATTERN_TEW) {       // packed by kernels: only the index lists visit the host
+    tw_handle_s* h = new (std::nothrow) tw_handle_s();
+    if (!h) return TW_ERR_ALLOC;
+    const tw_status st = twg::pack_device((const uint16_t*)B_dev, ldb, mask_dev, tile_mask_dev, K, N, G, pattern, s, h);
+    if (st != TW_OK) { tw_free(h); return st; }
+    *out = h;
+    return TW_OK;
+  }
+  // TEW: through the host packer
+  if (!tile_mask_dev) return TW_ERR_ARG;
+  std::vector<uint16_t> B((size_t)K * N);
+  std::vector<uint8_t> mask((size_t)K * N), tmask((size_t)K * N);
   if (hipMemcpy2DAsync(B.data(), (size_t)N * 2, B_dev, (size_t)ldb * 2, (size_t)N * 2, K, hipMemcpyDeviceToHost, s) !=
           hipSuccess ||
       hipMemcpyAsync(mask.data(), mask_dev, mask.size(), hipMemcpyDeviceToHost, s) != hipSuccess ||
-      (tile_mask_dev &&
-       hipMemcpyAsync(tmask.data(), tile_mask_dev, tmask.size(), hipMemcpyDeviceToHost, s) != hipSuccess) ||
+      hipMemcpyAsync(tmask.data(), tile_mask_dev, tmask.size(), hipMemcpyDeviceToHost, s) != hipSuccess ||
       hipStreamSynchronize(s) != hipSuccess) {
     (void)hipGetLastError();
     return TW_ERR_HIP;
   }
-  return tw_pack(B.data(), mask.data(), tile_mask_dev ? tmask.data() : nullptr, K, N, G, pattern, out);
+  return tw_pack(B.data(), mask.data(), tmask.data(), K, N, G, pattern, out);
 } catch (const std::bad_alloc&) {
   return TW_ERR_ALLOC;
 }
@@ -317,8 +332,11 @@ tw_status tw_concat(const tw_handle_t* parts, int n, int upload, tw_handle_t* ou
   if (!out) return TW_ERR_ARG;
   *out = nullptr;
   if (!parts || n < 1) return TW_ERR_ARG;
-  for (int i = 0; i < n; ++i)
+  for (int i = 0; i < n; ++i) {
     if (!parts[i]) return TW_ERR_ARG;
+    const tw_status sf = twg::fetch_logical_values(parts[i]);   // a device-packed member
+    if (sf != TW_OK) return sf;
+  }
   tw_handle_s* h = new (std::nothrow) tw_handle_s();
   if (!h) return TW_ERR_ALLOC;
   tw_status st = twg::concat_host(parts, n, h);
@@ -663,6 +681,8 @@ tw_status tw_dense_gemm_i8(const void* A, const void* B, void* C, int M, int K, 
 tw_status tw_export(tw_handle_t h, tw_packed_view* out) {
   if (!h || !out) return TW_ERR_ARG;
   std::memset(out, 0, sizeof(*out));
+  const tw_status sf = twg::fetch_logical_values(h);   // device-packed: the values come over now
+  if (sf != TW_OK) return sf;
   out->K = h->K; out->N = h->N; out->G = h->G; out->pattern = h->pattern;
   out->n_kept = h->n_kept; out->n_tiles = h->n_tiles; out->dtype = h->dtype;
   out->col_idx = h->col_idx.data(); out->cto_n = h->cto_n.data();
@@ -681,6 +701,8 @@ tw_status tw_export(tw_handle_t h, tw_packed_view* out) {
 
 tw_status tw_unpack(tw_handle_t h, uint16_t* Bm, uint8_t* mask) {
   if (!h) return TW_ERR_ARG;
+  const tw_status sf = twg::fetch_logical_values(h);
+  if (sf != TW_OK) return sf;
   return twg::unpack_host(h, Bm, mask);
 }
 
@@ -688,6 +710,7 @@ tw_status tw_free(tw_handle_t h) {
   if (!h) return TW_OK;
   tw_status st = TW_OK;
   if (h->img.blob && hipFree(h->img.blob) != hipSuccess) st = TW_ERR_HIP;
+  if (h->dev_logical && hipFree(h->dev_logical) != hipSuccess) st = TW_ERR_HIP;
   delete h;
   return st;
 }

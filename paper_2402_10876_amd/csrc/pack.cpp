@@ -68,35 +68,18 @@ bool is_tile_wise(const uint8_t* S, int K, int N, int G, const std::vector<int32
 
 }  // namespace
 
-tw_status pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_mask, int K,
-                    int N, int G, int pattern, tw_handle_s* h) try {
-  h->K = K; h->N = N; h->G = G; h->pattern = pattern;
-  const bool tvw = pattern == TW_PATTERN_TVW, tew = pattern == TW_PATTERN_TEW;
-  const uint8_t* S = ((tvw || tew) && tile_mask) ? tile_mask : mask;
-  structure_of(S, K, N, G, h->col_idx, h->tile_k_off, h->row_idx);
+// Tiles of G over the kept columns (Algorithm 3: Condense, then split by (1,G)).
+void set_tiles_of_G(tw_handle_s* h) {
   h->n_kept = (int32_t)h->col_idx.size();
   h->n_tiles = (int32_t)h->tile_k_off.size() - 1;
   h->tile_col_off.resize(h->n_tiles + 1);
-  for (int t = 0; t <= h->n_tiles; ++t) h->tile_col_off[t] = std::min(t * G, h->n_kept);
-  if (!tvw || tile_mask) {
-    if (!is_tile_wise(S, K, N, G, h->col_idx, h->tile_k_off)) return TW_ERR_MASK;
-  }
-  if (tvw && tile_mask) {
-    for (size_t i = 0, e = (size_t)K * N; i < e; ++i)
-      if (mask[i] && !tile_mask[i]) return TW_ERR_MASK;
-  }
-  if (tew) {   // the restored elements: in the mask, not in the tile mask; column by column
-    for (size_t i = 0, e = (size_t)K * N; i < e; ++i)
-      if (tile_mask[i] && !mask[i]) return TW_ERR_MASK;
-    h->ew_col_ptr.assign(N + 1, 0);
-    for (int n = 0; n < N; ++n) {
-      for (int k = 0; k < K; ++k) {
-        const size_t i = (size_t)k * N + n;
-        if (mask[i] && !tile_mask[i]) { h->ew_row.push_back(k); h->ew_val.push_back(B[i]); }
-      }
-      h->ew_col_ptr[n + 1] = (int32_t)h->ew_row.size();
-    }
-  }
+  for (int t = 0; t <= h->n_tiles; ++t) h->tile_col_off[t] = std::min(t * h->G, h->n_kept);
+}
+
+// Everything that follows from the index lists alone: offsets (index minus position, Section V),
+// where each tile's values and 2:4 bytes start, the condensed work.
+void finish_lists(tw_handle_s* h) {
+  const bool tvw = h->pattern == TW_PATTERN_TVW;
   h->cto_n.resize(h->n_kept);
   for (int j = 0; j < h->n_kept; ++j) h->cto_n[j] = h->col_idx[j] - j;
   h->cto_k.resize(h->row_idx.size());
@@ -117,13 +100,40 @@ tw_status pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_
       h->meta_off[t + 1] = h->meta_off[t] + (int64_t)ng * w;
     }
   }
-  {
-    std::vector<uint8_t> used(K, 0);
-    for (int32_t r : h->row_idx) used[r] = 1;
-    for (int32_t r : h->ew_row) used[r] = 1;
-    h->k_union = 0;
-    for (int k = 0; k < K; ++k) h->k_union += used[k];
+  std::vector<uint8_t> used(h->K, 0);
+  for (int32_t r : h->row_idx) used[r] = 1;
+  for (int32_t r : h->ew_row) used[r] = 1;
+  h->k_union = 0;
+  for (int k = 0; k < h->K; ++k) h->k_union += used[k];
+}
+
+tw_status pack_host(const uint16_t* B, const uint8_t* mask, const uint8_t* tile_mask, int K,
+                    int N, int G, int pattern, tw_handle_s* h) try {
+  h->K = K; h->N = N; h->G = G; h->pattern = pattern;
+  const bool tvw = pattern == TW_PATTERN_TVW, tew = pattern == TW_PATTERN_TEW;
+  const uint8_t* S = ((tvw || tew) && tile_mask) ? tile_mask : mask;
+  structure_of(S, K, N, G, h->col_idx, h->tile_k_off, h->row_idx);
+  set_tiles_of_G(h);
+  if (!tvw || tile_mask) {
+    if (!is_tile_wise(S, K, N, G, h->col_idx, h->tile_k_off)) return TW_ERR_MASK;
   }
+  if (tvw && tile_mask) {
+    for (size_t i = 0, e = (size_t)K * N; i < e; ++i)
+      if (mask[i] && !tile_mask[i]) return TW_ERR_MASK;
+  }
+  if (tew) {   // the restored elements: in the mask, not in the tile mask; column by column
+    for (size_t i = 0, e = (size_t)K * N; i < e; ++i)
+      if (tile_mask[i] && !mask[i]) return TW_ERR_MASK;
+    h->ew_col_ptr.assign(N + 1, 0);
+    for (int n = 0; n < N; ++n) {
+      for (int k = 0; k < K; ++k) {
+        const size_t i = (size_t)k * N + n;
+        if (mask[i] && !tile_mask[i]) { h->ew_row.push_back(k); h->ew_val.push_back(B[i]); }
+      }
+      h->ew_col_ptr[n + 1] = (int32_t)h->ew_row.size();
+    }
+  }
+  finish_lists(h);
   h->values.assign((size_t)h->val_off[h->n_tiles], 0);
   if (!tvw) {
     for (int t = 0; t < h->n_tiles; ++t) {
@@ -285,6 +295,12 @@ tw_status concat_host(const tw_handle_s* const* parts, int n, tw_handle_s* h) tr
 //      16-bit half selected by its ABID field, 2 bits per stored element).
 // ---------------------------------------------------------------------------
 void build_device_image(tw_handle_s* h) {
+  build_device_lists(h);
+  build_device_values(h);
+}
+
+// The integer parts of the device image: they follow from the logical lists alone.
+void build_device_lists(tw_handle_s* h) {
   DeviceImage& d = h->img;
   const int G = h->G, nt = h->n_tiles;
   const bool tvw = h->pattern == TW_PATTERN_TVW;
@@ -338,6 +354,20 @@ void build_device_image(tw_handle_s* h) {
     d.tile_sched[4 * pos + 2] = d.tile_kp_off[t + 1] - d.tile_kp_off[t];
     d.tile_sched[4 * pos + 3] = h->tile_col_off[t + 1] - h->tile_col_off[t];
   }
+  // sizes of the value parts (elements), so that a device image can be allocated before its
+  // values exist (device-side packing)
+  if (i8) { d.n_vals = tvw ? (size_t)d.tile_kp_off[nt] / 2 * G : ((size_t)d.tile_kp_off[nt] + KSTEP_I8) * G; }
+  else d.n_vals = tvw ? (size_t)d.tile_kp_off[nt] / 2 * G : ((size_t)d.tile_kp_off[nt] + KSTEP_TW) * G;
+  d.n_meta = !tvw ? 0 : i8 ? (size_t)d.tile_kp_off[nt] / 64 * (G / 32) * 64
+                           : (size_t)d.tile_kp_off[nt] / KSTEP_TVW * (G / 32) * 64;
+}
+
+// The value parts of the device image, from the logical values (layouts above).
+void build_device_values(tw_handle_s* h) {
+  DeviceImage& d = h->img;
+  const int G = h->G, nt = h->n_tiles;
+  const bool tvw = h->pattern == TW_PATTERN_TVW;
+  const bool i8 = h->dtype == TW_DTYPE_I8;
   if (i8 && tvw) {
     // int8 TVW, register order of v_smfmac_i32_32x32x64_i8's sparse operand: for K-stage s
     // (128 condensed rows), half u (64 rows = 16 groups of 4), column block nb and lane l:

@@ -8,6 +8,8 @@
 
 #include "twgemm.h"
 
+typedef struct ihipStream_t* hipStream_t;   // as the HIP runtime declares it (this header is also built without HIP)
+
 namespace twg {
 
 // K-step the device image is padded to.  One main-loop stage of the TW kernel
@@ -32,6 +34,7 @@ struct DeviceImage {
   std::vector<uint32_t> meta;        // TVW: swizzled 2-bit position words
   std::vector<int32_t> ew_ptr;       // TEW: N+1 offsets into ew_pairs, by original column
   std::vector<uint32_t> ew_pairs;    // TEW: restored elements, row << 16 | fp16 bits
+  size_t n_vals = 0, n_meta = 0;     // elements of the value / position-word parts (set with the lists)
   // device copies (one allocation, sub-pointers)
   void* blob = nullptr;
   size_t blob_bytes = 0;
@@ -64,6 +67,12 @@ struct tw_handle_s {
   int32_t k_union = 0;  // K rows kept by at least one tile
   int32_t max_kp = 0;  // largest padded K_t
   twg::DeviceImage img;
+  // device-side packing (tw_pack_dev): the logical values / 2:4 bytes live in this device
+  // allocation (values first, then meta and valid at the offsets below) until somebody asks for
+  // them on the host
+  void* dev_logical = nullptr;
+  size_t dev_logical_meta_off = 0, dev_logical_valid_off = 0;
+  bool host_values_ready = true;     // false: `values` / `meta` / `valid` still have to be fetched
 };
 
 namespace twg {
@@ -75,6 +84,18 @@ tw_status unpack_host(const tw_handle_s* h, uint16_t* Bm, uint8_t* mask);
 tw_status concat_host(const tw_handle_s* const* parts, int n, tw_handle_s* h);
 // Launch order of the tiles, read when a device image is built: 1 = longest K_t first.
 extern std::atomic<int> longest_first;
-// Builds h->img host staging from the logical form.
+// Builds h->img host staging from the logical form: the integer parts (from the lists alone),
+// the value parts, or both.
 void build_device_image(tw_handle_s* h);
+void build_device_lists(tw_handle_s* h);
+void build_device_values(tw_handle_s* h);
+// From h->col_idx / tile_k_off / row_idx: tiles of G over the kept columns; then offsets,
+// value offsets and the condensed work.
+void set_tiles_of_G(tw_handle_s* h);
+void finish_lists(tw_handle_s* h);
+// Device-side packer (pack_dev.hip): fills *h from device buffers, image included (fp16, TW / TVW).
+tw_status pack_device(const uint16_t* B, int ldb, const uint8_t* mask, const uint8_t* tile_mask, int K, int N,
+                      int G, int pattern, hipStream_t stream, tw_handle_s* h);
+// Copies the logical values of a device-packed handle to the host if they are not there yet.
+tw_status fetch_logical_values(tw_handle_s* h);
 }  // namespace twg

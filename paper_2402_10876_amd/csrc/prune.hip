@@ -17,6 +17,7 @@
 #include <mutex>
 
 #include "prune.h"
+#include "scan.h"
 
 namespace twg {
 
@@ -36,57 +37,56 @@ __device__ __forceinline__ bool before(u128 sa, int ia, u128 sb, int ib) {   // 
   return sa < sb || (sa == sb && ia < ib);
 }
 
-// TW-C scores: one thread per column, rows in order (coalesced across the threads).
-__global__ void column_scores(const uint16_t* B, int K, int N, int ldb, u128* score) {
+// TW-C scores: thread (column, slice of rows); the squares of a slice are summed in a 128-bit
+// register and added to the column's score as three 32-bit limbs, each in a 64-bit word of its
+// own (2^32 limbs fit before a word overflows), so that plain 64-bit atomics keep the sum exact
+// and independent of the order; column_score_finish carries the limbs into one 128-bit integer.
+__global__ void column_scores(const uint16_t* B, int K, int N, int ldb, unsigned long long* limbs) {
   const int n = blockIdx.x * blockDim.x + threadIdx.x;
   if (n >= N) return;
   u128 s = 0;
-  for (int k = 0; k < K; ++k) s += square48(B[(size_t)k * ldb + n]);
-  score[n] = s;
+  for (int k = blockIdx.y; k < K; k += gridDim.y) s += square48(B[(size_t)k * ldb + n]);
+  atomicAdd(limbs + 3 * (size_t)n + 0, (unsigned long long)(uint32_t)s);
+  atomicAdd(limbs + 3 * (size_t)n + 1, (unsigned long long)(uint32_t)(s >> 32));
+  atomicAdd(limbs + 3 * (size_t)n + 2, (unsigned long long)(s >> 64));
+}
+__global__ void column_score_finish(const unsigned long long* limbs, int N, u128* score) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N) return;
+  score[n] = (u128)limbs[3 * (size_t)n] + ((u128)limbs[3 * (size_t)n + 1] << 32) + ((u128)limbs[3 * (size_t)n + 2] << 64);
 }
 
-// keep[i] = 1 unless i is among the `n_pruned` lowest of its segment by (score, index).
-// grid.y = segment (one for the columns, one per tile for the rows), segment length `len`.
-__global__ void keep_all_but_lowest(const u128* score, int len, int n_pruned, int32_t* keep) {
-  const u128* s = score + (size_t)blockIdx.y * len;
+// Rank by counting, in parts: workgroup (x, y, z) compares entries [256 x, +256) of segment z
+// with entries [256 y, +256) of the same segment (staged in LDS; all lanes read the same LDS
+// address, a broadcast) and adds the number that come before in (score, index) order to
+// rank[i].  grid.z = segment (one for the columns, one per tile for the rows).
+__global__ void rank_partial(const u128* score, int len, int32_t* rank) {
+  constexpr int CHUNK = 256;
+  __shared__ u128 chunk[CHUNK];
+  const u128* s = score + (size_t)blockIdx.z * len;
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  const int c0 = blockIdx.y * CHUNK, cn = min(CHUNK, len - c0);
+  if ((int)threadIdx.x < cn) chunk[threadIdx.x] = s[c0 + threadIdx.x];
+  __syncthreads();
   if (i >= len) return;
   const u128 mine = s[i];
-  int rank = 0;
-  for (int j = 0; j < len; ++j) rank += before(s[j], j, mine, i);
-  keep[(size_t)blockIdx.y * len + i] = rank >= n_pruned;
+  int r = 0;
+  for (int j = 0; j < cn; ++j) r += before(chunk[j], c0 + j, mine, i);
+  if (r) atomicAdd(rank + (size_t)blockIdx.z * len + i, r);
+}
+// keep[i] = 1 unless i is among the `n_pruned` lowest of its segment (in place: rank -> keep).
+__global__ void keep_from_rank(int32_t* rank_keep, size_t n, int n_pruned) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) rank_keep[i] = rank_keep[i] >= n_pruned;
+}
+__global__ void zero_i32(int32_t* p, size_t n) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0;
 }
 
-// Condense: positions of the kept entries of each segment, in ascending order.
-// One workgroup per segment; pos[i] = index among the kept (or -1), list[pos] = i.
-__global__ void compact(const int32_t* keep, int len, int32_t* pos, int32_t* list) {
-  __shared__ int part[1024];
-  __shared__ int base;
-  const int32_t* kp = keep + (size_t)blockIdx.x * len;
-  int32_t* ps = pos + (size_t)blockIdx.x * len;
-  int32_t* ls = list + (size_t)blockIdx.x * len;
-  if (threadIdx.x == 0) base = 0;
-  __syncthreads();
-  for (int c0 = 0; c0 < len; c0 += (int)blockDim.x) {
-    const int i = c0 + threadIdx.x;
-    const int v = i < len ? kp[i] : 0;
-    part[threadIdx.x] = v;
-    __syncthreads();
-    for (int d = 1; d < (int)blockDim.x; d <<= 1) {          // inclusive scan
-      const int add = (int)threadIdx.x >= d ? part[threadIdx.x - d] : 0;
-      __syncthreads();
-      part[threadIdx.x] += add;
-      __syncthreads();
-    }
-    if (i < len) {
-      const int p = base + part[threadIdx.x] - v;
-      ps[i] = v ? p : -1;
-      if (v) ls[p] = i;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) base += part[blockDim.x - 1];
-    __syncthreads();
-  }
+__global__ void zero_u64(unsigned long long* p, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = 0ull;
 }
 
 // TW-R scores: tile t = kept columns [t*G, min((t+1)*G, n_kept)); one thread per (tile, row).
@@ -137,7 +137,8 @@ size_t align_up(size_t x) { return (x + 255) / 256 * 256; }
 size_t prune_workspace_bytes(int K, int N, int G) {
   const size_t nt = (size_t)(N + G - 1) / G;
   return align_up((size_t)N * 16) + 3 * align_up((size_t)N * 4) +          // column score, keep, pos, list
-         align_up(nt * K * 16) + 3 * align_up(nt * K * 4);                  // row score, keep, pos, list
+         align_up(nt * K * 16) + 3 * align_up(nt * K * 4) +                 // row score, keep, pos, list
+         align_up((size_t)N * 24);                                          // column score limbs
 }
 
 hipError_t prune_device(const uint16_t* B, int K, int N, int ldb, int G, bool tvw, int n_cols_pruned,
@@ -154,7 +155,8 @@ hipError_t prune_device(const uint16_t* B, int K, int N, int ldb, int G, bool tv
   u128* row_score = (u128*)w;            w += align_up(ntmax * K * 16);
   int32_t* row_keep = (int32_t*)w;       w += align_up(ntmax * K * 4);
   int32_t* row_pos = (int32_t*)w;        w += align_up(ntmax * K * 4);
-  int32_t* row_list = (int32_t*)w;
+  int32_t* row_list = (int32_t*)w;       w += align_up(ntmax * K * 4);
+  unsigned long long* col_limbs = (unsigned long long*)w;
   const int T = 256;
   (void)hipGetLastError();   // an error left behind by an earlier call of this thread is not this call's
   // a failed launch ends the call: later kernels would read workspace nobody wrote
@@ -164,12 +166,22 @@ hipError_t prune_device(const uint16_t* B, int K, int N, int ldb, int G, bool tv
     const hipError_t e_ = hipGetLastError();                                  \
     if (e_ != hipSuccess) return e_;                                          \
   } while (0)
-  TWG_LAUNCH(column_scores, dim3((N + T - 1) / T), dim3(T), B, K, N, ldb, col_score);
-  TWG_LAUNCH(keep_all_but_lowest, dim3((N + T - 1) / T, 1), dim3(T), col_score, N, n_cols_pruned, col_keep);
+  // zeroed by a kernel, not a memset node: the caller may be capturing a graph
+  TWG_LAUNCH(zero_u64, dim3((3 * N + T - 1) / T), dim3(T), col_limbs, 3 * N);
+  const int ky = K < 128 ? K : 128;      // row slices: 128 x N/256 workgroups
+  TWG_LAUNCH(column_scores, dim3((N + T - 1) / T, ky), dim3(T), B, K, N, ldb, col_limbs);
+  TWG_LAUNCH(column_score_finish, dim3((N + T - 1) / T), dim3(T), col_limbs, N, col_score);
+  const unsigned nb = (unsigned)((N + T - 1) / T);
+  TWG_LAUNCH(zero_i32, dim3(nb), dim3(T), col_keep, (size_t)N);
+  TWG_LAUNCH(rank_partial, dim3(nb, nb, 1), dim3(T), col_score, N, col_keep);
+  TWG_LAUNCH(keep_from_rank, dim3(nb), dim3(T), col_keep, (size_t)N, n_cols_pruned);
   TWG_LAUNCH(compact, dim3(1), dim3(1024), col_keep, N, col_pos, kept_cols);
   if (nt > 0) {
     TWG_LAUNCH(tile_row_scores, dim3((K + T - 1) / T, nt), dim3(T), B, K, ldb, G, n_kept, kept_cols, row_score);
-    TWG_LAUNCH(keep_all_but_lowest, dim3((K + T - 1) / T, nt), dim3(T), row_score, K, K - rows_per_tile, row_keep);
+    const unsigned kb = (unsigned)((K + T - 1) / T), all = (unsigned)(((size_t)nt * K + T - 1) / T);
+    TWG_LAUNCH(zero_i32, dim3(all), dim3(T), row_keep, (size_t)nt * K);
+    TWG_LAUNCH(rank_partial, dim3(kb, kb, nt), dim3(T), row_score, K, row_keep);
+    TWG_LAUNCH(keep_from_rank, dim3(all), dim3(T), row_keep, (size_t)nt * K, K - rows_per_tile);
   }
   const size_t total = (size_t)K * N;
   const unsigned eb = (unsigned)((total + T - 1) / T);      // the caller keeps K * N / 256 inside the grid limit
