@@ -359,7 +359,7 @@ static tw_status gemm_launch(const Opts& o, const void* A, int M, int lda, int l
     g.conv_P = conv->geom.P; g.conv_L = conv->geom.L; g.conv_H = conv->geom.H; g.conv_W = conv->geom.W;
   }
   g.col_idx = h->img.d_col_idx; g.tile_order = h->img.d_tile_order;
-  g.tile_sched = h->img.d_tile_sched;
+  g.tile_sched = h->img.d_tile_sched; g.uniform_kp = h->img.uniform_kp;
   g.zero_cols = h->img.d_zero_cols; g.n_zero = (int)h->img.zero_cols.size();
   g.meta = h->img.d_meta;
   g.ew_ptr = h->img.d_ew_ptr; g.ew_pairs = h->img.d_ew_pairs;
@@ -603,6 +603,7 @@ static tw_status gemm_i8_launch(const void* A, int M, int lda, tw_handle_t h, vo
   g.c_i8 = c_dtype; g.scale = scale;
   g.vals = (const int8_t*)h->img.d_vals;
   g.row_idx = h->img.d_row_idx; g.col_idx = h->img.d_col_idx; g.tile_sched = h->img.d_tile_sched;
+  g.uniform_kp = h->img.uniform_kp;
   if (conv) {
     g.row_idx = conv->d_off;
     g.conv_P = conv->geom.P; g.conv_L = conv->geom.L; g.conv_H = conv->geom.H; g.conv_W = conv->geom.W;

@@ -255,8 +255,13 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
   int kp0, ns32;                                       // ns32: stages of 32 rows
   if constexpr (DENSE) { kp0 = 0; ns32 = g.K / KS; }   // host guarantees K % (32 KSPLIT) == 0
   else {
-    const int4v rec = scalar_load4(g.tile_sched + 4 * t);
-    t = rec[0]; kp0 = rec[1]; ns32 = rec[2] / KS;
+    // equal tiles in column order (the usual per-tile pruning recipe): the record follows from
+    // the launch position, which saves the first of the kernel's dependent round trips
+    if (g.uniform_kp > 0) { kp0 = t * g.uniform_kp; ns32 = g.uniform_kp / KS; }
+    else {
+      const int4v rec = scalar_load4(g.tile_sched + 4 * t);
+      t = rec[0]; kp0 = rec[1]; ns32 = rec[2] / KS;
+    }
   }
   if constexpr (SPLIT) {                               // this workgroup's share of the stages
     const int first = ns32 * split / S, last = ns32 * (split + 1) / S;

@@ -137,8 +137,11 @@ __global__ __launch_bounds__(NWAVES * 64, (TM * TN >= 256 * 128) ? 2 : 1) void t
   int kp0, ns64;                         // ns64: stages of 64 rows
   if constexpr (DENSE) { kp0 = 0; ns64 = g.K / KS8; }  // host guarantees K % 64 == 0
   else {
-    const int4v rec = scalar_load4(g.tile_sched + 4 * t);
-    t = rec[0]; kp0 = rec[1]; ns64 = rec[2] / KS8;
+    if (g.uniform_kp > 0) { kp0 = t * g.uniform_kp; ns64 = g.uniform_kp / KS8; }   // equal tiles in column order
+    else {
+      const int4v rec = scalar_load4(g.tile_sched + 4 * t);
+      t = rec[0]; kp0 = rec[1]; ns64 = rec[2] / KS8;
+    }
   }
   const int ns = (ns64 + KSPLIT - 1) / KSPLIT;         // pipeline stages of KSS rows
   const int8_t* Bt = DENSE ? g.vals + (size_t)t * TN : g.vals + (size_t)kp0 * TN;

@@ -114,8 +114,12 @@ __global__ __launch_bounds__(256) void tvw_gemm_i8_kernel(GemmI8Args g) {
   }
   int mt, pos;
   tile_of_workgroup(g, blockIdx.x, n_gemm, mt, pos);
-  const int4v rec = scalar_load4(g.tile_sched + 4 * pos);
-  const int t = rec[0], kp0 = rec[1], ns = rec[2] / KSV;
+  int t, kp0, ns;
+  if (g.uniform_kp > 0) { t = pos; kp0 = pos * g.uniform_kp; ns = g.uniform_kp / KSV; }   // equal tiles in column order
+  else {
+    const int4v rec = scalar_load4(g.tile_sched + 4 * pos);
+    t = rec[0]; kp0 = rec[1]; ns = rec[2] / KSV;
+  }
   const int m0 = mt * TM;
   // this tile's compressed values (kp0/2 rows x TN bytes) and position words
   const char* Vt = (const char*)g.vals + (size_t)kp0 / 2 * TN;

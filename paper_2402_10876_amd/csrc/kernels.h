@@ -17,6 +17,8 @@ struct GemmArgs {
   const int32_t* col_idx;        // TW: n_tiles*G kept-column indices, -1 = none (CTO_n)
   const int32_t* tile_order;     // TW: launch order of tiles (longest first) or null
   const int32_t* tile_sched;     // TW: per launch position {tile, kp offset, Kp_t, width}, 16-byte records
+  int uniform_kp;                // > 0: every tile has this padded K_t and launch position = tile, so the
+                                 // record is (pos, pos * uniform_kp, uniform_kp) and need not be loaded
   const int32_t* zero_cols;      // pruned columns of C, written as +0
   const uint32_t* meta;          // TVW: 2:4 position words
   const int32_t* ew_ptr;         // TEW: N+1 offsets into ew_pairs by original column of C
@@ -50,6 +52,7 @@ struct GemmI8Args {
   const int32_t* row_idx;
   const int32_t* col_idx;
   const int32_t* tile_sched;
+  int uniform_kp;                // as in GemmArgs
   const int32_t* zero_cols;
   const uint32_t* meta;          // TVW: 2:4 position words
   int n_zero;

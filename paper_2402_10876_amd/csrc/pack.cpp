@@ -354,6 +354,12 @@ void build_device_lists(tw_handle_s* h) {
     d.tile_sched[4 * pos + 2] = d.tile_kp_off[t + 1] - d.tile_kp_off[t];
     d.tile_sched[4 * pos + 3] = h->tile_col_off[t + 1] - h->tile_col_off[t];
   }
+  // equal tiles launched in column order: the kernels can form the record from the position
+  d.uniform_kp = nt > 0 ? d.tile_sched[2] : 0;
+  for (int pos = 0; pos < nt && d.uniform_kp; ++pos)
+    if (d.tile_sched[4 * pos] != pos || d.tile_sched[4 * pos + 2] != d.uniform_kp ||
+        d.tile_sched[4 * pos + 1] != pos * d.uniform_kp)
+      d.uniform_kp = 0;
   // sizes of the value parts (elements), so that a device image can be allocated before its
   // values exist (device-side packing)
   if (i8) { d.n_vals = tvw ? (size_t)d.tile_kp_off[nt] / 2 * G : ((size_t)d.tile_kp_off[nt] + KSTEP_I8) * G; }

@@ -34,6 +34,7 @@ struct DeviceImage {
   std::vector<uint32_t> meta;        // TVW: swizzled 2-bit position words
   std::vector<int32_t> ew_ptr;       // TEW: N+1 offsets into ew_pairs, by original column
   std::vector<uint32_t> ew_pairs;    // TEW: restored elements, row << 16 | fp16 bits
+  int32_t uniform_kp = 0;            // > 0: all tiles have this padded K_t and are launched in column order
   size_t n_vals = 0, n_meta = 0;     // elements of the value / position-word parts (set with the lists)
   // device copies (one allocation, sub-pointers)
   void* blob = nullptr;
