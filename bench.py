@@ -26,6 +26,8 @@ Prints ONE JSON line: dense-equivalent TFLOP/s of the whole step, plus
                 BERT-large FFN sparsity sweep, the VGG-16 im2col GEMMs): time, our dense
                 kernel's time, binding roof and the fraction of it (outside the timed region);
   cpu_baseline  the fp64 oracle timed on the host cores.
+`--extra cube,imbalance,tew,i8,conv` adds opt-in sweeps (the 4096^3 sparsity sweep, uneven
+tiles, TEW, int8, convolutions without a materialised img2col matrix) under `extra`.
 `--calibrate` runs the calibration kernels alone (the command the rocprofv3 summary in
 profiles/ was taken with).
 """
@@ -95,6 +97,15 @@ def calibration(tw, torch, dev, stream, quick=False):
     out["read_GBps"] = timed(tw.CAL_READ, nbytes) / 1e9
     out["write_GBps"] = timed(tw.CAL_WRITE, nbytes) / 1e9
     out["store_ct_25MB_GBps"] = timed(tw.CAL_STORE_CT, 3072 * 4096 * 2, reps=10) / 1e9
+    # What one launch costs before and after it moves any data: zero fills in the epilogue's
+    # pattern at four sizes; time = fixed + bytes / rate by least squares.
+    sizes = [768 * 4096 * 2, 3072 * 4096 * 2, 4 * 3072 * 4096 * 2, 8 * 3072 * 4096 * 2]
+    us = [s / timed(tw.CAL_STORE_CT, s, reps=10) * 1e6 for s in sizes]          # units == bytes written
+    A = np.vstack([np.ones(len(sizes)), np.array(sizes, dtype=np.float64)]).T
+    fixed_us, us_per_byte = np.linalg.lstsq(A, np.array(us), rcond=None)[0]
+    out["store_ct_us_by_MB"] = {f"{s / 1e6:.1f}": round(t, 2) for s, t in zip(sizes, us)}
+    out["launch_fixed_us"] = float(fixed_us)
+    out["store_ct_fit_GBps"] = float(1e-3 / us_per_byte)
     iters = 2000 if quick else 8000
     out["mfma_f16_TFLOPs"] = timed(tw.CAL_MFMA_F16, nbytes, iters) / 1e12
     out["smfmac_f16_dense_eq_TFLOPs"] = timed(tw.CAL_SMFMAC_F16, nbytes, iters) / 1e12
@@ -106,8 +117,9 @@ def calibration(tw, torch, dev, stream, quick=False):
     return out
 
 
-def extra_rows(tw, wl, torch, dev, stream, skip_cfg, reps=24, sets=6):
-    """One row per other configured workload (launch configuration as the heuristics pick it)."""
+def extra_rows(tw, wl, torch, dev, stream, skip_cfg, reps=24, sets=24):
+    """One row per other configured workload (launch configuration as the heuristics pick it),
+    timed on enough rotating buffer sets (about 600 MB) that operands come from HBM."""
     def timed(fn, rounds=3):
         vals = []
         for _ in range(rounds):
@@ -175,6 +187,179 @@ def extra_rows(tw, wl, torch, dev, stream, skip_cfg, reps=24, sets=6):
     return rows
 
 
+def extra_sweeps(tw, wl, torch, dev, stream, which, reps=24, sets=6):
+    """Opt-in measurements beyond the configured workloads (`--extra cube,imbalance,tew,i8,conv`):
+    the 4096^3 sparsity sweep of Section VI-B (TVW at 50 % is plain 2:4), uneven tiles from one
+    magnitude threshold over all tile rows (Section V "load imbalance") launched longest first
+    and in column order, TEW at 75 % with delta restored elements (Section VI, impact of delta),
+    int8 TW / TVW against the dense int8 kernel and the fp16 launch of the same mask (Section
+    VI-B), and config 5's convolutions on the wide input against the materialised matrix."""
+    def timed(fn, rounds=3):
+        vals = []
+        for _ in range(rounds):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for r in range(reps):
+                fn(r)
+            e1.record()
+            torch.cuda.synchronize()
+            vals.append(e0.elapsed_time(e1) / reps * 1e-3)
+        return float(np.median(vals))
+    out = {}
+    wl.SHAPES[6] = [wl.Shape("cube_4096", 4096, 4096, 4096, 0.02)]
+    wl.CONFIGS[6] = dict(G=128, pattern="tw", sparsity=0.75, col_frac=0.10)
+
+    def gemm_rows(plan):
+        rows, dense = [], {}
+        for entry in plan:
+            cfg, si, pattern, sp, G = entry[:5]
+            delta = entry[5] if len(entry) > 5 else 0.0
+            shp = wl.SHAPES[cfg][si]
+            M, K, N = shp.M, shp.K, shp.N
+            nsets = max(2, min(sets, int(600e6 // (2 * M * (K + N)))))
+            cf = 0.0 if sp == 0.0 or (pattern == "tvw" and sp == 0.5) else None
+            c = wl.make_case(cfg, si, pattern=pattern, sparsity=sp, G=G, col_frac=cf, with_A=False, delta=delta)
+            pat = {"tw": tw.PATTERN_TW, "tvw": tw.PATTERN_TVW, "tew": tw.PATTERN_TEW}[pattern]
+            packed = [tw.tw_pack(c.B, c.mask, G, pat, tile_mask=c.tile_mask if pattern != "tw" else None)
+                      for _ in range(nsets)]
+            A = [torch.randn((K, M), dtype=torch.float16, device=dev) for _ in range(nsets)]
+            C = [torch.empty((N, M), dtype=torch.float16, device=dev) for _ in range(nsets)]
+            skw, sk, ku = packed[0].flop_counts()
+            t = timed(lambda r: tw.tw_gemm(A[r % nsets].data_ptr(), M, M, tw.LAYOUT_KM, packed[r % nsets],
+                                           C[r % nsets].data_ptr(), M, stream))
+            if (cfg, si) not in dense:
+                Bd = torch.from_numpy(c.B).to(dev)
+                dense[(cfg, si)] = timed(lambda r: tw.tw_dense_gemm(A[r % nsets].data_ptr(), Bd.data_ptr(),
+                                                                    C[r % nsets].data_ptr(), M, K, N, M, N, M,
+                                                                    tw.LAYOUT_KM, stream))
+            td = dense[(cfg, si)]
+            nnz_ew = int(c.mask.sum() - c.tile_mask.sum()) if pattern == "tew" else 0
+            ab = algorithmic_bytes(M, ku, N, "tvw" if pattern == "tvw" else "tw", skw, sk) + 4 * nnz_ew
+            bound, frac = roof(ab, issued_flops(M, skw, pattern), t)
+            row = dict(shape=shp.name, M=M, K=K, N=N, G=G, pattern=pattern, sparsity=sp, us=round(t * 1e6, 2),
+                       dense_us=round(td * 1e6, 2), speedup_vs_dense=round(td / t, 3),
+                       dense_eq_tflops=round(2.0 * M * K * N / t / 1e12, 1), bound=bound, frac=round(frac, 4))
+            if pattern == "tew":
+                row.update(delta=delta, restored=nnz_ew)
+            rows.append(row)
+            for p in packed:
+                p.free()
+        return rows
+
+    if "cube" in which:
+        plan = [(6, 0, "tw", sp, G) for sp in (0.0, 0.1, 0.25, 0.5, 0.75, 0.875) for G in (128, 64)]
+        plan += [(6, 0, "tvw", sp, 128) for sp in (0.5, 0.75, 0.875)]
+        out["cube"] = gemm_rows(plan)
+    if "tew" in which:
+        out["tew"] = gemm_rows([(cfg, si, "tew", 0.75, 128, delta) for cfg, si in ((2, 0), (2, 1), (2, 2), (4, 0), (4, 1))
+                                for delta in (0.005, 0.015, 0.05)])
+    if "imbalance" in which:
+        rows = []
+        for cfg, si in ((4, 0), (4, 1), (6, 0)):
+            shp = wl.SHAPES[cfg][si]
+            M, K, N = shp.M, shp.K, shp.N
+            nsets = max(2, min(sets, int(600e6 // (2 * M * (K + N)))))
+            A = [torch.randn((K, M), dtype=torch.float16, device=dev) for _ in range(nsets)]
+            C = [torch.empty((N, M), dtype=torch.float16, device=dev) for _ in range(nsets)]
+            for recipe in ("per_tile", "global", "global, column blocks rescaled"):
+                if recipe.startswith("global,"):
+                    # i.i.d. weights give nearly even tiles under one threshold; trained layers do
+                    # not: rescale each block of 128 columns by exp(N(0, 0.6^2)) before thresholding
+                    Bs = wl.make_B(wl.seed_for(cfg, si), K, N, shp.sigma).astype(np.float32)
+                    f = np.exp(0.6 * np.random.default_rng(wl.seed_for(cfg, si) + 7).standard_normal((N + 127) // 128))
+                    Bs = (Bs * np.repeat(f, 128)[:N]).astype(np.float16)
+                    mask = wl.tw_mask(Bs, 128, density=0.25, col_frac=0.10, recipe="global")
+                else:
+                    c = wl.make_case(cfg, si, pattern="tw", sparsity=0.75, G=128, recipe=recipe, with_A=False)
+                    Bs, mask = c.B, c.mask
+                row = dict(shape=shp.name, M=M, K=K, N=N, G=128, pattern="tw", sparsity=0.75, recipe=recipe)
+                for order in (1, 0):
+                    tw.tw_set_option("tile_order", order)
+                    packed = [tw.tw_pack(Bs, mask, 128, tw.PATTERN_TW) for _ in range(nsets)]
+                    t = timed(lambda r: tw.tw_gemm(A[r % nsets].data_ptr(), M, M, tw.LAYOUT_KM, packed[r % nsets],
+                                                   C[r % nsets].data_ptr(), M, stream))
+                    kt = np.array([len(r) for r in packed[0].export()["row_idx"]])
+                    row.update({("us_longest_first" if order else "us_column_order"): round(t * 1e6, 2),
+                                "K_t_min": int(kt.min()), "K_t_mean": round(float(kt.mean()), 1), "K_t_max": int(kt.max())})
+                    for p in packed:
+                        p.free()
+                tw.tw_set_option("tile_order", 1)
+                rows.append(row)
+            del A, C
+        out["imbalance"] = rows
+    if "conv" in which:
+        rows = []
+        for si, (name, g, N) in enumerate(wl.CONV_LAYERS):
+            M, K, Mp, ldx = g.B * g.H * g.W, g.K, g.Mp, wl.conv_ldx(g)
+            ns_conv = max(2, min(24, int(600e6 // (2 * (g.C * ldx + N * Mp)))))
+            ns_mat = max(2, min(sets, int(600e6 // (2 * M * (K + N)))))
+            X = [torch.randn((g.C, ldx), dtype=torch.float16, device=dev) for _ in range(ns_conv)]
+            Cw = [torch.empty((N, Mp), dtype=torch.float16, device=dev) for _ in range(ns_conv)]
+            A = [torch.randn((K, M), dtype=torch.float16, device=dev) for _ in range(ns_mat)]
+            Cm = [torch.empty((N, M), dtype=torch.float16, device=dev) for _ in range(ns_mat)]
+            for pattern, sp, G in (("tw", 0.75, 128), ("tw", 0.75, 64), ("tvw", 0.875, 128), ("tw", 0.0, 128)):
+                c = wl.make_case(5, si, pattern=pattern, sparsity=sp, G=G, col_frac=0.0 if sp == 0.0 else None,
+                                 with_A=False)
+                pat = tw.PATTERN_TW if pattern == "tw" else tw.PATTERN_TVW
+                packed = [tw.tw_pack(c.B, c.mask, G, pat, tile_mask=c.tile_mask if pattern != "tw" else None)
+                          for _ in range(ns_conv)]
+                bound_ = [tw.tw_conv_bind(p, g, ldx) for p in packed]
+                skw, sk, ku = packed[0].flop_counts()
+                t_conv = timed(lambda r: tw.tw_conv_gemm(X[r % ns_conv].data_ptr(), bound_[r % ns_conv],
+                                                         Cw[r % ns_conv].data_ptr(), Mp, stream))
+                t_mat = timed(lambda r: tw.tw_gemm(A[r % ns_mat].data_ptr(), M, M, tw.LAYOUT_KM, packed[r % ns_mat],
+                                                   Cm[r % ns_mat].data_ptr(), M, stream))
+                wbytes = 2 * skw if pattern == "tw" else skw + skw // 8
+                ab = 2 * g.C * Mp + 2 * N * Mp + wbytes + 4 * sk       # the input once, C over the wide grid, weight
+                rows.append(dict(shape=name, positions=M, wide_grid=Mp, K=K, N=N, G=G, pattern=pattern, sparsity=sp,
+                                 us_implicit=round(t_conv * 1e6, 2), us_materialised=round(t_mat * 1e6, 2),
+                                 input_MB=round(2 * g.C * Mp / 1e6, 2), materialised_A_MB=round(2 * M * ku / 1e6, 2),
+                                 alg_MB=round(ab / 1e6, 2), alg_GBps=round(ab / t_conv / 1e9, 1)))
+                for b in bound_:
+                    b.free()
+                for p in packed:
+                    p.free()
+            del X, Cw, A, Cm
+        out["conv"] = rows
+    if "i8" in which:
+        rows = []
+        for cfg, si in [(2, 0), (2, 1), (2, 2), (4, 0), (4, 1)]:
+            shp = wl.SHAPES[cfg][si]
+            M, K, N, G = shp.M, shp.K, shp.N, 128
+            nsets = max(2, min(sets, int(600e6 // (M * (K + 4 * N)))))
+            B8 = wl.rng_i8(wl.seed_for(cfg, si) + 1, (K, N))
+            for pattern, sp in (("tw", 0.75), ("tw", 0.875), ("tvw", 0.875)):
+                B16 = B8.astype(np.float16)
+                if pattern == "tw":
+                    mask = tmask = wl.tw_mask(B16, G, density=1.0 - sp, col_frac=0.10)
+                else:
+                    mask, tmask = wl.tvw_mask(B16, G, sparsity=sp, col_frac=0.10)
+                pat = tw.PATTERN_TW if pattern == "tw" else tw.PATTERN_TVW
+                tmk = tmask if pattern == "tvw" else None
+                packed = [tw.tw_pack_i8(B8, mask, G, pat, tile_mask=tmk) for _ in range(nsets)]
+                p16 = [tw.tw_pack(B16, mask, G, pat, tile_mask=tmk) for _ in range(nsets)]
+                A8 = [torch.randint(-127, 128, (K, M), dtype=torch.int8, device=dev) for _ in range(nsets)]
+                A16 = [a.to(torch.float16) for a in A8]
+                C8 = [torch.empty((N, M), dtype=torch.int8, device=dev) for _ in range(nsets)]
+                C16 = [torch.empty((N, M), dtype=torch.float16, device=dev) for _ in range(nsets)]
+                Bd = torch.from_numpy(B8).to(dev)
+                t8 = timed(lambda r: tw.tw_gemm_i8(A8[r % nsets].data_ptr(), M, M, packed[r % nsets],
+                                                   C8[r % nsets].data_ptr(), M, 1, 1e-3, stream))
+                td8 = timed(lambda r: tw.tw_dense_gemm_i8(A8[r % nsets].data_ptr(), Bd.data_ptr(), C8[r % nsets].data_ptr(),
+                                                          M, K, N, M, N, M, 1, 1e-3, stream))
+                t16 = timed(lambda r: tw.tw_gemm(A16[r % nsets].data_ptr(), M, M, tw.LAYOUT_KM, p16[r % nsets],
+                                                 C16[r % nsets].data_ptr(), M, stream))
+                rows.append(dict(shape=shp.name, M=M, K=K, N=N, G=G, pattern=pattern + "_i8", sparsity=sp,
+                                 us_i8_out=round(t8 * 1e6, 2), dense_i8_us=round(td8 * 1e6, 2), fp16_us=round(t16 * 1e6, 2),
+                                 speedup_vs_dense_i8=round(td8 / t8, 3), speedup_vs_fp16=round(t16 / t8, 3),
+                                 dense_eq_tops=round(2.0 * M * K * N / t8 / 1e12, 1)))
+                for p in packed + p16:
+                    p.free()
+                del A8, A16, C8, C16
+        out["i8"] = rows
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -186,6 +371,8 @@ def main():
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-rows", action="store_true", help="skip the rows of the other configured workloads")
     ap.add_argument("--no-calibration", action="store_true")
+    ap.add_argument("--extra", default="", help="comma list of opt-in sweeps, printed under `extra`: "
+                                                "cube, imbalance, tew, i8, conv (each takes 10-60 s)")
     ap.add_argument("--calibrate", action="store_true", help="run the calibration kernels only and print their rates")
     ap.add_argument("--separate-qkv", action="store_true",
                     help="time the step with Q, K and V as three launches (6 launches per step)")
@@ -409,6 +596,8 @@ def main():
             (cal["mfma_f16_TFLOPs"] if args.pattern == "tw" else cal["smfmac_f16_dense_eq_TFLOPs"] / 2.0))
     if rows is not None:
         out["rows"] = rows
+    if args.extra:
+        out["extra"] = extra_sweeps(tw, wl, torch, dev, stream, set(args.extra.split(",")))
 
     if not args.no_cpu_baseline:
         from oracle import gemm as og

@@ -100,11 +100,15 @@ int pick_tile_m_tvw(const Opts& o, int G, int M, int n_tiles) {
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 // K-split inside the workgroup pays when 128-row tiles cannot give every CU a
-// workgroup and the K loop is long enough to amortise the final reduction.
+// workgroup and the K loop is long enough to amortise the final reduction.  64-row tiles
+// only where 128-row tiles would leave more than half of the CUs idle: they move half as much
+// again from L2 into LDS per product and read A in 128-byte pieces (3072 x 768 at M = 4096 from
+// cold HBM: 15.9 us with 64-row tiles, 13.7 with 128-row tiles; 4608 x 512 at M = 1568, 52
+// tiles of 128 rows: 11.1 against 14.2 us the other way).
 bool use_ksplit(int M, int n_tiles, int max_k, int* tm) {
   const long wgs128 = (long)((M + 127) / 128) * n_tiles;
   if (max_k < 12 * 32 || wgs128 > 320) return false;
-  *tm = wgs128 <= 224 ? 64 : 128;
+  *tm = wgs128 < 128 ? 64 : 128;
   return true;
 }
 
