@@ -386,7 +386,7 @@ const char* tw_status_str(int status);
  *   "depth"    stages in flight of the asynchronous pipeline: 3 (default) .. 8 (6 and 8 exist for
               4-wave tiles of 64 x 128, 128 x 128 and 128 x 64 only; TVW: 3 or 4)
    "idx_route" how the asynchronous TW kernel reads a tile's kept-row list: 0 = automatic
-              (through LDS where at most two 4-wave workgroups share a CU, scalar loads
+              (through LDS where at most one and a half 4-wave workgroups per CU run, scalar loads
               otherwise), 1 = scalar loads, 2 = through LDS
    "wg_split" K split across workgroups (tw_gemm_ex with a workspace): 0 / 1 = off,
               2..8 = workgroups per (M-tile, N-tile) pair

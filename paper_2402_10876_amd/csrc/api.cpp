@@ -65,7 +65,13 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 
 // and a half workgroups per CU still take the larger tile (128 rows; 256 for G = 64):
 // they are bound by the L2 -> LDS traffic, which is (tm + G) / (tm G) per product
 // (measured on the 3 x 3 convolution 256 -> 256 at 56 x 56: 17.0 against 21.7 us).
-int pick_tile_m(const Opts& o, int M, int n_tiles, int G, int max_k) {
+// 256-row tiles of G = 128 (8 waves) need kept-row lists of at least 384 rows: with shorter
+// ones they lose 3-6 % to 128-row tiles (1024 x 4096 at M = 8192 from HBM: 23.5 against 22.2 us
+// at 87.5 %), with longer ones they win 10-25 % (44.5 against 49.1 us at 50 %).  `dense`: the
+// dense kernel has no gather to hide and takes 256 rows from one workgroup per CU on when
+// K >= 1024 (2304 x 256 at M = 25088: 41.3 against 48.5 us), 128 rows for shorter K
+// (768 x 3072 at M = 4096: 23.8 against 25.5 us).
+int pick_tile_m(const Opts& o, int M, int n_tiles, int G, int max_k, bool dense = false) {
   const int forced = o.tile_m;
   if (forced == 64 || forced == 128 || forced == 256) {
     if (!(G == 32 && forced == 64)) return forced;
@@ -75,6 +81,8 @@ int pick_tile_m(const Opts& o, int M, int n_tiles, int G, int max_k) {
     if (G == 32 && tm == 64) break;
     long need = max_k >= 768 ? 320 : 512;
     if (need == 512 && (tm == 128 || (tm == 256 && G == 64))) need = 384;
+    if (tm == 256 && G == 128 && max_k < 384) continue;
+    if (tm == 256 && dense) need = max_k >= 1024 ? 192 : 512;
     const long wgs = (long)((M + tm - 1) / tm) * n_tiles;
     if (wgs >= need) return tm;
   }
@@ -86,13 +94,18 @@ int pick_tile_m(const Opts& o, int M, int n_tiles, int G, int max_k) {
 // round: at most one workgroup per CU, or a remainder of at most half a round of 512.
 // Measured on the configured shapes: 3-13 % on the BERT-base ones, while large grids and
 // long K loops (the weight tile is re-read per workgroup) keep 128.  The 256-row instance
-// (8 waves) is within 3 % of the 128-row one everywhere and only used when asked for.
-int pick_tile_m_tvw(const Opts& o, int G, int M, int n_tiles) {
+// (8 waves) is within 3 % of the 128-row one on those; it is taken where a few N-tiles with
+// long kept-row lists meet many M-tiles (at most one round of 128-row workgroups, at least
+// three quarters of a round of 256-row ones): every workgroup reads its whole weight tile, and
+// 256 rows share it (from HBM, 4096 x 1024 at M = 8192: 36.6 / 23.0 / 16.4 against 38.9 / 25.9 /
+// 17.3 us at 75 / 87.5 / 93.75 %; 2304 x 256 at M = 25088: 15.8 against 18.6 us).
+int pick_tile_m_tvw(const Opts& o, int G, int M, int n_tiles, int max_k) {
   const int forced = o.tile_m;
   if (G != 128) return 128;
   if (forced == 64 || forced == 128 || forced == 256) return forced;
   const long wgs128 = (long)((M + 127) / 128) * n_tiles;
   if (wgs128 <= 256) return 64;
+  if (wgs128 <= 512 && (long)((M + 255) / 256) * n_tiles >= 192 && max_k >= 512) return 256;
   const long tail = wgs128 % 512;
   return (wgs128 <= 1536 && tail != 0 && tail <= 256) ? 64 : 128;
 }
@@ -376,7 +389,7 @@ static tw_status gemm_launch(const Opts& o, const void* A, int M, int lda, int l
     return e == hipSuccess ? TW_OK : TW_ERR_HIP;
   }
   if (h->pattern == TW_PATTERN_TVW) {
-    const int tvw_tm = pick_tile_m_tvw(o, h->G, M, h->n_tiles > 0 ? h->n_tiles : 1);
+    const int tvw_tm = pick_tile_m_tvw(o, h->G, M, h->n_tiles > 0 ? h->n_tiles : 1, h->max_kp);
     hipError_t e = twg::launch_tvw_km(h->G, tvw_tm, o.depth > 4 ? 4 : o.depth, g, (hipStream_t)stream);
     if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
     return e == hipSuccess ? TW_OK : TW_ERR_HIP;
@@ -421,12 +434,15 @@ static tw_status gemm_launch(const Opts& o, const void* A, int M, int lda, int l
     if (ks == 2 || (ks == 0 && use_ksplit(M, h->n_tiles, h->max_kp, &tmk))) variant = twg::DMA_KSPLIT2;
     if (variant == twg::DMA_KSPLIT2 && ks == 2) tmk = tm == 256 ? 128 : tm;
     if (variant == twg::DMA_KSPLIT2 && h->G == 64) tmk = 128;   // the one K-split instance for G = 64
-    // kept-row lists through LDS where at most two 4-wave workgroups share a CU (nothing else
-    // there hides the scalar loads' round trip); by scalar loads for 8-wave tiles and full CUs
+    // kept-row lists through LDS where at most one and a half 4-wave workgroups per CU run
+    // (nothing else there hides the scalar loads' round trip: -6...-22 %); by scalar loads for
+    // 8-wave tiles and fuller CUs (two workgroups per CU: 3-7 % ahead of the LDS route, unless
+    // the lists are long: 4096 x 1024 at M = 8192 and 50 %, 46.3 with LDS against 50.0 us)
     const int tmu = variant == twg::DMA_KSPLIT2 ? tmk : tm;
     auto lidx_for = [&](int v, int t) {
       if (o.idx_route) return o.idx_route == 2;
-      return v != twg::DMA_WAVES8 && (long)((M + t - 1) / t) * h->n_tiles <= 512;
+      const long wgs = (long)((M + t - 1) / t) * h->n_tiles;
+      return v != twg::DMA_WAVES8 && (wgs <= 384 || (wgs <= 512 && h->max_kp >= 2048));
     };
     e = launch_dma(h->G, tmu, depth, variant, lidx_for(variant, tmu), g, (hipStream_t)stream);
     if (e == hipErrorInvalidValue && variant != twg::DMA_WAVES4)
@@ -568,7 +584,7 @@ tw_status tw_dense_gemm(const void* A, const void* B, void* C, int M, int K, int
     hipError_t em = twg::launch_dense_mk(tn, g, (hipStream_t)stream);
     return em == hipSuccess ? TW_OK : TW_ERR_HIP;
   }
-  const int tm = pick_tile_m(o, M, g.n_tiles, tn, K);
+  const int tm = pick_tile_m(o, M, g.n_tiles, tn, K, true);
   hipError_t e = hipErrorInvalidValue;
   const bool fits32 = (unsigned long long)K * (unsigned long long)lda * 2ull < (1ull << 32) &&
                       (unsigned long long)K * (unsigned long long)ldb * 2ull < (1ull << 32);
