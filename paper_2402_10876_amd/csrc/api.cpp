@@ -83,6 +83,10 @@ int pick_tile_m(const Opts& o, int M, int n_tiles, int G, int max_k, bool dense 
     if (need == 512 && (tm == 128 || (tm == 256 && G == 64))) need = 384;
     if (tm == 256 && G == 128 && max_k < 384) continue;
     if (tm == 256 && dense) need = max_k >= 1024 ? 192 : 512;
+    // one 256-row workgroup per CU with its kept-row lists through LDS: 3-9 % ahead of two
+    // 128-row ones when the lists are long (4096 x 1024 at M = 8192: 46.9 against 49.5 us at
+    // 50 %, 28.7 against 29.7 at 75 %; 2304 x 256 at M = 25088: 17.5 against 19.3 us)
+    if (tm == 256 && G == 128 && !dense && max_k >= 640) need = 192;
     const long wgs = (long)((M + tm - 1) / tm) * n_tiles;
     if (wgs >= need) return tm;
   }
@@ -435,14 +439,15 @@ static tw_status gemm_launch(const Opts& o, const void* A, int M, int lda, int l
     if (variant == twg::DMA_KSPLIT2 && ks == 2) tmk = tm == 256 ? 128 : tm;
     if (variant == twg::DMA_KSPLIT2 && h->G == 64) tmk = 128;   // the one K-split instance for G = 64
     // kept-row lists through LDS where at most one and a half 4-wave workgroups per CU run
-    // (nothing else there hides the scalar loads' round trip: -6...-22 %); by scalar loads for
-    // 8-wave tiles and fuller CUs (two workgroups per CU: 3-7 % ahead of the LDS route, unless
+    // (nothing else there hides the scalar loads' round trip: -6...-22 %) or one 8-wave
+    // workgroup; by scalar loads for fuller CUs (two workgroups per CU: 3-7 % ahead of the LDS route, unless
     // the lists are long: 4096 x 1024 at M = 8192 and 50 %, 46.3 with LDS against 50.0 us)
     const int tmu = variant == twg::DMA_KSPLIT2 ? tmk : tm;
     auto lidx_for = [&](int v, int t) {
       if (o.idx_route) return o.idx_route == 2;
       const long wgs = (long)((M + t - 1) / t) * h->n_tiles;
-      return v != twg::DMA_WAVES8 && (wgs <= 384 || (wgs <= 512 && h->max_kp >= 2048));
+      if (v == twg::DMA_WAVES8) return wgs <= 256;       // alone on its CU: nothing else hides the round trip
+      return wgs <= 384 || (wgs <= 512 && h->max_kp >= 2048);
     };
     e = launch_dma(h->G, tmu, depth, variant, lidx_for(variant, tmu), g, (hipStream_t)stream);
     if (e == hipErrorInvalidValue && variant != twg::DMA_WAVES4)
