@@ -45,6 +45,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+PREWARM_S = 0.05            # untimed launches before each measurement (see main)
 FP16_PEAK_TFLOPS = 2500.0
 PLAN = [(0, 4), (1, 1), (2, 1)]          # (shape index in the config, copies per layer)
 # HBM-side bytes per launch (average over the launches of a step), NOT measured by this run:
@@ -125,7 +126,12 @@ def calibration(tw, torch, dev, stream, quick=False):
 def extra_rows(tw, wl, torch, dev, stream, skip_cfg, reps=24, sets=24):
     """One row per other configured workload (launch configuration as the heuristics pick it),
     timed on enough rotating buffer sets (about 600 MB) that operands come from HBM."""
-    def timed(fn, rounds=3):
+    def timed(fn, rounds=5):
+        t_w = time.perf_counter()      # untimed: first touch of fresh buffers, clocks up after host-side packing
+        while time.perf_counter() - t_w < PREWARM_S:
+            for r in range(reps):
+                fn(r)
+            torch.cuda.synchronize()
         vals = []
         for _ in range(rounds):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -199,7 +205,12 @@ def extra_sweeps(tw, wl, torch, dev, stream, which, reps=24, sets=6):
     and in column order, TEW at 75 % with delta restored elements (Section VI, impact of delta),
     int8 TW / TVW against the dense int8 kernel and the fp16 launch of the same mask (Section
     VI-B), and config 5's convolutions on the wide input against the materialised matrix."""
-    def timed(fn, rounds=3):
+    def timed(fn, rounds=5):
+        t_w = time.perf_counter()      # untimed: first touch of fresh buffers, clocks up after host-side packing
+        while time.perf_counter() - t_w < PREWARM_S:
+            for r in range(reps):
+                fn(r)
+            torch.cuda.synchronize()
         vals = []
         for _ in range(rounds):
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -457,6 +468,14 @@ def main():
     # (first thing after the opening synchronisation, last thing before the closing one) gives
     # the device-side span of the same launches: span / launches is the average launch duration
     # of the roofline (back-to-back launches, so the gap between two kernels is part of it).
+    # Before the W warm-up steps: the same steps, untimed, for PREWARM_S seconds.  The weights were
+    # just packed on the host, the GPU sat idle meanwhile, and its clocks take tens of milliseconds
+    # of work to come back up; a short run (few steps, few warm-up steps) would time that ramp.
+    t_w = time.perf_counter()
+    while time.perf_counter() - t_w < PREWARM_S:
+        for i in range(args.sets):
+            step(i)
+        torch.cuda.synchronize()
     for i in range(args.warmup):
         step(i)
     torch.cuda.synchronize()

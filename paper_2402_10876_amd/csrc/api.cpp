@@ -612,11 +612,12 @@ tw_status tw_dense_gemm(const void* A, const void* B, void* C, int M, int K, int
 
 // int8 M-tile: 256 rows while that still gives every CU two workgroups, else 128.  The 64-row
 // instance (G = 128) is only used on request: it measured no better than 128 rows on the small
-// BERT-base launches and worse on the dense baseline.
-static int pick_tile_m_i8(const Opts& o, int M, int n_tiles, int G) {
+// BERT-base launches and worse on the dense baseline.  As for fp16, 256 rows need kept-row lists of
+// at least 384 rows (1024 x 4096 at M = 8192 and 87.5 %, from HBM: 17.5 against 16.3 us).
+static int pick_tile_m_i8(const Opts& o, int M, int n_tiles, int G, int max_k) {
   const int forced = o.tile_m;
   if (forced == 128 || forced == 256 || (forced == 64 && G == 128)) return forced;
-  return (long)((M + 255) / 256) * n_tiles >= 512 ? 256 : 128;
+  return (max_k >= 384 && (long)((M + 255) / 256) * n_tiles >= 512) ? 256 : 128;
 }
 
 // The launch behind tw_gemm_i8 and tw_conv_gemm_i8 (conv: see gemm_launch).
@@ -645,7 +646,7 @@ static tw_status gemm_i8_launch(const void* A, int M, int lda, tw_handle_t h, vo
     e = twg::launch_tvw_i8(h->G, tm, g, (hipStream_t)stream);
   } else {
     // long K with too few tiles to fill the chip: split K inside the workgroup (as the fp16 path)
-    const int tm = pick_tile_m_i8(o, M, h->n_tiles > 0 ? h->n_tiles : 1, h->G);
+    const int tm = pick_tile_m_i8(o, M, h->n_tiles > 0 ? h->n_tiles : 1, h->G, h->max_kp);
     const int ks = o.ksplit;
     int tmk = tm;
     e = hipErrorInvalidValue;
@@ -699,7 +700,7 @@ tw_status tw_dense_gemm_i8(const void* A, const void* B, void* C, int M, int K, 
   g.n_tiles = (N + tn - 1) / tn;
   const Opts o = default_opts();
   g.xcd_map = o.xcd_map ? 1 : 0;
-  hipError_t e = twg::launch_dense_i8(tn, pick_tile_m_i8(o, M, g.n_tiles, tn), g, (hipStream_t)stream);
+  hipError_t e = twg::launch_dense_i8(tn, pick_tile_m_i8(o, M, g.n_tiles, tn, K), g, (hipStream_t)stream);
   if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
   return e == hipSuccess ? TW_OK : TW_ERR_HIP;
 }
