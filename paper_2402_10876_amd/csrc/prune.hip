@@ -37,23 +37,23 @@ __device__ __forceinline__ bool before(u128 sa, int ia, u128 sb, int ib) {   // 
   return sa < sb || (sa == sb && ia < ib);
 }
 
-// TW-C scores: thread (column, slice of rows); the squares of a slice are summed in a 128-bit
-// register and added to the column's score as three 32-bit limbs, each in a 64-bit word of its
-// own (2^32 limbs fit before a word overflows), so that plain 64-bit atomics keep the sum exact
-// and independent of the order; column_score_finish carries the limbs into one 128-bit integer.
-__global__ void column_scores(const uint16_t* B, int K, int N, int ldb, unsigned long long* limbs) {
+// TW-C scores in two steps, exact and independent of any order (integer sums): thread (column,
+// slice y of the rows k = y, y + slices, ..) writes the slice's sum of squares; column_score_finish
+// adds a column's slices and clears its rank counter for the counting that follows.
+__global__ void column_partial(const uint16_t* B, int K, int N, int ldb, u128* partial) {
   const int n = blockIdx.x * blockDim.x + threadIdx.x;
   if (n >= N) return;
   u128 s = 0;
   for (int k = blockIdx.y; k < K; k += gridDim.y) s += square48(B[(size_t)k * ldb + n]);
-  atomicAdd(limbs + 3 * (size_t)n + 0, (unsigned long long)(uint32_t)s);
-  atomicAdd(limbs + 3 * (size_t)n + 1, (unsigned long long)(uint32_t)(s >> 32));
-  atomicAdd(limbs + 3 * (size_t)n + 2, (unsigned long long)(s >> 64));
+  partial[(size_t)blockIdx.y * N + n] = s;
 }
-__global__ void column_score_finish(const unsigned long long* limbs, int N, u128* score) {
+__global__ void column_score_finish(const u128* partial, int slices, int N, u128* score, int32_t* rank) {
   const int n = blockIdx.x * blockDim.x + threadIdx.x;
   if (n >= N) return;
-  score[n] = (u128)limbs[3 * (size_t)n] + ((u128)limbs[3 * (size_t)n + 1] << 32) + ((u128)limbs[3 * (size_t)n + 2] << 64);
+  u128 s = 0;
+  for (int y = 0; y < slices; ++y) s += partial[(size_t)y * N + n];
+  score[n] = s;
+  rank[n] = 0;
 }
 
 // Rank by counting, in parts: workgroup (x, y, z) compares entries [256 x, +256) of segment z
@@ -79,25 +79,30 @@ __global__ void keep_from_rank(int32_t* rank_keep, size_t n, int n_pruned) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) rank_keep[i] = rank_keep[i] >= n_pruned;
 }
-__global__ void zero_i32(int32_t* p, size_t n) {
-  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0;
-}
-
-__global__ void zero_u64(unsigned long long* p, int n) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n) p[i] = 0ull;
-}
-
-// TW-R scores: tile t = kept columns [t*G, min((t+1)*G, n_kept)); one thread per (tile, row).
+// TW-R scores: tile t = kept columns [t*G, min((t+1)*G, n_kept)); one wave per (tile, row), its
+// lanes over the tile's columns (neighbouring lanes read neighbouring kept columns of one row).
+// The lanes' 128-bit sums meet as three 32-bit limbs, each in a 64-bit word (64 lanes cannot
+// overflow it), added across the wave; lane 0 carries them into the score and clears the row's
+// rank counter.
 __global__ void tile_row_scores(const uint16_t* B, int K, int ldb, int G, int n_kept,
-                                const int32_t* kept_cols, u128* score) {
-  const int t = blockIdx.y, k = blockIdx.x * blockDim.x + threadIdx.x;
-  if (k >= K) return;
+                                const int32_t* kept_cols, u128* score, int32_t* rank) {
+  const int t = blockIdx.y, lane = threadIdx.x & 63;
+  const int k = blockIdx.x * (blockDim.x >> 6) + (threadIdx.x >> 6);
+  if (k >= K) return;                                   // whole waves leave together
   const int c0 = t * G, c1 = min(c0 + G, n_kept);
   u128 s = 0;
-  for (int c = c0; c < c1; ++c) s += square48(B[(size_t)k * ldb + kept_cols[c]]);
-  score[(size_t)t * K + k] = s;
+  for (int c = c0 + lane; c < c1; c += 64) s += square48(B[(size_t)k * ldb + kept_cols[c]]);
+  unsigned long long l0 = (uint32_t)s, l1 = (uint32_t)(s >> 32), l2 = (unsigned long long)(s >> 64);
+#pragma unroll
+  for (int d = 32; d >= 1; d >>= 1) {
+    l0 += __shfl_xor(l0, d);
+    l1 += __shfl_xor(l1, d);
+    l2 += __shfl_xor(l2, d);
+  }
+  if (lane == 0) {
+    score[(size_t)t * K + k] = (u128)l0 + ((u128)l1 << 32) + ((u128)l2 << 64);
+    rank[(size_t)t * K + k] = 0;
+  }
 }
 
 // tile_mask[k][n] = column n kept and row k kept in n's tile; `mask` (TVW) starts as zeros.
@@ -134,11 +139,19 @@ size_t align_up(size_t x) { return (x + 255) / 256 * 256; }
 
 }  // namespace
 
+// Row slices of the column scores: about 512 workgroups of 256 columns in all, so at most
+// 2 MiB of partial sums whatever the shape.
+static int column_slices(int K, int N) {
+  const int nbx = (N + 255) / 256;
+  const int want = 512 / nbx > 1 ? 512 / nbx : 1;
+  return K < want ? K : want;
+}
+
 size_t prune_workspace_bytes(int K, int N, int G) {
   const size_t nt = (size_t)(N + G - 1) / G;
   return align_up((size_t)N * 16) + 3 * align_up((size_t)N * 4) +          // column score, keep, pos, list
          align_up(nt * K * 16) + 3 * align_up(nt * K * 4) +                 // row score, keep, pos, list
-         align_up((size_t)N * 24);                                          // column score limbs
+         align_up((size_t)column_slices(K, N) * N * 16);                    // column scores per row slice
 }
 
 hipError_t prune_device(const uint16_t* B, int K, int N, int ldb, int G, bool tvw, int n_cols_pruned,
@@ -156,7 +169,7 @@ hipError_t prune_device(const uint16_t* B, int K, int N, int ldb, int G, bool tv
   int32_t* row_keep = (int32_t*)w;       w += align_up(ntmax * K * 4);
   int32_t* row_pos = (int32_t*)w;        w += align_up(ntmax * K * 4);
   int32_t* row_list = (int32_t*)w;       w += align_up(ntmax * K * 4);
-  unsigned long long* col_limbs = (unsigned long long*)w;
+  u128* col_partial = (u128*)w;
   const int T = 256;
   (void)hipGetLastError();   // an error left behind by an earlier call of this thread is not this call's
   // a failed launch ends the call: later kernels would read workspace nobody wrote
@@ -166,20 +179,17 @@ hipError_t prune_device(const uint16_t* B, int K, int N, int ldb, int G, bool tv
     const hipError_t e_ = hipGetLastError();                                  \
     if (e_ != hipSuccess) return e_;                                          \
   } while (0)
-  // zeroed by a kernel, not a memset node: the caller may be capturing a graph
-  TWG_LAUNCH(zero_u64, dim3((3 * N + T - 1) / T), dim3(T), col_limbs, 3 * N);
-  const int ky = K < 128 ? K : 128;      // row slices: 128 x N/256 workgroups
-  TWG_LAUNCH(column_scores, dim3((N + T - 1) / T, ky), dim3(T), B, K, N, ldb, col_limbs);
-  TWG_LAUNCH(column_score_finish, dim3((N + T - 1) / T), dim3(T), col_limbs, N, col_score);
+  // (counters are cleared by the kernels, not by memset nodes: the caller may be capturing a graph)
+  const int ky = column_slices(K, N);
   const unsigned nb = (unsigned)((N + T - 1) / T);
-  TWG_LAUNCH(zero_i32, dim3(nb), dim3(T), col_keep, (size_t)N);
+  TWG_LAUNCH(column_partial, dim3(nb, ky), dim3(T), B, K, N, ldb, col_partial);
+  TWG_LAUNCH(column_score_finish, dim3(nb), dim3(T), col_partial, ky, N, col_score, col_keep);
   TWG_LAUNCH(rank_partial, dim3(nb, nb, 1), dim3(T), col_score, N, col_keep);
   TWG_LAUNCH(keep_from_rank, dim3(nb), dim3(T), col_keep, (size_t)N, n_cols_pruned);
   TWG_LAUNCH(compact, dim3(1), dim3(1024), col_keep, N, col_pos, kept_cols);
   if (nt > 0) {
-    TWG_LAUNCH(tile_row_scores, dim3((K + T - 1) / T, nt), dim3(T), B, K, ldb, G, n_kept, kept_cols, row_score);
+    TWG_LAUNCH(tile_row_scores, dim3((K + 3) / 4, nt), dim3(T), B, K, ldb, G, n_kept, kept_cols, row_score, row_keep);
     const unsigned kb = (unsigned)((K + T - 1) / T), all = (unsigned)(((size_t)nt * K + T - 1) / T);
-    TWG_LAUNCH(zero_i32, dim3(all), dim3(T), row_keep, (size_t)nt * K);
     TWG_LAUNCH(rank_partial, dim3(kb, kb, nt), dim3(T), row_score, K, row_keep);
     TWG_LAUNCH(keep_from_rank, dim3(all), dim3(T), row_keep, (size_t)nt * K, K - rows_per_tile);
   }
