@@ -103,7 +103,7 @@ def test_conv_equals_the_launch_on_the_materialised_matrix():
 @pytest.mark.parametrize("layer,G", [(1, 64), (1, 128), (0, 128)])
 def test_conv_vgg_layer_on_sampled_positions(layer, G):
     """The configured 3x3 layers at full size (512 -> 512 at 14 x 14 and 256 -> 256 at 56 x 56, batch
-    8; the launch configuration the sweep times), checked on sampled positions the oracle computes
+    8; the launch configuration the benchmark times), checked on sampled positions the oracle computes
     one by one."""
     from tests import gpu_util as gu
     name, g, N = wl.CONV_LAYERS[layer]

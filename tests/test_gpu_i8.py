@@ -146,7 +146,7 @@ def test_i8_concat_runs_as_one_launch():
 
 
 def test_i8_full_size_bert_shape_on_sampled_rows():
-    """768 x 3072 at M = 4096 in the launch configuration the sweep times (automatic tile
+    """768 x 3072 at M = 4096 in the launch configuration the benchmark times (automatic tile
     choice), checked on sampled rows of C the oracle computes one by one."""
     M, K, N, G = 4096, 768, 3072, 128
     A, B = wl.rng_i8(40, (M, K)), wl.rng_i8(41, (K, N), sigma=30.0)
