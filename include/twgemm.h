@@ -248,7 +248,10 @@ tw_status tw_gemm(const void* A_dev, int M, int lda, int layout, tw_handle_t h,
  *                   xcd_map -1 (default) | 0 | 1 | 2,
  *                   wg_split 0 = automatic when a workspace is given, 1 = never,
  *                            2..8 = that many workgroups per (M-tile, N-tile) pair,
- *                   idx_route 0 = automatic, 1 = kept-row lists by scalar loads, 2 = through LDS
+ *                   idx_route 0 = automatic, 1 = kept-row lists by scalar loads, 2 = through LDS,
+ *                   tiles_per_wg 0 = automatic (one: more never measured faster), 1..8 = tiles a
+ *                            workgroup of the asynchronous TW kernel computes one after the
+ *                            other (same results bit for bit)
  *   workspace_dev device memory, 256-byte aligned, at least tw_gemm_workspace_bytes(h, M) bytes,
  *                 prepared ONCE with tw_workspace_init (its first 4 KiB are counters that every
  *                 launch leaves at zero again).  Launches that share a workspace must not
@@ -260,7 +263,7 @@ tw_status tw_gemm(const void* A_dev, int M, int lda, int layout, tw_handle_t h,
  * invalid option value, a misaligned workspace, or wg_split > 1 with a workspace too small.
  */
 typedef struct {
-  int32_t tile_m, kernel, depth, waves, ksplit, xcd_map, wg_split, idx_route;
+  int32_t tile_m, kernel, depth, waves, ksplit, xcd_map, wg_split, idx_route, tiles_per_wg;
   void* workspace_dev;
   size_t workspace_bytes;
 } tw_launch_opts;
@@ -390,6 +393,11 @@ const char* tw_status_str(int status);
               otherwise), 1 = scalar loads, 2 = through LDS
    "wg_split" K split across workgroups (tw_gemm_ex with a workspace): 0 / 1 = off,
               2..8 = workgroups per (M-tile, N-tile) pair
+ *   "tiles_per_wg" tiles a workgroup of the asynchronous TW kernel computes one after the other
+ *              (plain TW, 4 waves, G = 128, 64- or 128-row tiles, 3 stages; ignored elsewhere): the
+ *              stores of a finished tile drain while the next one loads.  0 = automatic (one:
+ *              with every tile resident at once the launches are faster than with tiles in
+ *              sequence), 1..8 = that many; the results do not change
  *   "tile_order"  read by tw_pack / tw_concat: 1 (default) = tiles are launched longest
  *              kept-row list first (uneven tiles, Section V "load imbalance"); 0 = in
  *              column order

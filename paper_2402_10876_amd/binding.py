@@ -46,7 +46,7 @@ class _View(C.Structure):
 class LaunchOpts(C.Structure):
     """tw_launch_opts: per-call launch options (see include/twgemm.h)."""
     _fields_ = [("tile_m", C.c_int32), ("kernel", C.c_int32), ("depth", C.c_int32), ("waves", C.c_int32),
-                ("ksplit", C.c_int32), ("xcd_map", C.c_int32), ("wg_split", C.c_int32), ("idx_route", C.c_int32),
+                ("ksplit", C.c_int32), ("xcd_map", C.c_int32), ("wg_split", C.c_int32), ("idx_route", C.c_int32), ("tiles_per_wg", C.c_int32),
                 ("workspace_dev", C.c_void_p), ("workspace_bytes", C.c_size_t)]
 
 

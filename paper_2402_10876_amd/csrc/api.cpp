@@ -20,18 +20,19 @@ std::atomic<int> opt_depth{3};
 std::atomic<int> opt_waves{4};
 std::atomic<int> opt_ksplit{0};   // 0 = automatic, 1 = off, 2 = two K groups per workgroup
 std::atomic<int> opt_wg_split{0}; // 0 / 1 = off, 2..8 = workgroups per tile (needs a workspace)
+std::atomic<int> opt_tiles_per_wg{0};  // 0 = automatic, 1..8 = tiles a workgroup computes one after the other
 std::atomic<int> opt_idx_route{0};// kept-row lists: 0 = automatic, 1 = scalar loads, 2 = through LDS
 
 // What one launch runs with: the caller's tw_launch_opts, or the process defaults above
 // (tw_set_option) when there is none.  Read once per call, never shared between calls.
 struct Opts {
-  int tile_m, xcd_map, kernel, depth, waves, ksplit, wg_split, idx_route;
+  int tile_m, xcd_map, kernel, depth, waves, ksplit, wg_split, idx_route, tiles_per_wg;
   void* ws;
   size_t ws_bytes;
 };
 Opts default_opts() {
   return Opts{opt_tile_m.load(), opt_xcd_map.load(), opt_kernel.load(), opt_depth.load(), opt_waves.load(),
-              opt_ksplit.load(), opt_wg_split.load(), opt_idx_route.load(), nullptr, 0};
+              opt_ksplit.load(), opt_wg_split.load(), opt_idx_route.load(), opt_tiles_per_wg.load(), nullptr, 0};
 }
 bool opts_from(const tw_launch_opts* in, Opts* o) {
   *o = default_opts();
@@ -42,9 +43,11 @@ bool opts_from(const tw_launch_opts* in, Opts* o) {
   if (in->waves != 0 && in->waves != 4 && in->waves != 8) return false;
   if (in->xcd_map < -1 || in->xcd_map > 2 || in->wg_split < 0 || in->wg_split > 8) return false;
   if (in->idx_route < 0 || in->idx_route > 2) return false;
+  if (in->tiles_per_wg < 0 || in->tiles_per_wg > 8) return false;
   if (in->workspace_dev && ((uintptr_t)in->workspace_dev & 255)) return false;
   o->tile_m = in->tile_m; o->kernel = in->kernel; o->ksplit = in->ksplit; o->wg_split = in->wg_split;
   o->idx_route = in->idx_route;
+  o->tiles_per_wg = in->tiles_per_wg;
   o->depth = in->depth ? in->depth : 3;
   o->waves = in->waves ? in->waves : 4;
   o->xcd_map = in->xcd_map < 0 ? 1 : in->xcd_map;
@@ -387,6 +390,7 @@ static tw_status gemm_launch(const Opts& o, const void* A, int M, int lda, int l
   g.ew_last = h->img.ew_pairs.empty() ? 0 : (int)h->img.ew_pairs.size() - 1;
   g.n_tiles = h->n_tiles; g.K = h->K; g.N = h->N; g.xcd_map = o.xcd_map;
   g.wg_split = 1;
+  g.tiles_per_wg = 1;
   if (layout == TW_LAYOUT_MK) {
     hipError_t e = twg::launch_tw_mk(h->G, g, (hipStream_t)stream);
     if (e == hipErrorInvalidValue) return TW_ERR_UNSUPPORTED;
@@ -449,6 +453,8 @@ static tw_status gemm_launch(const Opts& o, const void* A, int M, int lda, int l
       if (v == twg::DMA_WAVES8) return wgs <= 256;       // alone on its CU: nothing else hides the round trip
       return wgs <= 384 || (wgs <= 512 && h->max_kp >= 2048);
     };
+    // several tiles per workgroup (plain TW, 4 waves, 64- or 128-row tiles of G = 128, 3 stages): on request
+    if (!tew && variant == twg::DMA_WAVES4 && o.tiles_per_wg > 1) g.tiles_per_wg = o.tiles_per_wg;
     e = launch_dma(h->G, tmu, depth, variant, lidx_for(variant, tmu), g, (hipStream_t)stream);
     if (e == hipErrorInvalidValue && variant != twg::DMA_WAVES4)
       e = launch_dma(h->G, tm, depth, twg::DMA_WAVES4, lidx_for(twg::DMA_WAVES4, tm), g, (hipStream_t)stream);
@@ -463,7 +469,7 @@ tw_status tw_launch_opts_init(tw_launch_opts* opts) {
   if (!opts) return TW_ERR_ARG;
   const Opts d = default_opts();
   opts->tile_m = d.tile_m; opts->kernel = d.kernel; opts->depth = d.depth; opts->waves = d.waves;
-  opts->ksplit = d.ksplit; opts->xcd_map = d.xcd_map; opts->wg_split = d.wg_split; opts->idx_route = d.idx_route;
+  opts->ksplit = d.ksplit; opts->xcd_map = d.xcd_map; opts->wg_split = d.wg_split; opts->idx_route = d.idx_route; opts->tiles_per_wg = d.tiles_per_wg;
   opts->workspace_dev = nullptr; opts->workspace_bytes = 0;
   return TW_OK;
 }
@@ -749,6 +755,7 @@ tw_status tw_set_option(const char* name, int value) {
   if (!std::strcmp(name, "kernel")) { opt_kernel.store(value); return TW_OK; }
   if (!std::strcmp(name, "waves")) { opt_waves.store(value == 8 ? 8 : 4); return TW_OK; }
   if (!std::strcmp(name, "ksplit")) { opt_ksplit.store(value); return TW_OK; }
+  if (!std::strcmp(name, "tiles_per_wg")) { opt_tiles_per_wg.store(value < 0 || value > 8 ? 0 : value); return TW_OK; }
   if (!std::strcmp(name, "idx_route")) { opt_idx_route.store(value < 0 || value > 2 ? 0 : value); return TW_OK; }
   if (!std::strcmp(name, "wg_split")) { opt_wg_split.store(value < 0 || value > 8 ? 0 : value); return TW_OK; }
   if (!std::strcmp(name, "tile_order")) { twg::longest_first.store(value != 0); return TW_OK; }

@@ -187,12 +187,19 @@ __device__ __forceinline__ void ew_fill_column(const GemmArgs& g, int which) {
 // tiles in split order (so the sum does not depend on who was last), runs the epilogue and puts
 // the counter back to zero.  Nobody waits for anybody: a workgroup that is not last is done.
 // LIDX: the kept-row list reaches the lanes through LDS (see fetch_rows) instead of scalar loads.
+// MULTI: a workgroup computes g.tiles_per_wg jobs one after the other (job ids blockIdx.x,
+// + gridDim.x, ..; gridDim.x is a multiple of 8, so every job keeps the workgroup's XCD).  The
+// next job's first copies are issued as soon as every wave has read its staged chunks: the
+// stores of the finished tile drain while the next one loads (the copies' waits count the
+// stores as older operations, which only makes them wait longer).  Per job the kernel
+// arguments are read again through a pointer the compiler cannot see through and the lane id is
+// made opaque, so that nothing derived from them stays in registers across jobs.
 template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KSPLIT = 1, bool EW = false,
-          bool SPLIT = false, bool LIDX = true>
-// (the TEW epilogue must not cost the 128 x 128 instance its third wave per SIMD: the second
+          bool SPLIT = false, bool LIDX = true, bool MULTI = false>
+// (the TEW epilogue and the loop over jobs must not cost an instance a wave per SIMD: the second
 // launch-bound asks the compiler to keep the register count within that occupancy)
-__global__ __launch_bounds__(NWAVES * 64, (EW && TM <= 128 && TN <= 128 && NWAVES == 4) ? 3 : 1)
-void tw_gemm_km_dma_kernel(GemmArgs g) {
+__global__ __launch_bounds__(NWAVES * 64, (MULTI && TM * TN <= 64 * 128) ? 4 : ((EW || MULTI) && TM <= 128 && TN <= 128 && NWAVES == 4) ? 3 : 1)
+void tw_gemm_km_dma_kernel(GemmArgs g_arg) {
   constexpr int NT = NWAVES * 64;          // threads of the workgroup
   constexpr int WPG = NWAVES / KSPLIT;     // waves per group
   constexpr int KSS = KS * KSPLIT;         // condensed rows per pipeline stage
@@ -227,14 +234,16 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
   constexpr int LDS_BYTES = IDX_OFF + ((DENSE || !LIDX) ? 0 : 2 * CH * 4);
   __shared__ __attribute__((aligned(1024))) char lds[LDS_BYTES];
 
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   static_assert(!SPLIT || (!DENSE && !EW && KSPLIT == 1), "the split across workgroups exists for plain TW");
+  static_assert(!MULTI || (!DENSE && !EW && !SPLIT && KSPLIT == 1), "several jobs per workgroup exist for plain TW");
+  auto job = [&](const GemmArgs& g, const int bid, const int tid) {
+  const int lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int S = SPLIT ? g.wg_split : 1;
   const int n_gemm = g.n_mtiles * g.n_tiles * S;
-  if ((int)blockIdx.x >= n_gemm) {
-    if constexpr (EW) ew_fill_column(g, blockIdx.x - n_gemm);
-    else zero_fill_column(g, blockIdx.x - n_gemm);
+  if (bid >= n_gemm) {
+    if constexpr (EW) ew_fill_column(g, bid - n_gemm);
+    else zero_fill_column(g, bid - n_gemm);
     return;
   }
   int mt, t;                             // t: launch position of the tile, then the tile itself
@@ -242,13 +251,13 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
   if constexpr (SPLIT) {
     // the workgroups of a pair are neighbours in the XCD's contiguous range of logical ids:
     // they run on the same XCD at about the same time, and their partial tiles meet in its L2
-    const int lid = g.xcd_map ? xcd_remap(blockIdx.x, n_gemm) : (int)blockIdx.x;
+    const int lid = g.xcd_map ? xcd_remap(bid, n_gemm) : bid;
     pair = lid / S;
     split = lid - pair * S;
     mt = pair / g.n_tiles;
     t = pair - mt * g.n_tiles;
   } else {
-    tile_of_workgroup(g, blockIdx.x, n_gemm, mt, t);
+    tile_of_workgroup(g, bid, n_gemm, mt, t);
   }
   const int m0 = mt * TM;
 
@@ -674,15 +683,37 @@ void tw_gemm_km_dma_kernel(GemmArgs g) {
       }
     }
   }
+  };   // job
+  if constexpr (!MULTI) {
+    job(g_arg, (int)blockIdx.x, (int)threadIdx.x);
+  } else {
+    typedef const GemmArgs __attribute__((address_space(4)))* karg_ptr;
+    const int total_jobs = g_arg.n_mtiles * g_arg.n_tiles + g_arg.n_zero;
+    for (int r = 0; r < g_arg.tiles_per_wg; ++r) {
+      const int bid = (int)blockIdx.x + r * (int)gridDim.x;
+      if (bid >= total_jobs) break;
+      if (r) {                 // every wave has read its chunks of the staging area: it may be overwritten
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        __syncthreads();
+      }
+      karg_ptr gp = (karg_ptr)__builtin_amdgcn_kernarg_segment_ptr();
+      asm volatile("" : "+s"(gp));
+      int tid = threadIdx.x;
+      asm volatile("" : "+v"(tid));
+      job(*(const GemmArgs*)gp, bid, tid);
+    }
+  }
 }
 
 template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, int KSPLIT = 1, bool EW = false,
-          bool SPLIT = false, bool LIDX = true>
+          bool SPLIT = false, bool LIDX = true, bool MULTI = false>
 static hipError_t launch(const GemmArgs& g, hipStream_t stream) {
-  const int grid = g.n_mtiles * g.n_tiles * (SPLIT ? g.wg_split : 1) + g.n_zero;
-  if (grid <= 0) return hipSuccess;
+  const int jobs = g.n_mtiles * g.n_tiles * (SPLIT ? g.wg_split : 1) + g.n_zero;
+  if (jobs <= 0) return hipSuccess;
+  const int tpw = MULTI && g.tiles_per_wg > 1 ? g.tiles_per_wg : 1;
+  const int grid = MULTI ? ((jobs + tpw - 1) / tpw + 7) / 8 * 8 : jobs;
   (void)hipGetLastError();   // an error left behind by an earlier call of this thread is not this launch's
-  hipLaunchKernelGGL((tw_gemm_km_dma_kernel<TM, TN, WAVES_M, D, DENSE, NWAVES, KSPLIT, EW, SPLIT, LIDX>), dim3(grid),
+  hipLaunchKernelGGL((tw_gemm_km_dma_kernel<TM, TN, WAVES_M, D, DENSE, NWAVES, KSPLIT, EW, SPLIT, LIDX, MULTI>), dim3(grid),
                      dim3(NWAVES * 64), 0, stream, g);
   return hipGetLastError();
 }
@@ -707,8 +738,13 @@ static hipError_t dispatch_ew(int G, int tm, int variant, GemmArgs& g, hipStream
 }
 
 // Both index routes of an instance (the dense baseline has no kept-row list: one instance).
-template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4>
+template <int TM, int TN, int WAVES_M, int D, bool DENSE, int NWAVES = 4, bool MULTI_OK = false>
 static hipError_t launch2(bool lidx, const GemmArgs& g, hipStream_t stream) {
+  if constexpr (MULTI_OK && !DENSE) {
+    if (g.tiles_per_wg > 1)
+      return lidx ? launch<TM, TN, WAVES_M, D, false, NWAVES, 1, false, false, true, true>(g, stream)
+                  : launch<TM, TN, WAVES_M, D, false, NWAVES, 1, false, false, false, true>(g, stream);
+  }
   if constexpr (DENSE) return launch<TM, TN, WAVES_M, D, true, NWAVES>(g, stream);
   else if (lidx) return launch<TM, TN, WAVES_M, D, false, NWAVES, 1, false, false, true>(g, stream);
   else return launch<TM, TN, WAVES_M, D, false, NWAVES, 1, false, false, false>(g, stream);
@@ -732,7 +768,9 @@ static hipError_t dispatch(int G, int tm, int depth, int variant, bool lidx, Gem
   }
 #define TWG_CASE(TM_, TN_, WM_, D_) \
   if (G == TN_ && tm == TM_ && depth == D_) return launch2<TM_, TN_, WM_, D_, DENSE>(lidx, g, stream);
-  TWG_CASE(64, 128, 1, 3) TWG_CASE(128, 128, 2, 3) TWG_CASE(256, 128, 2, 3)
+  if (G == 128 && tm == 64 && depth == 3) return launch2<64, 128, 1, 3, DENSE, 4, true>(lidx, g, stream);
+  if (G == 128 && tm == 128 && depth == 3) return launch2<128, 128, 2, 3, DENSE, 4, true>(lidx, g, stream);
+  TWG_CASE(256, 128, 2, 3)
   TWG_CASE(64, 128, 1, 4) TWG_CASE(128, 128, 2, 4) TWG_CASE(256, 128, 2, 4)
   TWG_CASE(128, 64, 2, 3) TWG_CASE(256, 64, 4, 3)
   TWG_CASE(128, 64, 2, 4) TWG_CASE(256, 64, 4, 4)

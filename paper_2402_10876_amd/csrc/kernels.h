@@ -35,6 +35,7 @@ struct GemmArgs {
   // K split across workgroups (1 = off): wg_split workgroups share one (M-tile, N-tile) pair on
   // disjoint ranges of the kept rows; fp32 partial tiles go to ws_partials, the workgroup that
   // arrives last at ws_counters[pair] adds them up in split order and runs the epilogue.
+  int tiles_per_wg;              // asynchronous TW kernel: jobs per workgroup (> 1: the instances that loop)
   int wg_split;
   float* ws_partials;            // [pair][split][tile] fp32
   int* ws_counters;              // one per pair; zero between launches (the last arriver resets it)

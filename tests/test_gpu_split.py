@@ -16,7 +16,7 @@ import workloads as wl
 def test_option_and_workspace_errors_need_no_device():
     p = tw.tw_pack_host(np.ones((64, 128), np.float16), np.ones((64, 128), np.uint8), 128, tw.PATTERN_TW)
     assert tw.tw_gemm_workspace_bytes(p, 100) >= 4096 + 2 * 8 * 64 * 128 * 4
-    for bad in (dict(tile_m=100), dict(depth=5), dict(waves=3), dict(wg_split=9), dict(kernel=3), dict(xcd_map=7),
+    for bad in (dict(tile_m=100), dict(depth=5), dict(waves=3), dict(wg_split=9), dict(tiles_per_wg=9), dict(kernel=3), dict(xcd_map=7),
                 dict(workspace_dev=0x1010, workspace_bytes=1 << 20)):
         o = tw.tw_launch_opts(**bad)
         with pytest.raises(tw.TwError) as ei:
@@ -142,6 +142,28 @@ def test_both_routes_of_the_kept_row_list(route, tile_m, waves, G, depth):
     p.free()
     assert_C_close(C, og.gemm_oracle(A, B, mask), og.abs_bound(A, B, mask))
     assert np.array_equal(raw.view(np.uint16)[:, :M], raw2.view(np.uint16)[:, :M])
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("tpw", [2, 3, 8])
+@pytest.mark.parametrize("tile_m,waves,ksplit,G,route", [(64, 4, 1, 128, 2), (64, 4, 1, 128, 1), (128, 4, 1, 128, 1), (128, 4, 1, 128, 2),
+                                                        (256, 8, 1, 128, 1), (128, 4, 2, 128, 2), (128, 4, 1, 64, 2)])
+def test_several_tiles_per_workgroup(tpw, tile_m, waves, ksplit, G, route):
+    """A workgroup that computes several tiles one after the other (pruned columns and the ragged
+    last M-tile among its jobs, fewer jobs than tpw x workgroups at the end) gives the bits of one
+    tile per workgroup, and those match the oracle; instances without the loop ignore the option."""
+    rng = np.random.default_rng(tpw * 1000 + tile_m + waves + ksplit + G)
+    M, K, N = 490, 330, 530
+    mask = random_tw_mask(rng, K, N, G, col_keep=0.8, row_keep=0.5)
+    A, B = wl.make_A(71, M, K), wl.make_B(71, K, N, 0.1)
+    print(f"case tiles_per_wg={tpw} tile_m={tile_m} waves={waves} ksplit={ksplit} G={G} idx_route={route}", flush=True)
+    p = tw.tw_pack(B, mask, G, tw.PATTERN_TW)
+    kw = dict(tile_m=tile_m, waves=waves, kernel=2, ksplit=ksplit, idx_route=route)
+    C, raw = _run_ex(p, A, N, tw.tw_launch_opts(tiles_per_wg=tpw, **kw))
+    C1, raw1 = _run_ex(p, A, N, tw.tw_launch_opts(tiles_per_wg=1, **kw))
+    p.free()
+    assert_C_close(C, og.gemm_oracle(A, B, mask), og.abs_bound(A, B, mask))
+    assert np.array_equal(raw.view(np.uint16), raw1.view(np.uint16))
 
 
 @pytest.mark.gpu
