@@ -472,9 +472,11 @@ def main():
     # just packed on the host, the GPU sat idle meanwhile, and its clocks take tens of milliseconds
     # of work to come back up; a short run (few steps, few warm-up steps) would time that ramp.
     t_w = time.perf_counter()
+    prewarm_steps = 0
     while time.perf_counter() - t_w < PREWARM_S:
         for i in range(args.sets):
             step(i)
+        prewarm_steps += args.sets
         torch.cuda.synchronize()
     for i in range(args.warmup):
         step(i)
@@ -600,7 +602,7 @@ def main():
                         f"by the byte roof on these shapes)")
 
     out = dict(metric=f"{args.pattern.upper()} sparse GEMM effective (dense-equivalent) TFLOP/s, BERT-base layer",
-               value=value, unit="TFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup,
+               value=value, unit="TFLOP/s", n_gpus=1, steps=args.steps, warmup=args.warmup, prewarm_steps=prewarm_steps,
                ms_per_step=sec_per_step * 1e3, higher_is_better=True, scaling="weak",
                vs_baseline=None, dtype="f16", data="synthetic",
                config=dict(workload=f"BERT-base linear layers as {args.pattern.upper()} GEMM (config {cfg}): M=4096, "
