@@ -202,3 +202,22 @@ def test_requantize_against_exact_rational_arithmetic():
             want = min(n, 128 if s < 0 else 127) * (-1 if s < 0 else 1)
         assert int(og.requantize_i8(np.array([s]), np.float32(sc))[0]) == want, (s, sc)
     assert got.shape == sums.shape
+
+
+def test_element_bar_below_the_normal_range_of_fp16():
+    """One product below 2^-14: the correctly rounded fp16 value is up to half a subnormal spacing
+    (2^-25) from the exact one, more than 4e-3 of it; the bar accepts that value, not the grid
+    points beyond its two nearest ones, and still wants exact zeros where nothing is kept."""
+    from tests.helpers import assert_C_close
+    a, b = np.float16(-0.0004715919494628906), np.float16(-0.0147247314453125)
+    A, B = np.array([[a]], np.float16), np.array([[b, b]], np.float16)
+    mask = np.array([[1, 0]], np.uint8)
+    ref, S = og.gemm_oracle(A, B, mask), og.abs_bound(A, B, mask)
+    exact = float(a) * float(b)
+    stored = float(np.float16(exact))
+    assert abs(stored - exact) > 4e-3 * abs(exact) and abs(stored) < 2.0 ** -14
+    assert_C_close(np.array([[stored, 0.0]]), ref, S)
+    away = np.sign(stored - exact) * 2.0 ** -24            # one spacing further from the exact value
+    for wrong in ([[stored + away, 0.0]], [[stored - 2 * away, 0.0]], [[stored, 2.0 ** -24]]):
+        with pytest.raises(AssertionError):
+            assert_C_close(np.array(wrong), ref, S)
