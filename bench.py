@@ -26,7 +26,7 @@ Prints ONE JSON line: dense-equivalent TFLOP/s of the whole step, plus
                 BERT-large FFN sparsity sweep, the VGG-16 im2col GEMMs): time, our dense
                 kernel's time, binding roof and the fraction of it (outside the timed region);
   cpu_baseline  the fp64 oracle timed on the host cores.
-`--extra cube,imbalance,tew,i8,conv` adds opt-in sweeps (the 4096^3 sparsity sweep, uneven
+`--extra cube,imbalance,tew,i8,conv,options` adds opt-in sweeps (the 4096^3 sparsity sweep, uneven
 tiles, TEW, int8, convolutions without a materialised img2col matrix) under `extra`.
 `--calibrate` runs the calibration kernels alone (the command the rocprofv3 summary in
 profiles/ was taken with).
@@ -199,7 +199,7 @@ def extra_rows(tw, wl, torch, dev, stream, skip_cfg, reps=24, sets=24):
 
 
 def extra_sweeps(tw, wl, torch, dev, stream, which, reps=24, sets=6):
-    """Opt-in measurements beyond the configured workloads (`--extra cube,imbalance,tew,i8,conv`):
+    """Opt-in measurements beyond the configured workloads (`--extra cube,imbalance,tew,i8,conv`; `options` is handled in main, on the step's own buffers):
     the 4096^3 sparsity sweep of Section VI-B (TVW at 50 % is plain 2:4), uneven tiles from one
     magnitude threshold over all tile rows (Section V "load imbalance") launched longest first
     and in column order, TEW at 75 % with delta restored elements (Section VI, impact of delta),
@@ -388,7 +388,7 @@ def main():
     ap.add_argument("--no-rows", action="store_true", help="skip the rows of the other configured workloads")
     ap.add_argument("--no-calibration", action="store_true")
     ap.add_argument("--extra", default="", help="comma list of opt-in sweeps, printed under `extra`: "
-                                                "cube, imbalance, tew, i8, conv (each takes 10-60 s)")
+                                                "cube, imbalance, tew, i8, conv, options (each takes 10-60 s)")
     ap.add_argument("--calibrate", action="store_true", help="run the calibration kernels only and print their rates")
     ap.add_argument("--separate-qkv", action="store_true",
                     help="time the step with Q, K and V as three launches (6 launches per step)")
@@ -563,6 +563,32 @@ def main():
                  value=dense_flops_step / sec_other / 1e12)
     detail["separate_qkv" if grouped else "grouped_qkv"] = other
 
+    options_sweep = None
+    if "options" in set(args.extra.split(",")):
+        # the step itself with one process-wide launch option forced at a time (the value
+        # listed first is the default), values interleaved over 7 rounds of `steps` steps
+        plan = [("idx_route", (0, 1, 2)), ("xcd_map", (1, 2, 0)), ("depth", (3, 4)), ("tile_m", (0, 64, 128, 256)),
+                ("ksplit", (0, 1, 2)), ("waves", (4, 8))]
+        res = {}
+        for name, values in plan:
+            t = {v: [] for v in values}
+            for _ in range(7):
+                for v in values:
+                    tw.tw_set_option(name, v)
+                    for i in range(args.warmup):
+                        step(i)
+                    torch.cuda.synchronize()
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    for i in range(args.steps):
+                        step(i)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    t[v].append(e0.elapsed_time(e1) / args.steps * 1e3)
+            tw.tw_set_option(name, values[0])
+            res[name] = {str(v): round(float(np.median(t[v])), 2) for v in values}
+        options_sweep = dict(us_per_step=res, note="median of 7 interleaved rounds; first value = default")
+
     # release the step's buffers before the other workloads allocate theirs
     for ops in sets_grp:
         ops[0][1].free()
@@ -623,7 +649,10 @@ def main():
     if rows is not None:
         out["rows"] = rows
     if args.extra:
-        out["extra"] = extra_sweeps(tw, wl, torch, dev, stream, set(args.extra.split(",")))
+        which_extra = set(args.extra.split(","))
+        out["extra"] = extra_sweeps(tw, wl, torch, dev, stream, which_extra - {"options"})
+        if options_sweep is not None:
+            out["extra"]["options"] = options_sweep
 
     if not args.no_cpu_baseline:
         from oracle import gemm as og
